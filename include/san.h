@@ -1,0 +1,188 @@
+/*
+ * libsan -- shared-attention (SAN) Transformer decoding on one MI355X (gfx950).
+ *
+ * The library runs the cached auto-regressive Transformer decoder step in which
+ * the decoder layers are grouped into blocks by a sharing policy {pi_1..pi_N}
+ * (Sec. 3.3 of "Sharing Attention Weights for Fast Transformer"): inside a
+ * block only the first layer computes the attention weights
+ * S = Softmax(Q K^T / sqrt(d_k)) (Eq. 1, Eq. 3); the other layers of the block
+ * reuse them (Eq. 4, self-attention, each layer with its own V) or reuse the
+ * attended state A = S V itself (Eq. 5, encoder-decoder attention).
+ *
+ * General conventions
+ *   - Plain C ABI.  Every pointer parameter says whether it is HOST or DEVICE
+ *     memory.  DEVICE buffers are owned by the caller, must live on the device
+ *     that was current at san_init and must stay valid until the work queued by
+ *     the call has finished.
+ *   - All device work is queued on the stream given to san_init and is
+ *     asynchronous with respect to the host; no call synchronises the device
+ *     except san_init and san_free.  Calls on one context must not overlap.
+ *   - Every function returns a san_status (0 = ok) and never aborts; a text for
+ *     the last failure of a context is available from san_last_error.
+ *   - Rows: decoder row r = sentence * beam + beam_index, rows = batch * beam.
+ *   - Linear maps are stored [out_features][in_features], y = x W^T + b.
+ */
+#ifndef SAN_H
+#define SAN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct san_ctx san_ctx; /* opaque, owned by the library */
+
+#if defined(__GNUC__)
+#define SAN_API __attribute__((visibility("default")))
+#else
+#define SAN_API
+#endif
+
+typedef enum {
+  SAN_OK = 0,
+  SAN_EINVAL = 1,    /* bad argument or unsupported configuration           */
+  SAN_EPOLICY = 2,   /* policy does not partition the decoder layers        */
+  SAN_ESTATE = 3,    /* call out of order (e.g. decode before encode)       */
+  SAN_ECAPACITY = 4, /* exceeds max_batch / max_src_len / max_tgt_len       */
+  SAN_EHIP = 5,      /* a HIP runtime call failed                           */
+  SAN_ENOMEM = 6     /* device or host allocation failed                    */
+} san_status;
+
+enum { SAN_F32 = 0, SAN_BF16 = 1 };          /* storage type of weights, activations, caches;
+                                                accumulation, softmax and LayerNorm statistics are fp32 */
+enum { SAN_SELF_DOT = 0, SAN_SELF_AAN = 1 }; /* decoder self sub-layer: dot-product attention (Eq. 1-2)
+                                                or the average attention network (Tab. 6 rows "+AAN") */
+enum { SAN_SHARE_A = 0, SAN_SHARE_S = 1 };   /* enc-dec blocks: reuse A = S V (Eq. 5) or reuse S with a
+                                                per-layer V (Tab. 4, row "shared V: no")              */
+
+/* which tensor san_debug_get copies out */
+enum { SAN_DBG_S_SELF = 0, SAN_DBG_A_SELF = 1, SAN_DBG_S_CTX = 2, SAN_DBG_A_CTX = 3, SAN_DBG_HIDDEN = 4 };
+
+typedef struct {
+  int32_t n_enc_layers, n_dec_layers;
+  int32_t d_model, n_heads, d_ff, vocab; /* d_model % 64 == 0, d_ff % 64 == 0,
+                                            d_model / n_heads in {16,32,64,128}        */
+  int32_t max_batch;   /* sentences per san_encode call                               */
+  int32_t beam;        /* hypotheses per sentence (1 = greedy), 1..32                 */
+  int32_t max_src_len; /* source positions per sentence                              */
+  int32_t max_tgt_len; /* decode steps per sentence (self cache capacity)            */
+  int32_t dtype;       /* SAN_F32 | SAN_BF16                                          */
+  int32_t self_kind;   /* SAN_SELF_DOT | SAN_SELF_AAN                                 */
+  int32_t encdec_share;/* SAN_SHARE_A | SAN_SHARE_S                                   */
+  int32_t use_cache;   /* 1: key/value cache (Sec. 4.1 baseline); 0: recompute every
+                          target position at every step (Tab. 6 row "-Cache")         */
+  int32_t pad_id, bos_id, eos_id; /* eos_id < 0 switches EOS handling off in san_topk */
+  int32_t debug;       /* 1: keep per-layer S / A / hidden copies for san_debug_get   */
+  float ln_eps;        /* LayerNorm epsilon                                           */
+} san_config;
+
+/* Sharing policy (Sec. 3.3): block sizes bottom-up; each list must sum to
+ * n_dec_layers and hold only sizes >= 1.  With SAN_SELF_AAN self_pi is ignored. */
+typedef struct {
+  int32_t n_self;
+  const int32_t* self_pi; /* HOST */
+  int32_t n_encdec;
+  const int32_t* encdec_pi; /* HOST */
+} san_policy;
+
+/* Size in bytes of the weight blob san_init expects for this configuration
+ * (0 if the configuration is invalid).  Blob = these tensors back to back, in
+ * the storage type `dtype` (bf16 = upper 16 bits of the fp32 pattern):
+ *   src_emb[V][d], tgt_emb[V][d],
+ *   per encoder layer: attn {wq,bq,wk,bk,wv,bv,wo,bo}, ln1 {g,b},
+ *                      ffn {w1[F][d],b1,w2[d][F],b2}, ln2 {g,b}
+ *   per decoder layer: self {wq,bq,wk,bk,wv,bv,wo,bo}          (SAN_SELF_DOT)
+ *                      or aan {w1,b1,w2,b2,wg[2d][2d],bg[2d]}  (SAN_SELF_AAN),
+ *                      ln1 {g,b}, ctx {wq,bq,wk,bk,wv,bv,wo,bo}, ln2 {g,b},
+ *                      ffn {w1,b1,w2,b2}, ln3 {g,b}
+ *   w_out[V][d]
+ * The blob is always the full standard-Transformer tensor set; the tensors a
+ * policy makes unnecessary (Q/K projections of non-head self layers, Q/K/V of
+ * non-head enc-dec layers; Sec. 3.2) are simply not uploaded. */
+SAN_API size_t san_weight_bytes(const san_config* cfg);
+
+/* Build a context: validate cfg + policy, upload the needed weights from the
+ * HOST blob, allocate caches and workspaces on the current device.
+ * hip_stream: a hipStream_t (may be NULL = default stream) on which every later
+ * call queues its work.  *out receives the context (NULL on failure).
+ * Errors: SAN_EINVAL (shape/dtype/blob size), SAN_EPOLICY, SAN_ENOMEM, SAN_EHIP. */
+SAN_API int san_init(const san_config* cfg, const void* weights_host, size_t weight_bytes,
+             const san_policy* policy, void* hip_stream, san_ctx** out);
+
+/* Run the encoder stack on a padded source batch and precompute the
+ * encoder-decoder keys/values of every decoder layer that needs them (block
+ * heads; with SAN_SHARE_S also each follower's V).  Keys beyond src_len[b] are
+ * never attended; src_len[b] = 0 gives a zero context vector.  Resets the
+ * decoder state (step 0, empty cache).
+ *   src_ids_dev DEVICE int32 [batch][max_src], src_len_dev DEVICE int32 [batch].
+ * Errors: SAN_EINVAL (null, batch < 1, max_src < 1), SAN_ECAPACITY. */
+SAN_API int san_encode(san_ctx* ctx, const int32_t* src_ids_dev, const int32_t* src_len_dev,
+               int32_t batch, int32_t max_src);
+
+/* Rewind the decoder to step 0 for the batch already encoded (keeps the
+ * encoder-decoder keys/values).  Errors: SAN_ESTATE before san_encode. */
+SAN_API int san_rewind(san_ctx* ctx);
+
+/* One auto-regressive decoder step (Sec. 1: one target word at a time) for all
+ * batch*beam rows: embeds tokens at the current position, runs every decoder
+ * layer under the sharing policy, appends this position's keys/values to the
+ * cache and writes the output-layer logits.
+ *   tokens_dev DEVICE int32 [batch*beam] (ids outside [0,vocab) are clamped),
+ *   logits_dev DEVICE fp32 [batch*beam][vocab].
+ * Errors: SAN_ESTATE (no san_encode yet), SAN_ECAPACITY (step == max_tgt_len). */
+SAN_API int san_decode_step(san_ctx* ctx, const int32_t* tokens_dev, float* logits_dev);
+
+/* Beam step (Sec. 4.1: beam search over a batch).  Candidate (row r, word v)
+ * scores cum_score[r] + log_softmax(logits[r])[v]; per sentence the k best of
+ * the beam*vocab candidates are written in order of decreasing score, ties by
+ * the lower flat index beam_index*vocab + v.  When eos_id >= 0, a row whose
+ * last decoded input token was eos_id can only be extended by eos_id at cost 0.
+ *   logits_dev DEVICE fp32 [batch*beam][vocab], cum_score_dev DEVICE fp32
+ *   [batch*beam] (-inf marks a dead row), 1 <= k <= min(32, vocab);
+ *   out_token_dev / out_parent_dev DEVICE int32 [batch][k] (parent = global row
+ *   index), out_score_dev DEVICE fp32 [batch][k].
+ * Errors: SAN_ESTATE, SAN_EINVAL. */
+SAN_API int san_topk(san_ctx* ctx, const float* logits_dev, const float* cum_score_dev, int32_t k,
+             int32_t* out_token_dev, int32_t* out_parent_dev, float* out_score_dev);
+
+/* After a beam step: row r continues the hypothesis that was row parent[r].
+ * Every per-row decoder state (self-attention key/value history, AAN running
+ * sums, un-cached token history) follows; encoder-decoder keys/values are per
+ * sentence and do not move.  parent[r] must lie in r's own sentence
+ * (rows sentence*beam .. sentence*beam+beam-1); other values leave row r as is.
+ *   parent_idx_dev DEVICE int32 [batch*beam].
+ * Errors: SAN_ESTATE, SAN_EINVAL. */
+SAN_API int san_beam_reorder(san_ctx* ctx, const int32_t* parent_idx_dev);
+
+/* Copy a tensor of the most recent decode step to dst_dev (DEVICE, cap bytes).
+ * Needs cfg.debug = 1 and use_cache = 1.
+ *   SAN_DBG_S_SELF: fp32 [rows][heads][n], n = steps done (weights the layer used)
+ *   SAN_DBG_S_CTX : fp32 [rows][heads][max_src] (entries >= src_len are 0)
+ *   SAN_DBG_A_SELF / A_CTX / HIDDEN: fp32 [rows][d_model]
+ * Errors: SAN_ESTATE, SAN_EINVAL (layer, what, cap too small). */
+SAN_API int san_debug_get(san_ctx* ctx, int32_t what, int32_t layer, void* dst_dev, size_t cap);
+
+/* Number of decode steps done since the last san_encode / san_rewind (-1 if
+ * nothing is encoded). */
+SAN_API int32_t san_step(const san_ctx* ctx);
+
+/* Device bytes held by the context (weights uploaded / caches+workspaces):
+ * shows the parameter and cache saving of a policy (Sec. 3.2). */
+SAN_API size_t san_device_bytes(const san_ctx* ctx, int32_t which /* 0 = weights, 1 = state */);
+
+/* Number of kernels the last san_decode_step queued. */
+SAN_API int32_t san_last_launch_count(const san_ctx* ctx);
+
+/* Message of the last failed call on this context ("" if none).  With ctx ==
+ * NULL: message of the last failed san_init on this thread. */
+SAN_API const char* san_last_error(const san_ctx* ctx);
+
+/* Waits for the stream, frees everything san_init allocated. NULL is allowed. */
+SAN_API void san_free(san_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAN_H */

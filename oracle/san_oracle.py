@@ -371,9 +371,10 @@ class SanOracle:
         par = np.zeros((self.batch, k), dtype=np.int32)
         sc = np.zeros((self.batch, k), dtype=self.dt)
         margin = np.zeros(self.batch, dtype=self.dt)
-        flat_idx = np.arange(beam * V)
         for b in range(self.batch):
-            order = np.lexsort((flat_idx, -cand[b]))      # score desc, then index asc
+            # stable sort on the negated score: score descending, equal scores
+            # stay in ascending flat-index order
+            order = np.argsort(-cand[b], kind="stable")
             top = order[:k]
             tok[b] = top % V
             par[b] = b * beam + top // V

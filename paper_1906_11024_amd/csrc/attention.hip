@@ -1,0 +1,227 @@
+// Decode-time attention for the shared-attention decoder (Eq. 1-5).
+//
+// The work is HBM-bound (4 flops per key/value element pair), so the kernel is a
+// streaming one: a 64-lane wave owns one head of one key/value stream; LPP lanes
+// cover the dh elements of one position with 16-byte loads and 64/LPP positions
+// are in flight per load instruction, several instructions deep.  Scores live in
+// LDS (one row per query), the softmax max/sum are wave shuffles, and the
+// normalised weights are written out once per sharing block so that the other
+// layers of the block (apply mode) only stream their own V.
+#include "common.h"
+#include "kernels.h"
+
+namespace san {
+
+constexpr int kWavesPerBlock = 4;
+constexpr int kUnroll = 4;
+
+template <typename T, int LPP, int NQ>
+__global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
+  constexpr int EPL = Frag<T>::N;       // elements per lane per position
+  constexpr int PPL = kWave / LPP;      // positions per load instruction
+  constexpr int DH = LPP * EPL;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+  const int c = lane % LPP, g = lane / LPP;
+  float* sc = reinterpret_cast<float*>(smem) + (size_t)wid * NQ * p.lmax;                 // [NQ][lmax]
+  int* slots = reinterpret_cast<int*>(smem + sizeof(float) * kWavesPerBlock * NQ * p.lmax);  // [lmax], self mode
+
+  const int nhg = (p.H + kWavesPerBlock - 1) / kWavesPerBlock;
+  const int hg = blockIdx.x % nhg;
+  int rest = blockIdx.x / nhg;
+  const int h = hg * kWavesPerBlock + wid;
+  const bool head_ok = h < p.H;
+
+  // ---- which stream, which queries, how many keys
+  int n = 0;                 // keys this wave walks
+  int qrow[NQ], nk[NQ];      // query row (-1: none) and number of keys it may see
+  long long slot_base = 0;
+  if (p.self_mode) {
+    const int r = rest;
+    n = *p.t_dev + 1;
+    n = min(n, p.lmax);
+    qrow[0] = r;
+    nk[0] = n;
+#pragma unroll
+    for (int i = 1; i < NQ; ++i) { qrow[i] = -1; nk[i] = 0; }
+    // slot of key j: position-major cache, row taken from the ancestry table
+    for (int j = threadIdx.x; j < n; j += blockDim.x) slots[j] = j * p.rows + p.anc[(size_t)r * p.ld_anc + j];
+    __syncthreads();
+  } else {
+    const int nqb = (p.rpg + NQ - 1) / NQ;
+    const int qb = rest % nqb;
+    const int grp = rest / nqb;
+    slot_base = (long long)grp * p.slot_stride;
+    const int nfull = p.len ? max(0, min(p.len[grp], p.lmax)) : p.n_fixed;
+    n = 0;
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+      const int li = qb * NQ + i;
+      if (li < p.rpg) {
+        qrow[i] = grp * p.rpg + li;
+        nk[i] = p.causal ? min(nfull, li % p.causal + 1) : nfull;
+        n = max(n, nk[i]);
+      } else {
+        qrow[i] = -1;
+        nk[i] = 0;
+      }
+    }
+  }
+  if (!head_ok) return;  // no block-wide barrier below this point
+
+  const T* Kp = reinterpret_cast<const T*>(p.K);
+  const T* Vp = reinterpret_cast<const T*>(p.V);
+  const T* Qp = reinterpret_cast<const T*>(p.q);
+  T* Op = reinterpret_cast<T*>(p.out);
+  const int col = h * DH + c * EPL;
+
+  auto slot_of = [&](int j) -> long long { return p.self_mode ? (long long)slots[j] : slot_base + j; };
+
+  if (!p.apply) {
+    // ---- pass 1: scores (Eq. 1, numerator)
+    float qf[NQ][EPL];
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+      if (qrow[i] >= 0) {
+        load_frag(Qp + (size_t)qrow[i] * p.ldq + col, qf[i]);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) qf[i][e] *= p.scale;
+      } else {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) qf[i][e] = 0.f;
+      }
+    }
+    for (int j0 = 0; j0 < n; j0 += PPL * kUnroll) {
+      float kf[kUnroll][EPL];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int j = min(j0 + u * PPL + g, n - 1);
+        load_frag(Kp + slot_of(j) * p.ldk + col, kf[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int j = j0 + u * PPL + g;
+#pragma unroll
+        for (int i = 0; i < NQ; ++i) {
+          float dot = 0.f;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) dot = fmaf(qf[i][e], kf[u][e], dot);
+          dot = xor_sum<1, LPP>(dot);
+          if (c == 0 && j < n) sc[i * p.lmax + j] = (j < nk[i]) ? dot : -INFINITY;
+        }
+      }
+    }
+    // ---- softmax over key positions, one query at a time
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+      if (qrow[i] < 0) continue;
+      float* row = sc + i * p.lmax;
+      float m = -INFINITY;
+      for (int j = lane; j < n; j += kWave) m = fmaxf(m, row[j]);
+      m = wave_max(m);
+      float s = 0.f;
+      for (int j = lane; j < n; j += kWave) {
+        const float e = (row[j] == -INFINITY) ? 0.f : expf(row[j] - m);
+        row[j] = e;
+        s += e;
+      }
+      s = wave_sum(s);
+      const float inv = s > 0.f ? 1.0f / s : 0.f;
+      float* Sg = p.S_buf ? p.S_buf + ((size_t)qrow[i] * p.H + h) * p.ldS : nullptr;
+      for (int j = lane; j < n; j += kWave) {
+        const float w = row[j] * inv;
+        row[j] = w;
+        if (p.emit) Sg[j] = w;
+      }
+      if (p.emit && p.zero_tail)
+        for (int j = n + lane; j < p.ldS; j += kWave) Sg[j] = 0.f;
+    }
+  } else {
+    // ---- shared weights: S^{m+i} = S^m (Eq. 4)
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+      if (qrow[i] < 0) continue;
+      const float* Sg = p.S_buf + ((size_t)qrow[i] * p.H + h) * p.ldS;
+      for (int j = lane; j < n; j += kWave) sc[i * p.lmax + j] = (j < nk[i]) ? Sg[j] : 0.f;
+    }
+  }
+  // LDS rows are private to the wave; make the writes above visible to all its lanes
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+  // ---- pass 2: A = S V (Eq. 2)
+  float acc[NQ][EPL];
+#pragma unroll
+  for (int i = 0; i < NQ; ++i)
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[i][e] = 0.f;
+  for (int j0 = 0; j0 < n; j0 += PPL * kUnroll) {
+    float vf[kUnroll][EPL];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int j = min(j0 + u * PPL + g, n - 1);
+      load_frag(Vp + slot_of(j) * p.ldv + col, vf[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int j = j0 + u * PPL + g;
+      if (j < n) {
+#pragma unroll
+        for (int i = 0; i < NQ; ++i) {
+          const float w = sc[i * p.lmax + j];
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) acc[i][e] = fmaf(w, vf[u][e], acc[i][e]);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[i][e] = xor_sum<LPP, kWave>(acc[i][e]);
+    if (g == 0 && qrow[i] >= 0) store_frag(Op + (size_t)qrow[i] * p.ldo + col, acc[i]);
+  }
+}
+
+template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p, hipStream_t stream) {
+  const int nhg = (p.H + kWavesPerBlock - 1) / kWavesPerBlock;
+  if (p.self_mode) {
+    const size_t smem = sizeof(float) * kWavesPerBlock * p.lmax + sizeof(int) * p.lmax;
+    dim3 grid((unsigned)(p.rows * nhg));
+    hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(256), smem, stream, p);
+  } else if (p.rpg == 1) {
+    const size_t smem = sizeof(float) * kWavesPerBlock * p.lmax;
+    dim3 grid((unsigned)(p.groups * nhg));
+    hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(256), smem, stream, p);
+  } else {
+    const int nqb = (p.rpg + 3) / 4;
+    const size_t smem = sizeof(float) * kWavesPerBlock * 4 * p.lmax;
+    dim3 grid((unsigned)((size_t)p.groups * nqb * nhg));
+    hipLaunchKernelGGL((attention_kernel<T, LPP, 4>), grid, dim3(256), smem, stream, p);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_attention(int dtype, const AttnParams& p, hipStream_t stream) {
+  if (p.rows <= 0 || p.lmax <= 0) return hipSuccess;
+  const int lpp = dtype == 1 ? p.dh / 8 : p.dh / 4;
+  if (dtype == 1) {
+    switch (lpp) {
+      case 2: return launch_lpp<bf16_t, 2>(p, stream);
+      case 4: return launch_lpp<bf16_t, 4>(p, stream);
+      case 8: return launch_lpp<bf16_t, 8>(p, stream);
+      case 16: return launch_lpp<bf16_t, 16>(p, stream);
+      default: return hipErrorInvalidValue;
+    }
+  }
+  switch (lpp) {
+    case 4: return launch_lpp<float, 4>(p, stream);
+    case 8: return launch_lpp<float, 8>(p, stream);
+    case 16: return launch_lpp<float, 16>(p, stream);
+    case 32: return launch_lpp<float, 32>(p, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace san

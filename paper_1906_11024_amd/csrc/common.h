@@ -1,0 +1,100 @@
+// Device-side helpers shared by the gfx950 kernels: storage types, 16-byte
+// fragment access, wavefront (64-lane) reductions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace san {
+
+constexpr int kWave = 64;
+
+// bf16 storage: the upper 16 bits of an fp32 pattern.
+struct bf16_t {
+  uint16_t v;
+};
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x.v) << 16); }
+
+// round-to-nearest-even fp32 -> bf16 (NaN kept quiet)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ T from_f32(float f);
+template <> __device__ __forceinline__ float from_f32<float>(float f) { return f; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float f) {
+  bf16_t r;
+  r.v = f32_to_bf16_bits(f);
+  return r;
+}
+
+// Elements of T in one 16-byte fragment.
+template <typename T> struct Frag;
+template <> struct Frag<float> {
+  static constexpr int N = 4;
+};
+template <> struct Frag<bf16_t> {
+  static constexpr int N = 8;
+};
+
+// Load a 16-byte fragment (p must be 16-byte aligned) and widen to fp32.
+__device__ __forceinline__ void load_frag(const float* p, float (&out)[4]) {
+  const float4 v = *reinterpret_cast<const float4*>(p);
+  out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+}
+__device__ __forceinline__ void load_frag(const bf16_t* p, float (&out)[8]) {
+  const uint4 v = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    out[2 * i] = __uint_as_float(w[i] << 16);
+    out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ void store_frag(float* p, const float (&in)[4]) {
+  *reinterpret_cast<float4*>(p) = make_float4(in[0], in[1], in[2], in[3]);
+}
+__device__ __forceinline__ void store_frag(bf16_t* p, const float (&in)[8]) {
+  uint4 v;
+  uint32_t w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    w[i] = (uint32_t)f32_to_bf16_bits(in[2 * i]) | ((uint32_t)f32_to_bf16_bits(in[2 * i + 1]) << 16);
+  v.x = w[0]; v.y = w[1]; v.z = w[2]; v.w = w[3];
+  *reinterpret_cast<uint4*>(p) = v;
+}
+
+// 4 consecutive elements (used by row-wise kernels; p aligned to 4 elements).
+__device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 load4(const bf16_t* p) {
+  const uint2 v = *reinterpret_cast<const uint2*>(p);
+  return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
+                     __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
+}
+__device__ __forceinline__ void store4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void store4(bf16_t* p, float4 v) {
+  uint2 o;
+  o.x = (uint32_t)f32_to_bf16_bits(v.x) | ((uint32_t)f32_to_bf16_bits(v.y) << 16);
+  o.y = (uint32_t)f32_to_bf16_bits(v.z) | ((uint32_t)f32_to_bf16_bits(v.w) << 16);
+  *reinterpret_cast<uint2*>(p) = o;
+}
+
+// Reductions over the lanes whose ids differ only in the bits of `mask_bits`
+// (a contiguous run of xor strides from `lo` up to, not including, `hi`).
+template <int LO, int HI> __device__ __forceinline__ float xor_sum(float v) {
+#pragma unroll
+  for (int s = LO; s < HI; s <<= 1) v += __shfl_xor(v, s, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) { return xor_sum<1, kWave>(v); }
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int s = 1; s < kWave; s <<= 1) v = fmaxf(v, __shfl_xor(v, s, kWave));
+  return v;
+}
+
+}  // namespace san

@@ -1,0 +1,99 @@
+// Host-side launchers of the gfx950 kernels.  Every launcher only queues work on
+// `stream`; `dtype` selects the storage type of T-typed buffers (0 fp32, 1 bf16).
+// Launchers return hipSuccess or the launch error.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace san {
+
+// ---------------------------------------------------------------- projections
+// out[m][n] = sum_k A[m][k] * W[n][k] (+ bias[n]) (ReLU) on MFMA tiles.
+// The N columns are cut into segments of seg_w columns; segment s goes to
+// out[s] + (*t_dev) * tstride[s] + m * ldo[s] + (n - s*seg_w).
+//   out_kind 0: store as T;  1: store fp32;  2: fp32 split-K partials
+//   [ksplit][M][N] at out[0] (no bias, no ReLU; the consumer reduces them).
+struct GemmParams {
+  const void* A; int lda;
+  const void* W;              // [N][K]
+  const void* bias;           // T [N] or nullptr
+  void* out[3]; int ldo[3]; long long tstride[3];
+  int seg_w;
+  const int* t_dev;           // nullptr: no step offset
+  int M, N, K;                // K % (128 / sizeof(T)) == 0
+  int relu, out_kind, ksplit;
+};
+hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream);
+// tile edge (rows of A per block) the launcher would pick; used to size split-K
+int gemm_pick_ksplit(int M, int N, int K, int dtype);
+
+// ------------------------------------------------------------------ attention
+// One kernel for every attention in the model.  A wave owns one head of one
+// key/value stream and NQ queries that share the stream.
+//  self (cached decoding): stream = history of decoder row r, key j lives in
+//     slot j*rows + anc[r*ld_anc + j], n = *t_dev + 1 keys, one query.
+//  grouped: stream = group g (a sentence's encoder memory, or the positions of
+//     one hypothesis when nothing is cached), key j in slot g*slot_stride + j;
+//     the group's rpg query rows are g*rpg .. g*rpg+rpg-1; n = len[g] or, when
+//     causal, query i (its index inside the group modulo causal_mod) sees
+//     keys 0..i.
+//  apply = 0: S = softmax(q K^T * scale) (Eq. 1), out = S V (Eq. 2); S is also
+//     written to S_buf when emit != 0.   apply = 1: S is read from S_buf (the
+//     block head's weights, Eq. 4) and only out = S V runs.
+struct AttnParams {
+  const void* q; int ldq;           // T [rows][ldq]
+  const void* K; long long ldk;     // T, slot stride in elements (unused when apply)
+  const void* V; long long ldv;
+  float* S_buf; int ldS;            // fp32 [rows][H][ldS]
+  void* out; int ldo;               // T [rows][ldo]
+  const int* anc; int ld_anc;       // self mode
+  const int* t_dev;                 // self mode
+  const int* len;                   // grouped, non-causal: keys per group (nullptr: n_fixed)
+  int n_fixed;
+  int self_mode, rows, groups, rpg, slot_stride, causal;
+  int H, dh;
+  int apply, emit, zero_tail;
+  int lmax;                         // capacity of one score row (>= any n)
+  float scale;
+};
+hipError_t launch_attention(int dtype, const AttnParams& p, hipStream_t stream);
+
+// ------------------------------------------------------------------ row-wise
+// x[r] = emb[clamp(tok)] * scale + pe[pos]; row r = hyp*rpg + i reads token
+// tok[hyp*tok_stride + i]; pos = *t_dev when t_dev != nullptr, else i.
+hipError_t launch_embed(int dtype, const int* tok, int tok_stride, int rpg, const void* emb, const float* pe,
+                        const int* t_dev, void* x, int rows, int d, int vocab, float scale, hipStream_t stream);
+
+// out[m] = LayerNorm(sum_s part[s][m] + bias + res[m]) * g + b  (row-wise over n)
+hipError_t launch_ln_reduce(int dtype, const float* part, int nsplit, const void* bias, const void* res, int ldr,
+                            const void* gamma, const void* beta, void* out, int ldo, float* out_f32, int M, int n,
+                            float eps, hipStream_t stream);
+
+// start of a decode step: last_tok[r] = tok[r]; anc[r][t] = r; hist[r][t] = tok[r]
+hipError_t launch_step_begin(const int* tok, int* last_tok, int* anc, int* hist, int ld, const int* t_dev, int rows,
+                             hipStream_t stream);
+hipError_t launch_bump(int* t_dev, hipStream_t stream);
+hipError_t launch_to_f32(int dtype, const void* src, int lds, float* dst, int rows, int cols, hipStream_t stream);
+// dst[r][h][0..n) = src[r][h][0..n) with source row stride ldS
+hipError_t launch_compact_S(const float* src, int ldS, float* dst, int rows_h, int n, hipStream_t stream);
+
+// ------------------------------------------------------------------- AAN layer
+hipError_t launch_aan_pre(int dtype, float* sum, const void* x, void* avg, void* cat, const int* t_dev, int rows,
+                          int d, hipStream_t stream);
+// x = LN(x + sigmoid(zi) * x + sigmoid(zf) * g), z = gate pre-activations (fp32, bias not yet added)
+hipError_t launch_aan_post(int dtype, const float* z, const void* bg, const void* cat, const void* gamma,
+                           const void* beta, void* x, float* out_f32, int rows, int d, float eps,
+                           hipStream_t stream);
+
+// ---------------------------------------------------------------------- search
+hipError_t launch_topk(const float* logits, const float* cum, const int* last_tok, int eos_id, int batch, int beam,
+                       int vocab, int k, float* cand_lp, int* cand_idx, int* out_tok, int* out_parent,
+                       float* out_score, hipStream_t stream);
+// per sentence, in place: tab[r][j] = tab[parent[r]][j] for j < *t_dev
+hipError_t launch_reorder_table(int* tab, int ld, const int* parent, const int* t_dev, int batch, int beam,
+                                int max_t, hipStream_t stream);
+// per sentence, in place: st[l][r][c] = st[l][parent[r]][c]
+hipError_t launch_reorder_rows(float* st, const int* parent, int layers, int batch, int beam, int d,
+                               hipStream_t stream);
+
+}  // namespace san

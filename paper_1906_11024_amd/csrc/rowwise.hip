@@ -1,0 +1,337 @@
+// Row-wise kernels of the decoder step: embedding, split-K reduce + bias +
+// residual + LayerNorm, the average-attention (AAN) pre/post stages, beam-state
+// reordering and small utilities.  All are bandwidth-trivial; they exist to keep
+// the number of passes over the [rows][d] activations small.
+#include "common.h"
+#include "kernels.h"
+
+namespace san {
+
+// ---------------------------------------------------------------- embedding
+template <typename T>
+__global__ __launch_bounds__(256) void embed_kernel(const int* tok, int tok_stride, int rpg, const T* emb,
+                                                    const float* pe, const int* t_dev, T* x, int rows, int d,
+                                                    int vocab, float scale) {
+  const int r = blockIdx.x;
+  if (r >= rows) return;
+  const int hyp = r / rpg, i = r % rpg;
+  int id = tok[(size_t)hyp * tok_stride + i];
+  id = min(max(id, 0), vocab - 1);
+  const int pos = t_dev ? *t_dev : i;
+  const T* e = emb + (size_t)id * d;
+  const float* pp = pe + (size_t)pos * d;
+  for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
+    const float4 ev = load4(e + c);
+    const float4 pv = *reinterpret_cast<const float4*>(pp + c);
+    store4(x + (size_t)r * d + c,
+           make_float4(fmaf(ev.x, scale, pv.x), fmaf(ev.y, scale, pv.y), fmaf(ev.z, scale, pv.z),
+                       fmaf(ev.w, scale, pv.w)));
+  }
+}
+
+hipError_t launch_embed(int dtype, const int* tok, int tok_stride, int rpg, const void* emb, const float* pe,
+                        const int* t_dev, void* x, int rows, int d, int vocab, float scale, hipStream_t stream) {
+  if (rows <= 0) return hipSuccess;
+  const int threads = d / 4 >= 256 ? 256 : (d / 4 >= 128 ? 128 : 64);
+  if (dtype == 1)
+    hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(rows), dim3(threads), 0, stream, tok, tok_stride, rpg,
+                       (const bf16_t*)emb, pe, t_dev, (bf16_t*)x, rows, d, vocab, scale);
+  else
+    hipLaunchKernelGGL(embed_kernel<float>, dim3(rows), dim3(threads), 0, stream, tok, tok_stride, rpg,
+                       (const float*)emb, pe, t_dev, (float*)x, rows, d, vocab, scale);
+  return hipGetLastError();
+}
+
+// ------------------------------------------- reduce + bias + residual + LayerNorm
+constexpr int kLnMaxIter = 8;  // n <= 8 * 256 = 2048 columns, one wave per row
+
+template <typename T>
+__device__ __forceinline__ void layer_norm_row(float (&v)[kLnMaxIter][4], int n, int lane, const T* gamma,
+                                               const T* beta, float eps, T* out, float* out_f32) {
+  float s = 0.f;
+#pragma unroll
+  for (int it = 0; it < kLnMaxIter; ++it) {
+    const int c = it * 256 + lane * 4;
+    if (c < n) s += (v[it][0] + v[it][1]) + (v[it][2] + v[it][3]);
+  }
+  const float mean = wave_sum(s) / (float)n;
+  float q = 0.f;
+#pragma unroll
+  for (int it = 0; it < kLnMaxIter; ++it) {
+    const int c = it * 256 + lane * 4;
+    if (c < n) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float dlt = v[it][e] - mean;
+        q = fmaf(dlt, dlt, q);
+      }
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)n + eps);
+#pragma unroll
+  for (int it = 0; it < kLnMaxIter; ++it) {
+    const int c = it * 256 + lane * 4;
+    if (c < n) {
+      const float4 g = load4(gamma + c), b = load4(beta + c);
+      const float4 y = make_float4((v[it][0] - mean) * rstd * g.x + b.x, (v[it][1] - mean) * rstd * g.y + b.y,
+                                   (v[it][2] - mean) * rstd * g.z + b.z, (v[it][3] - mean) * rstd * g.w + b.w);
+      store4(out + c, y);
+      if (out_f32) *reinterpret_cast<float4*>(out_f32 + c) = y;
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void ln_reduce_kernel(const float* part, int nsplit, const T* bias, const T* res,
+                                                        int ldr, const T* gamma, const T* beta, T* out, int ldo,
+                                                        float* out_f32, int M, int n, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (m >= M) return;
+  float v[kLnMaxIter][4];
+#pragma unroll
+  for (int it = 0; it < kLnMaxIter; ++it) {
+    const int c = it * 256 + lane * 4;
+    if (c < n) {
+      float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int s = 0; s < nsplit; ++s) {
+        const float4 pv = *reinterpret_cast<const float4*>(part + ((size_t)s * M + m) * n + c);
+        a.x += pv.x; a.y += pv.y; a.z += pv.z; a.w += pv.w;
+      }
+      if (bias) {
+        const float4 bv = load4(bias + c);
+        a.x += bv.x; a.y += bv.y; a.z += bv.z; a.w += bv.w;
+      }
+      if (res) {
+        const float4 rv = load4(res + (size_t)m * ldr + c);
+        a.x += rv.x; a.y += rv.y; a.z += rv.z; a.w += rv.w;
+      }
+      v[it][0] = a.x; v[it][1] = a.y; v[it][2] = a.z; v[it][3] = a.w;
+    }
+  }
+  layer_norm_row<T>(v, n, lane, gamma, beta, eps, out + (size_t)m * ldo, out_f32 ? out_f32 + (size_t)m * n : nullptr);
+}
+
+hipError_t launch_ln_reduce(int dtype, const float* part, int nsplit, const void* bias, const void* res, int ldr,
+                            const void* gamma, const void* beta, void* out, int ldo, float* out_f32, int M, int n,
+                            float eps, hipStream_t stream) {
+  if (M <= 0) return hipSuccess;
+  if (n > kLnMaxIter * 256 || n % 4) return hipErrorInvalidValue;
+  dim3 grid((M + 3) / 4);
+  if (dtype == 1)
+    hipLaunchKernelGGL(ln_reduce_kernel<bf16_t>, grid, dim3(256), 0, stream, part, nsplit, (const bf16_t*)bias,
+                       (const bf16_t*)res, ldr, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)out, ldo,
+                       out_f32, M, n, eps);
+  else
+    hipLaunchKernelGGL(ln_reduce_kernel<float>, grid, dim3(256), 0, stream, part, nsplit, (const float*)bias,
+                       (const float*)res, ldr, (const float*)gamma, (const float*)beta, (float*)out, ldo, out_f32,
+                       M, n, eps);
+  return hipGetLastError();
+}
+
+// -------------------------------------------------------------- step bookkeeping
+__global__ void step_begin_kernel(const int* tok, int* last_tok, int* anc, int* hist, int ld, const int* t_dev,
+                                  int rows) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= rows) return;
+  const int t = *t_dev;
+  const int id = tok[r];
+  last_tok[r] = id;
+  if (t < ld) {
+    if (anc) anc[(size_t)r * ld + t] = r;
+    if (hist) hist[(size_t)r * ld + t] = id;
+  }
+}
+hipError_t launch_step_begin(const int* tok, int* last_tok, int* anc, int* hist, int ld, const int* t_dev, int rows,
+                             hipStream_t stream) {
+  hipLaunchKernelGGL(step_begin_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, tok, last_tok, anc, hist,
+                     ld, t_dev, rows);
+  return hipGetLastError();
+}
+
+__global__ void bump_kernel(int* t_dev) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *t_dev = *t_dev + 1;
+}
+hipError_t launch_bump(int* t_dev, hipStream_t stream) {
+  hipLaunchKernelGGL(bump_kernel, dim3(1), dim3(64), 0, stream, t_dev);
+  return hipGetLastError();
+}
+
+template <typename T> __global__ void to_f32_kernel(const T* src, int lds, float* dst, int rows, int cols) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)rows * cols) return;
+  const int r = (int)(i / cols), c = (int)(i % cols);
+  dst[i] = to_f32(src[(size_t)r * lds + c]);
+}
+hipError_t launch_to_f32(int dtype, const void* src, int lds, float* dst, int rows, int cols, hipStream_t stream) {
+  const size_t total = (size_t)rows * cols;
+  if (!total) return hipSuccess;
+  dim3 grid((unsigned)((total + 255) / 256));
+  if (dtype == 1)
+    hipLaunchKernelGGL(to_f32_kernel<bf16_t>, grid, dim3(256), 0, stream, (const bf16_t*)src, lds, dst, rows, cols);
+  else
+    hipLaunchKernelGGL(to_f32_kernel<float>, grid, dim3(256), 0, stream, (const float*)src, lds, dst, rows, cols);
+  return hipGetLastError();
+}
+
+__global__ void compact_S_kernel(const float* src, int ldS, float* dst, int rows_h, int n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)rows_h * n) return;
+  dst[i] = src[(i / n) * ldS + (i % n)];
+}
+hipError_t launch_compact_S(const float* src, int ldS, float* dst, int rows_h, int n, hipStream_t stream) {
+  const size_t total = (size_t)rows_h * n;
+  if (!total) return hipSuccess;
+  hipLaunchKernelGGL(compact_S_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, src, ldS, dst,
+                     rows_h, n);
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------------- AAN stages
+// Running sum of the layer inputs (fp32 state), its mean over the t+1 positions,
+// and a copy of x into the left half of the gate GEMM's input [x ; g].
+template <typename T>
+__global__ __launch_bounds__(256) void aan_pre_kernel(float* sum, const T* x, T* avg, T* cat, const int* t_dev,
+                                                      int rows, int d) {
+  const size_t i4 = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i4 >= (size_t)rows * d) return;
+  const int r = (int)(i4 / d), c = (int)(i4 % d);
+  const int t = *t_dev;
+  const float4 xv = load4(x + i4);
+  float4 s = (t == 0) ? make_float4(0.f, 0.f, 0.f, 0.f) : *reinterpret_cast<const float4*>(sum + i4);
+  s.x += xv.x; s.y += xv.y; s.z += xv.z; s.w += xv.w;
+  *reinterpret_cast<float4*>(sum + i4) = s;
+  const float inv = 1.0f / (float)(t + 1);
+  store4(avg + i4, make_float4(s.x * inv, s.y * inv, s.z * inv, s.w * inv));
+  store4(cat + (size_t)r * 2 * d + c, xv);
+}
+hipError_t launch_aan_pre(int dtype, float* sum, const void* x, void* avg, void* cat, const int* t_dev, int rows,
+                          int d, hipStream_t stream) {
+  const size_t total = (size_t)rows * d / 4;
+  if (!total) return hipSuccess;
+  dim3 grid((unsigned)((total + 255) / 256));
+  if (dtype == 1)
+    hipLaunchKernelGGL(aan_pre_kernel<bf16_t>, grid, dim3(256), 0, stream, sum, (const bf16_t*)x, (bf16_t*)avg,
+                       (bf16_t*)cat, t_dev, rows, d);
+  else
+    hipLaunchKernelGGL(aan_pre_kernel<float>, grid, dim3(256), 0, stream, sum, (const float*)x, (float*)avg,
+                       (float*)cat, t_dev, rows, d);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void aan_post_kernel(const float* z, const T* bg, const T* cat, const T* gamma,
+                                                       const T* beta, T* x, float* out_f32, int rows, int d,
+                                                       float eps) {
+  const int lane = threadIdx.x & 63;
+  const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (m >= rows) return;
+  float v[kLnMaxIter][4];
+#pragma unroll
+  for (int it = 0; it < kLnMaxIter; ++it) {
+    const int c = it * 256 + lane * 4;
+    if (c < d) {
+      const float4 zi = *reinterpret_cast<const float4*>(z + (size_t)m * 2 * d + c);
+      const float4 zf = *reinterpret_cast<const float4*>(z + (size_t)m * 2 * d + d + c);
+      const float4 bi = load4(bg + c), bf = load4(bg + d + c);
+      const float4 xv = load4(cat + (size_t)m * 2 * d + c);
+      const float4 gv = load4(cat + (size_t)m * 2 * d + d + c);
+      const float zia[4] = {zi.x + bi.x, zi.y + bi.y, zi.z + bi.z, zi.w + bi.w};
+      const float zfa[4] = {zf.x + bf.x, zf.y + bf.y, zf.z + bf.z, zf.w + bf.w};
+      const float xa[4] = {xv.x, xv.y, xv.z, xv.w}, ga[4] = {gv.x, gv.y, gv.z, gv.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float ig = 1.0f / (1.0f + expf(-zia[e]));
+        const float fg = 1.0f / (1.0f + expf(-zfa[e]));
+        v[it][e] = xa[e] + ig * xa[e] + fg * ga[e];
+      }
+    }
+  }
+  layer_norm_row<T>(v, d, lane, gamma, beta, eps, x + (size_t)m * d, out_f32 ? out_f32 + (size_t)m * d : nullptr);
+}
+hipError_t launch_aan_post(int dtype, const float* z, const void* bg, const void* cat, const void* gamma,
+                           const void* beta, void* x, float* out_f32, int rows, int d, float eps,
+                           hipStream_t stream) {
+  if (rows <= 0) return hipSuccess;
+  if (d > kLnMaxIter * 256 || d % 4) return hipErrorInvalidValue;
+  dim3 grid((rows + 3) / 4);
+  if (dtype == 1)
+    hipLaunchKernelGGL(aan_post_kernel<bf16_t>, grid, dim3(256), 0, stream, z, (const bf16_t*)bg,
+                       (const bf16_t*)cat, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)x, out_f32, rows, d,
+                       eps);
+  else
+    hipLaunchKernelGGL(aan_post_kernel<float>, grid, dim3(256), 0, stream, z, (const float*)bg, (const float*)cat,
+                       (const float*)gamma, (const float*)beta, (float*)x, out_f32, rows, d, eps);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------ beam reordering
+// A thread owns one column of one sentence: it reads that column of every old row
+// of the sentence, then writes the permuted rows, so the update is safe in place.
+constexpr int kMaxBeam = 32;
+
+__global__ void reorder_table_kernel(int* tab, int ld, const int* parent, const int* t_dev, int batch, int beam,
+                                     int max_t) {
+  const int b = blockIdx.y;
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const int n = min(*t_dev, max_t);
+  if (j >= n) return;
+  int old[kMaxBeam];
+#pragma unroll
+  for (int k = 0; k < kMaxBeam; ++k)
+    if (k < beam) old[k] = tab[(size_t)(b * beam + k) * ld + j];
+#pragma unroll
+  for (int k = 0; k < kMaxBeam; ++k) {
+    if (k < beam) {
+      const int pl = parent[b * beam + k] - b * beam;
+      if (pl >= 0 && pl < beam && pl != k) {
+        int v = old[0];
+#pragma unroll
+        for (int q = 1; q < kMaxBeam; ++q)
+          if (q == pl) v = old[q];
+        tab[(size_t)(b * beam + k) * ld + j] = v;
+      }
+    }
+  }
+}
+hipError_t launch_reorder_table(int* tab, int ld, const int* parent, const int* t_dev, int batch, int beam,
+                                int max_t, hipStream_t stream) {
+  if (beam > kMaxBeam) return hipErrorInvalidValue;
+  dim3 grid((max_t + 127) / 128, batch);
+  hipLaunchKernelGGL(reorder_table_kernel, grid, dim3(128), 0, stream, tab, ld, parent, t_dev, batch, beam, max_t);
+  return hipGetLastError();
+}
+
+__global__ void reorder_rows_kernel(float* st, const int* parent, int batch, int beam, int d) {
+  const int b = blockIdx.y, l = blockIdx.z;
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= d) return;
+  float* base = st + ((size_t)l * batch * beam + (size_t)b * beam) * d + c;
+  float old[kMaxBeam];
+#pragma unroll
+  for (int k = 0; k < kMaxBeam; ++k)
+    if (k < beam) old[k] = base[(size_t)k * d];
+#pragma unroll
+  for (int k = 0; k < kMaxBeam; ++k) {
+    if (k < beam) {
+      const int pl = parent[b * beam + k] - b * beam;
+      if (pl >= 0 && pl < beam && pl != k) {
+        float v = old[0];
+#pragma unroll
+        for (int q = 1; q < kMaxBeam; ++q)
+          if (q == pl) v = old[q];
+        base[(size_t)k * d] = v;
+      }
+    }
+  }
+}
+hipError_t launch_reorder_rows(float* st, const int* parent, int layers, int batch, int beam, int d,
+                               hipStream_t stream) {
+  if (beam > kMaxBeam) return hipErrorInvalidValue;
+  if (layers <= 0) return hipSuccess;
+  dim3 grid((d + 127) / 128, batch, layers);
+  hipLaunchKernelGGL(reorder_rows_kernel, grid, dim3(128), 0, stream, st, parent, batch, beam, d);
+  return hipGetLastError();
+}
+
+}  // namespace san

@@ -1,0 +1,717 @@
+// libsan: host side of the C ABI declared in include/san.h.  It validates the
+// configuration and the sharing policy, uploads only the tensors the policy needs,
+// owns the key/value caches and workspaces, and queues the kernels of each call on
+// the caller's stream.  No arithmetic of the method happens on the host.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/san.h"
+#include "kernels.h"
+
+using namespace san;
+
+namespace {
+
+thread_local std::string g_init_error;
+
+struct EncLayer {
+  void *wqkv, *bqkv, *wo, *bo, *ln1g, *ln1b, *w1, *b1, *w2, *b2, *ln2g, *ln2b;
+};
+
+struct DecLayer {
+  // self sub-layer
+  int self_head = 0;          // first layer of this layer's self-attention block
+  void *w_self = nullptr, *b_self = nullptr;  // head: [3d][d] (q;k;v), follower: [d][d] (v)
+  void *wo = nullptr, *bo = nullptr, *ln1g = nullptr, *ln1b = nullptr;
+  void *aw1 = nullptr, *ab1 = nullptr, *aw2 = nullptr, *ab2 = nullptr, *awg = nullptr, *abg = nullptr;
+  void *Kc = nullptr, *Vc = nullptr;          // [max_tgt][rows][d]
+  float* S_self = nullptr;                    // block head only: [rows*][H][max_tgt]
+  float* aan_sum = nullptr;
+  // encoder-decoder sub-layer
+  int ctx_head = 0;
+  void *wq_c = nullptr, *bq_c = nullptr;      // head only
+  void *wkv_c = nullptr, *bkv_c = nullptr;    // head: [2d][d] (k;v); follower in mode S: [d][d] (v)
+  void *wo_c = nullptr, *bo_c = nullptr, *ln2g = nullptr, *ln2b = nullptr;
+  void* mem = nullptr;                        // head: [batch*max_src][2d]; follower (mode S): [..][d]
+  float* S_ctx = nullptr;                     // head only
+  void* A_ctx = nullptr;                      // head only: T [rows*][d]
+  // feed-forward sub-layer
+  void *w1 = nullptr, *b1 = nullptr, *w2 = nullptr, *b2 = nullptr, *ln3g = nullptr, *ln3b = nullptr;
+  float *dbg_A_self = nullptr, *dbg_A_ctx = nullptr, *dbg_hidden = nullptr;
+};
+
+}  // namespace
+
+struct san_ctx {
+  san_config cfg;
+  hipStream_t stream = nullptr;
+  int dt = 0, esz = 4;
+  int d = 0, H = 0, dh = 0, F = 0, V = 0, rows_max = 0, rows_src_max = 0;
+  std::vector<EncLayer> enc;
+  std::vector<DecLayer> dec;
+  void *src_emb = nullptr, *tgt_emb = nullptr, *w_out = nullptr;
+  float* pe = nullptr;
+  // workspaces
+  void *x = nullptr, *qkv = nullptr, *ab = nullptr, *hb = nullptr, *cat = nullptr;
+  float* part = nullptr;
+  size_t part_elems = 0;
+  int *t_dev = nullptr, *anc = nullptr, *hist = nullptr, *last_tok = nullptr, *src_len = nullptr;
+  float* cand_lp = nullptr;
+  int* cand_idx = nullptr;
+  // state
+  int batch = 0, max_src = 0, t = -1;
+  size_t weight_bytes = 0, state_bytes = 0;
+  int launches = 0;
+  std::vector<void*> allocs;
+  std::string err;
+};
+
+namespace {
+
+int fail(san_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg; else g_init_error = msg;
+  return code;
+}
+
+#define HIP_TRY(c, expr)                                                                        \
+  do {                                                                                          \
+    hipError_t e_ = (expr);                                                                     \
+    if (e_ != hipSuccess)                                                                       \
+      return fail((c), e_ == hipErrorOutOfMemory ? SAN_ENOMEM : SAN_EHIP,                       \
+                  std::string(#expr) + ": " + hipGetErrorString(e_));                           \
+  } while (0)
+
+#define LAUNCH(c, expr)      \
+  do {                       \
+    HIP_TRY((c), (expr));    \
+    ++(c)->launches;         \
+  } while (0)
+
+// ---- blob layout: element offsets of every tensor, in the order san.h documents
+struct Blob {
+  size_t src_emb, tgt_emb, w_out, total;
+  struct Attn { size_t wq, bq, wk, bk, wv, bv, wo, bo; };
+  struct Ffn { size_t w1, b1, w2, b2; };
+  struct Ln { size_t g, b; };
+  struct Enc { Attn attn; Ln ln1; Ffn ffn; Ln ln2; };
+  struct Dec { Attn self; Ffn aan; size_t wg, bg; Ln ln1; Attn ctx; Ln ln2; Ffn ffn; Ln ln3; };
+  std::vector<Enc> enc;
+  std::vector<Dec> dec;
+};
+
+Blob layout(const san_config& c) {
+  Blob b;
+  size_t o = 0;
+  const size_t d = c.d_model, F = c.d_ff, V = c.vocab;
+  auto take = [&](size_t n) { size_t r = o; o += n; return r; };
+  auto attn = [&]() { Blob::Attn a; a.wq = take(d * d); a.bq = take(d); a.wk = take(d * d); a.bk = take(d);
+                      a.wv = take(d * d); a.bv = take(d); a.wo = take(d * d); a.bo = take(d); return a; };
+  auto ffn = [&]() { Blob::Ffn f; f.w1 = take(F * d); f.b1 = take(F); f.w2 = take(d * F); f.b2 = take(d); return f; };
+  auto ln = [&]() { Blob::Ln l; l.g = take(d); l.b = take(d); return l; };
+  b.src_emb = take(V * d);
+  b.tgt_emb = take(V * d);
+  for (int i = 0; i < c.n_enc_layers; ++i) {
+    Blob::Enc e; e.attn = attn(); e.ln1 = ln(); e.ffn = ffn(); e.ln2 = ln();
+    b.enc.push_back(e);
+  }
+  for (int i = 0; i < c.n_dec_layers; ++i) {
+    Blob::Dec e{};
+    if (c.self_kind == SAN_SELF_AAN) { e.aan = ffn(); e.wg = take(4 * d * d); e.bg = take(2 * d); }
+    else e.self = attn();
+    e.ln1 = ln(); e.ctx = attn(); e.ln2 = ln(); e.ffn = ffn(); e.ln3 = ln();
+    b.dec.push_back(e);
+  }
+  b.w_out = take(V * d);
+  b.total = o;
+  return b;
+}
+
+const char* check_config(const san_config& c) {
+  if (c.n_enc_layers < 1 || c.n_dec_layers < 1) return "layer counts must be >= 1";
+  if (c.d_model < 64 || c.d_model % 64 || c.d_model > 2048) return "d_model must be a multiple of 64 in [64, 2048]";
+  if (c.d_ff < 64 || c.d_ff % 64) return "d_ff must be a multiple of 64";
+  if (c.n_heads < 1 || c.d_model % c.n_heads) return "d_model must be divisible by n_heads";
+  const int dh = c.d_model / c.n_heads;
+  if (dh != 16 && dh != 32 && dh != 64 && dh != 128) return "head width must be 16, 32, 64 or 128";
+  if (c.vocab < 4 || c.vocab % 4) return "vocab must be a positive multiple of 4";
+  if (c.max_batch < 1 || c.max_src_len < 1 || c.max_tgt_len < 1) return "max_batch/max_src_len/max_tgt_len must be >= 1";
+  if (c.beam < 1 || c.beam > 32) return "beam must be in [1, 32]";
+  if (c.dtype != SAN_F32 && c.dtype != SAN_BF16) return "dtype must be SAN_F32 or SAN_BF16";
+  if (c.self_kind != SAN_SELF_DOT && c.self_kind != SAN_SELF_AAN) return "bad self_kind";
+  if (c.encdec_share != SAN_SHARE_A && c.encdec_share != SAN_SHARE_S) return "bad encdec_share";
+  if (c.use_cache != 0 && c.use_cache != 1) return "use_cache must be 0 or 1";
+  if (!c.use_cache && c.self_kind == SAN_SELF_AAN) return "the un-cached mode supports dot-product self-attention only";
+  if (!c.use_cache && c.debug) return "debug copies need use_cache = 1";
+  if (!(c.ln_eps > 0.f)) return "ln_eps must be > 0";
+  if ((long long)c.max_batch * c.beam * (long long)c.max_tgt_len > (1ll << 30)) return "batch*beam*max_tgt_len too large";
+  return nullptr;
+}
+
+bool policy_heads(int n, const int32_t* pi, int layers, std::vector<int>& head) {
+  head.clear();
+  if (n < 1 || !pi) return false;
+  int start = 0;
+  for (int i = 0; i < n; ++i) {
+    if (pi[i] < 1 || start + pi[i] > layers) return false;
+    for (int j = 0; j < pi[i]; ++j) head.push_back(start);
+    start += pi[i];
+  }
+  return start == layers;
+}
+
+int dalloc(san_ctx* c, void** p, size_t bytes, bool is_weight) {
+  *p = nullptr;
+  if (bytes == 0) bytes = 256;
+  HIP_TRY(c, hipMalloc(p, bytes));
+  c->allocs.push_back(*p);
+  (is_weight ? c->weight_bytes : c->state_bytes) += bytes;
+  return SAN_OK;
+}
+
+// upload `n` elements of the blob starting at element `off` to dst + dst_off elements
+int upload(san_ctx* c, void* dst, size_t dst_off, const void* blob, size_t off, size_t n) {
+  HIP_TRY(c, hipMemcpy((char*)dst + dst_off * c->esz, (const char*)blob + off * c->esz, n * c->esz,
+                       hipMemcpyHostToDevice));
+  return SAN_OK;
+}
+
+int wtensor(san_ctx* c, void** dst, const void* blob, size_t off, size_t n) {
+  int rc = dalloc(c, dst, n * c->esz, true);
+  if (rc) return rc;
+  return upload(c, *dst, 0, blob, off, n);
+}
+
+// ------------------------------------------------------------ kernel plumbing
+int gemm(san_ctx* c, const void* A, int lda, const void* W, const void* bias, int M, int N, int K, int relu,
+         int out_kind, void* o0, int ld0, long long ts0 = 0, void* o1 = nullptr, int ld1 = 0, long long ts1 = 0,
+         void* o2 = nullptr, int ld2 = 0, long long ts2 = 0, int seg_w = 0, bool use_t = false, int ksplit = 1) {
+  GemmParams p{};
+  p.A = A; p.lda = lda; p.W = W; p.bias = bias;
+  p.out[0] = o0; p.out[1] = o1; p.out[2] = o2;
+  p.ldo[0] = ld0; p.ldo[1] = ld1; p.ldo[2] = ld2;
+  p.tstride[0] = ts0; p.tstride[1] = ts1; p.tstride[2] = ts2;
+  p.seg_w = seg_w > 0 ? seg_w : (1 << 30);
+  p.t_dev = use_t ? c->t_dev : nullptr;
+  p.M = M; p.N = N; p.K = K; p.relu = relu; p.out_kind = out_kind; p.ksplit = ksplit;
+  LAUNCH(c, launch_gemm(c->dt, p, c->stream));
+  return SAN_OK;
+}
+
+// x_out = LayerNorm(res + A W^T + bias): split-K GEMM into fp32 partials, reduced
+// by the LayerNorm kernel.
+int gemm_ln(san_ctx* c, const void* A, int lda, const void* W, const void* bias, int M, int K, const void* res,
+            const void* g, const void* b, void* out, float* dbg) {
+  const int N = c->d;
+  int ks = gemm_pick_ksplit(M, N, K, c->dt);
+  while (ks > 1 && (size_t)ks * M * N > c->part_elems) ks /= 2;
+  if ((size_t)ks * M * N > c->part_elems) return fail(c, SAN_ECAPACITY, "split-K workspace too small");
+  int rc = gemm(c, A, lda, W, nullptr, M, N, K, 0, 2, c->part, N, 0, nullptr, 0, 0, nullptr, 0, 0, 0, false, ks);
+  if (rc) return rc;
+  LAUNCH(c, launch_ln_reduce(c->dt, c->part, ks, bias, res, N, g, b, out, N, dbg, M, N, c->cfg.ln_eps, c->stream));
+  return SAN_OK;
+}
+
+int ffn_block(san_ctx* c, const DecLayer* L, const EncLayer* E, int M, float* dbg) {
+  const void* w1 = L ? L->w1 : E->w1; const void* b1 = L ? L->b1 : E->b1;
+  const void* w2 = L ? L->w2 : E->w2; const void* b2 = L ? L->b2 : E->b2;
+  const void* g = L ? L->ln3g : E->ln2g; const void* b = L ? L->ln3b : E->ln2b;
+  int rc = gemm(c, c->x, c->d, w1, b1, M, c->F, c->d, 1, 0, c->hb, c->F);
+  if (rc) return rc;
+  return gemm_ln(c, c->hb, c->F, w2, b2, M, c->F, c->x, g, b, c->x, dbg);
+}
+
+int dbg_copy(san_ctx* c, const void* src, int lds, float* dst, int rows) {
+  if (!dst) return SAN_OK;
+  LAUNCH(c, launch_to_f32(c->dt, src, lds, dst, rows, c->d, c->stream));
+  return SAN_OK;
+}
+
+}  // namespace
+
+static int build_ctx(san_ctx* c, const Blob& bl, const void* blob, const std::vector<int>& self_head,
+                     const std::vector<int>& ctx_head) {
+  const san_config* cfg = &c->cfg;
+  const int esz = cfg->dtype == SAN_BF16 ? 2 : 4;
+  const int Ld = cfg->n_dec_layers;
+  c->dt = cfg->dtype; c->esz = esz;
+  c->d = cfg->d_model; c->H = cfg->n_heads; c->dh = c->d / c->H; c->F = cfg->d_ff; c->V = cfg->vocab;
+  c->rows_max = cfg->max_batch * cfg->beam;
+  c->rows_src_max = cfg->max_batch * cfg->max_src_len;
+  const size_t d = c->d, F = c->F, V = c->V;
+  const bool aan = cfg->self_kind == SAN_SELF_AAN, shareS = cfg->encdec_share == SAN_SHARE_S;
+  const bool nocache = !cfg->use_cache;
+  const int T = cfg->max_tgt_len;
+  // rows of the decoder-side activations: one per hypothesis, or one per
+  // (hypothesis, position) when nothing is cached
+  const size_t drows = nocache ? (size_t)c->rows_max * T : (size_t)c->rows_max;
+
+#define TRY(e) do { int rc_ = (e); if (rc_) return rc_; } while (0)
+    TRY(wtensor(c, &c->src_emb, blob, bl.src_emb, V * d));
+    TRY(wtensor(c, &c->tgt_emb, blob, bl.tgt_emb, V * d));
+    TRY(wtensor(c, &c->w_out, blob, bl.w_out, V * d));
+    // sinusoidal position table, built once in double on the host
+    {
+      const int npos = cfg->max_src_len > T ? cfg->max_src_len : T;
+      std::vector<float> pe((size_t)npos * d);
+      for (int pos = 0; pos < npos; ++pos)
+        for (size_t i = 0; i < d; i += 2) {
+          const double ang = (double)pos / std::pow(10000.0, (double)i / (double)d);
+          pe[pos * d + i] = (float)std::sin(ang);
+          pe[pos * d + i + 1] = (float)std::cos(ang);
+        }
+      TRY(dalloc(c, (void**)&c->pe, pe.size() * 4, true));
+      HIP_TRY(c, hipMemcpy(c->pe, pe.data(), pe.size() * 4, hipMemcpyHostToDevice));
+    }
+    c->enc.resize(cfg->n_enc_layers);
+    for (int i = 0; i < cfg->n_enc_layers; ++i) {
+      EncLayer& e = c->enc[i];
+      const Blob::Enc& o = bl.enc[i];
+      TRY(dalloc(c, &e.wqkv, 3 * d * d * esz, true));
+      TRY(dalloc(c, &e.bqkv, 3 * d * esz, true));
+      TRY(upload(c, e.wqkv, 0, blob, o.attn.wq, d * d));
+      TRY(upload(c, e.wqkv, d * d, blob, o.attn.wk, d * d));
+      TRY(upload(c, e.wqkv, 2 * d * d, blob, o.attn.wv, d * d));
+      TRY(upload(c, e.bqkv, 0, blob, o.attn.bq, d));
+      TRY(upload(c, e.bqkv, d, blob, o.attn.bk, d));
+      TRY(upload(c, e.bqkv, 2 * d, blob, o.attn.bv, d));
+      TRY(wtensor(c, &e.wo, blob, o.attn.wo, d * d));
+      TRY(wtensor(c, &e.bo, blob, o.attn.bo, d));
+      TRY(wtensor(c, &e.ln1g, blob, o.ln1.g, d));
+      TRY(wtensor(c, &e.ln1b, blob, o.ln1.b, d));
+      TRY(wtensor(c, &e.w1, blob, o.ffn.w1, F * d));
+      TRY(wtensor(c, &e.b1, blob, o.ffn.b1, F));
+      TRY(wtensor(c, &e.w2, blob, o.ffn.w2, d * F));
+      TRY(wtensor(c, &e.b2, blob, o.ffn.b2, d));
+      TRY(wtensor(c, &e.ln2g, blob, o.ln2.g, d));
+      TRY(wtensor(c, &e.ln2b, blob, o.ln2.b, d));
+    }
+    c->dec.resize(Ld);
+    for (int n = 0; n < Ld; ++n) {
+      DecLayer& L = c->dec[n];
+      const Blob::Dec& o = bl.dec[n];
+      L.self_head = self_head[n];
+      L.ctx_head = ctx_head[n];
+      const size_t cache_bytes = (size_t)T * c->rows_max * d * esz;
+      if (aan) {
+        TRY(wtensor(c, &L.aw1, blob, o.aan.w1, F * d));
+        TRY(wtensor(c, &L.ab1, blob, o.aan.b1, F));
+        TRY(wtensor(c, &L.aw2, blob, o.aan.w2, d * F));
+        TRY(wtensor(c, &L.ab2, blob, o.aan.b2, d));
+        TRY(wtensor(c, &L.awg, blob, o.wg, 4 * d * d));
+        TRY(wtensor(c, &L.abg, blob, o.bg, 2 * d));
+        TRY(dalloc(c, (void**)&L.aan_sum, (size_t)c->rows_max * d * 4, false));
+      } else {
+        if (L.self_head == n) {   // block head: fused [q;k;v] projection, key and value cache, weight scratch
+          TRY(dalloc(c, &L.w_self, 3 * d * d * esz, true));
+          TRY(dalloc(c, &L.b_self, 3 * d * esz, true));
+          TRY(upload(c, L.w_self, 0, blob, o.self.wq, d * d));
+          TRY(upload(c, L.w_self, d * d, blob, o.self.wk, d * d));
+          TRY(upload(c, L.w_self, 2 * d * d, blob, o.self.wv, d * d));
+          TRY(upload(c, L.b_self, 0, blob, o.self.bq, d));
+          TRY(upload(c, L.b_self, d, blob, o.self.bk, d));
+          TRY(upload(c, L.b_self, 2 * d, blob, o.self.bv, d));
+          if (!nocache) TRY(dalloc(c, &L.Kc, cache_bytes, false));
+          TRY(dalloc(c, (void**)&L.S_self, drows * c->H * T * 4, false));
+        } else {                  // follower: only V (Sec. 3.2: its Q/K transformations are discarded)
+          TRY(wtensor(c, &L.w_self, blob, o.self.wv, d * d));
+          TRY(wtensor(c, &L.b_self, blob, o.self.bv, d));
+        }
+        if (!nocache) TRY(dalloc(c, &L.Vc, cache_bytes, false));
+        TRY(wtensor(c, &L.wo, blob, o.self.wo, d * d));
+        TRY(wtensor(c, &L.bo, blob, o.self.bo, d));
+      }
+      TRY(wtensor(c, &L.ln1g, blob, o.ln1.g, d));
+      TRY(wtensor(c, &L.ln1b, blob, o.ln1.b, d));
+      if (L.ctx_head == n) {
+        TRY(wtensor(c, &L.wq_c, blob, o.ctx.wq, d * d));
+        TRY(wtensor(c, &L.bq_c, blob, o.ctx.bq, d));
+        TRY(dalloc(c, &L.wkv_c, 2 * d * d * esz, true));
+        TRY(dalloc(c, &L.bkv_c, 2 * d * esz, true));
+        TRY(upload(c, L.wkv_c, 0, blob, o.ctx.wk, d * d));
+        TRY(upload(c, L.wkv_c, d * d, blob, o.ctx.wv, d * d));
+        TRY(upload(c, L.bkv_c, 0, blob, o.ctx.bk, d));
+        TRY(upload(c, L.bkv_c, d, blob, o.ctx.bv, d));
+        TRY(dalloc(c, &L.mem, (size_t)c->rows_src_max * 2 * d * esz, false));
+        TRY(dalloc(c, (void**)&L.S_ctx, drows * c->H * cfg->max_src_len * 4, false));
+        TRY(dalloc(c, &L.A_ctx, drows * d * esz, false));
+      } else if (shareS) {
+        TRY(wtensor(c, &L.wkv_c, blob, o.ctx.wv, d * d));
+        TRY(wtensor(c, &L.bkv_c, blob, o.ctx.bv, d));
+        TRY(dalloc(c, &L.mem, (size_t)c->rows_src_max * d * esz, false));
+      }
+      TRY(wtensor(c, &L.wo_c, blob, o.ctx.wo, d * d));
+      TRY(wtensor(c, &L.bo_c, blob, o.ctx.bo, d));
+      TRY(wtensor(c, &L.ln2g, blob, o.ln2.g, d));
+      TRY(wtensor(c, &L.ln2b, blob, o.ln2.b, d));
+      TRY(wtensor(c, &L.w1, blob, o.ffn.w1, F * d));
+      TRY(wtensor(c, &L.b1, blob, o.ffn.b1, F));
+      TRY(wtensor(c, &L.w2, blob, o.ffn.w2, d * F));
+      TRY(wtensor(c, &L.b2, blob, o.ffn.b2, d));
+      TRY(wtensor(c, &L.ln3g, blob, o.ln3.g, d));
+      TRY(wtensor(c, &L.ln3b, blob, o.ln3.b, d));
+      if (cfg->debug) {
+        TRY(dalloc(c, (void**)&L.dbg_A_self, (size_t)c->rows_max * d * 4, false));
+        TRY(dalloc(c, (void**)&L.dbg_A_ctx, (size_t)c->rows_max * d * 4, false));
+        TRY(dalloc(c, (void**)&L.dbg_hidden, (size_t)c->rows_max * d * 4, false));
+      }
+    }
+    // workspaces, sized for the largest row count any call uses
+    size_t mrows = drows > (size_t)c->rows_src_max ? drows : (size_t)c->rows_src_max;
+    const size_t wide = F > 2 * d ? F : 2 * d;
+    TRY(dalloc(c, &c->x, mrows * d * esz, false));
+    TRY(dalloc(c, &c->qkv, mrows * 3 * d * esz, false));
+    TRY(dalloc(c, &c->ab, mrows * d * esz, false));
+    TRY(dalloc(c, &c->hb, mrows * wide * esz, false));
+    if (aan) TRY(dalloc(c, &c->cat, (size_t)c->rows_max * 2 * d * esz, false));
+    c->part_elems = mrows * 2 * d;
+    if (c->part_elems < (size_t)4 << 20) c->part_elems = (size_t)4 << 20;
+    TRY(dalloc(c, (void**)&c->part, c->part_elems * 4, false));
+    TRY(dalloc(c, (void**)&c->t_dev, 256, false));
+    TRY(dalloc(c, (void**)&c->anc, (size_t)c->rows_max * T * 4, false));
+    if (nocache) TRY(dalloc(c, (void**)&c->hist, (size_t)c->rows_max * T * 4, false));
+    TRY(dalloc(c, (void**)&c->last_tok, (size_t)c->rows_max * 4, false));
+    TRY(dalloc(c, (void**)&c->src_len, (size_t)cfg->max_batch * 4, false));
+    TRY(dalloc(c, (void**)&c->cand_lp, (size_t)c->rows_max * 32 * 4, false));
+    TRY(dalloc(c, (void**)&c->cand_idx, (size_t)c->rows_max * 32 * 4, false));
+    HIP_TRY(c, hipMemset(c->t_dev, 0, 256));
+    HIP_TRY(c, hipMemset(c->last_tok, 0xff, (size_t)c->rows_max * 4));
+    HIP_TRY(c, hipDeviceSynchronize());
+#undef TRY
+  return SAN_OK;
+}
+
+// =============================================================================
+extern "C" {
+
+size_t san_weight_bytes(const san_config* cfg) {
+  if (!cfg || check_config(*cfg)) return 0;
+  return layout(*cfg).total * (cfg->dtype == SAN_BF16 ? 2 : 4);
+}
+
+const char* san_last_error(const san_ctx* ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
+
+void san_free(san_ctx* ctx) {
+  if (!ctx) return;
+  (void)hipStreamSynchronize(ctx->stream);
+  for (void* p : ctx->allocs) (void)hipFree(p);
+  delete ctx;
+}
+
+int san_init(const san_config* cfg, const void* weights_host, size_t weight_bytes, const san_policy* policy,
+             void* hip_stream, san_ctx** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !weights_host || !policy || !out) return fail(nullptr, SAN_EINVAL, "null argument");
+  if (const char* m = check_config(*cfg)) return fail(nullptr, SAN_EINVAL, m);
+  const Blob bl = layout(*cfg);
+  const int esz = cfg->dtype == SAN_BF16 ? 2 : 4;
+  if (weight_bytes != bl.total * esz) {
+    char buf[128];
+    snprintf(buf, sizeof buf, "weight blob is %zu bytes, expected %zu", weight_bytes, bl.total * (size_t)esz);
+    return fail(nullptr, SAN_EINVAL, buf);
+  }
+  std::vector<int> self_head, ctx_head;
+  const int Ld = cfg->n_dec_layers;
+  if (cfg->self_kind == SAN_SELF_AAN) {
+    for (int i = 0; i < Ld; ++i) self_head.push_back(i);
+  } else if (!policy_heads(policy->n_self, policy->self_pi, Ld, self_head)) {
+    return fail(nullptr, SAN_EPOLICY, "self-attention policy must be block sizes >= 1 that sum to n_dec_layers");
+  }
+  if (!policy_heads(policy->n_encdec, policy->encdec_pi, Ld, ctx_head))
+    return fail(nullptr, SAN_EPOLICY, "enc-dec policy must be block sizes >= 1 that sum to n_dec_layers");
+
+  san_ctx* c = new (std::nothrow) san_ctx();
+  if (!c) return fail(nullptr, SAN_ENOMEM, "host allocation failed");
+  c->cfg = *cfg;
+  c->stream = (hipStream_t)hip_stream;
+  const int rc = build_ctx(c, bl, weights_host, self_head, ctx_head);
+  if (rc) {
+    g_init_error = c->err;
+    for (void* p : c->allocs) (void)hipFree(p);
+    delete c;
+    return rc;
+  }
+  *out = c;
+  return SAN_OK;
+}
+
+int san_encode(san_ctx* c, const int32_t* src_ids_dev, const int32_t* src_len_dev, int32_t batch, int32_t max_src) {
+  if (!c) return SAN_EINVAL;
+  if (!src_ids_dev || !src_len_dev || batch < 1 || max_src < 1) return fail(c, SAN_EINVAL, "san_encode: bad argument");
+  if (batch > c->cfg.max_batch || max_src > c->cfg.max_src_len)
+    return fail(c, SAN_ECAPACITY, "san_encode: batch or max_src exceeds the configured maximum");
+  const int d = c->d, Ms = batch * max_src;
+  const float scale = 1.0f / std::sqrt((float)c->dh);
+  c->t = -1;
+  int rc;
+  HIP_TRY(c, hipMemcpyAsync(c->src_len, src_len_dev, (size_t)batch * 4, hipMemcpyDeviceToDevice, c->stream));
+  LAUNCH(c, launch_embed(c->dt, src_ids_dev, max_src, max_src, c->src_emb, c->pe, nullptr, c->x, Ms, d, c->V,
+                         (float)std::sqrt((double)d), c->stream));
+  for (const EncLayer& e : c->enc) {
+    if ((rc = gemm(c, c->x, d, e.wqkv, e.bqkv, Ms, 3 * d, d, 0, 0, c->qkv, 3 * d))) return rc;
+    AttnParams a{};
+    a.q = c->qkv; a.ldq = 3 * d;
+    a.K = (char*)c->qkv + (size_t)d * c->esz; a.ldk = 3 * d;
+    a.V = (char*)c->qkv + (size_t)2 * d * c->esz; a.ldv = 3 * d;
+    a.out = c->ab; a.ldo = d;
+    a.len = c->src_len; a.rows = Ms; a.groups = batch; a.rpg = max_src; a.slot_stride = max_src;
+    a.H = c->H; a.dh = c->dh; a.lmax = max_src; a.scale = scale;
+    LAUNCH(c, launch_attention(c->dt, a, c->stream));
+    if ((rc = gemm_ln(c, c->ab, d, e.wo, e.bo, Ms, d, c->x, e.ln1g, e.ln1b, c->x, nullptr))) return rc;
+    if ((rc = ffn_block(c, nullptr, &e, Ms, nullptr))) return rc;
+  }
+  // encoder-decoder keys/values: block heads get [K;V]; in mode S every follower gets its own V
+  for (DecLayer& L : c->dec) {
+    if (!L.mem) continue;
+    const int N = L.wq_c ? 2 * d : d;
+    if ((rc = gemm(c, c->x, d, L.wkv_c, L.bkv_c, Ms, N, d, 0, 0, L.mem, N))) return rc;
+  }
+  HIP_TRY(c, hipMemsetAsync(c->t_dev, 0, 4, c->stream));
+  c->batch = batch; c->max_src = max_src; c->t = 0;
+  return SAN_OK;
+}
+
+int san_rewind(san_ctx* c) {
+  if (!c) return SAN_EINVAL;
+  if (c->t < 0) return fail(c, SAN_ESTATE, "san_rewind before san_encode");
+  HIP_TRY(c, hipMemsetAsync(c->t_dev, 0, 4, c->stream));
+  c->t = 0;
+  return SAN_OK;
+}
+
+static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
+  const int d = c->d, B = c->batch * c->cfg.beam, T = c->cfg.max_tgt_len;
+  const float scale = 1.0f / std::sqrt((float)c->dh);
+  const bool aan = c->cfg.self_kind == SAN_SELF_AAN, shareS = c->cfg.encdec_share == SAN_SHARE_S;
+  const bool dbg = c->cfg.debug != 0;
+  const long long slab = (long long)B * d;   // cache elements per position
+  int rc;
+  LAUNCH(c, launch_step_begin(tokens, c->last_tok, c->anc, nullptr, T, c->t_dev, B, c->stream));
+  LAUNCH(c, launch_embed(c->dt, tokens, 1, 1, c->tgt_emb, c->pe, c->t_dev, c->x, B, d, c->V,
+                         (float)std::sqrt((double)d), c->stream));
+  const int Ld = (int)c->dec.size();
+  for (int n = 0; n < Ld; ++n) {
+    DecLayer& L = c->dec[n];
+    if (aan) {
+      LAUNCH(c, launch_aan_pre(c->dt, L.aan_sum, c->x, c->ab, c->cat, c->t_dev, B, d, c->stream));
+      if ((rc = gemm(c, c->ab, d, L.aw1, L.ab1, B, c->F, d, 1, 0, c->hb, c->F))) return rc;
+      // g goes to the right half of [x ; g]
+      if ((rc = gemm(c, c->hb, c->F, L.aw2, L.ab2, B, d, c->F, 0, 0, (char*)c->cat + (size_t)d * c->esz, 2 * d))) return rc;
+      if ((rc = gemm(c, c->cat, 2 * d, L.awg, nullptr, B, 2 * d, 2 * d, 0, 2, c->part, 2 * d))) return rc;
+      LAUNCH(c, launch_aan_post(c->dt, c->part, L.abg, c->cat, L.ln1g, L.ln1b, c->x, L.dbg_A_self, B, d,
+                                c->cfg.ln_eps, c->stream));
+    } else {
+      const bool head = L.self_head == n;
+      const bool has_followers = head && n + 1 < Ld && c->dec[n + 1].self_head == n;
+      if (head) {   // Eq. 3: q, k, v; k and v land directly in this position's cache slot
+        if ((rc = gemm(c, c->x, d, L.w_self, L.b_self, B, 3 * d, d, 0, 0, c->qkv, d, 0, L.Kc, d, slab, L.Vc, d, slab, d,
+                       true)))
+          return rc;
+      } else {      // Eq. 4: only v
+        if ((rc = gemm(c, c->x, d, L.w_self, L.b_self, B, d, d, 0, 0, L.Vc, d, slab, nullptr, 0, 0, nullptr, 0, 0, 0,
+                       true)))
+          return rc;
+      }
+      AttnParams a{};
+      a.q = c->qkv; a.ldq = d;
+      a.K = L.Kc; a.ldk = d; a.V = L.Vc; a.ldv = d;
+      a.S_buf = c->dec[L.self_head].S_self; a.ldS = T;
+      a.out = c->ab; a.ldo = d;
+      a.anc = c->anc; a.ld_anc = T; a.t_dev = c->t_dev;
+      a.self_mode = 1; a.rows = B; a.H = c->H; a.dh = c->dh; a.lmax = T; a.scale = scale;
+      a.apply = head ? 0 : 1;
+      a.emit = head && (has_followers || dbg);
+      LAUNCH(c, launch_attention(c->dt, a, c->stream));
+      if ((rc = dbg_copy(c, c->ab, d, L.dbg_A_self, B))) return rc;
+      if ((rc = gemm_ln(c, c->ab, d, L.wo, L.bo, B, d, c->x, L.ln1g, L.ln1b, c->x, nullptr))) return rc;
+    }
+    // ---- encoder-decoder attention
+    const bool chead = L.ctx_head == n;
+    DecLayer& Hd = c->dec[L.ctx_head];
+    const void* A = Hd.A_ctx;
+    if (chead || shareS) {
+      AttnParams a{};
+      if (chead) {
+        if ((rc = gemm(c, c->x, d, L.wq_c, L.bq_c, B, d, d, 0, 0, c->qkv, d))) return rc;
+        a.q = c->qkv; a.ldq = d;
+        a.K = L.mem; a.ldk = 2 * d;
+        a.V = (char*)L.mem + (size_t)d * c->esz; a.ldv = 2 * d;
+        a.out = L.A_ctx;
+        const bool has_followers = n + 1 < Ld && c->dec[n + 1].ctx_head == n;
+        a.emit = (shareS && has_followers) || dbg;
+        a.zero_tail = dbg;
+      } else {    // mode S follower: head's weights times this layer's own V
+        a.V = L.mem; a.ldv = d;
+        a.out = c->ab;
+        a.apply = 1;
+        A = c->ab;
+      }
+      a.S_buf = Hd.S_ctx; a.ldS = c->cfg.max_src_len;
+      a.ldo = d;
+      a.len = c->src_len; a.rows = B; a.groups = c->batch; a.rpg = c->cfg.beam; a.slot_stride = c->max_src;
+      a.H = c->H; a.dh = c->dh; a.lmax = c->max_src; a.scale = scale;
+      LAUNCH(c, launch_attention(c->dt, a, c->stream));
+    }
+    if ((rc = dbg_copy(c, A, d, L.dbg_A_ctx, B))) return rc;
+    if ((rc = gemm_ln(c, A, d, L.wo_c, L.bo_c, B, d, c->x, L.ln2g, L.ln2b, c->x, nullptr))) return rc;
+    if ((rc = ffn_block(c, &L, nullptr, B, L.dbg_hidden))) return rc;
+  }
+  return gemm(c, c->x, d, c->w_out, nullptr, B, c->V, d, 0, 1, logits, c->V);
+}
+
+// Nothing cached: every position of every hypothesis is recomputed (rows =
+// hypotheses x positions), with a causal mask in self-attention.
+static int decode_uncached(san_ctx* c, const int32_t* tokens, float* logits) {
+  const int d = c->d, B = c->batch * c->cfg.beam, T = c->cfg.max_tgt_len;
+  const int np = c->t + 1, M = B * np;
+  const float scale = 1.0f / std::sqrt((float)c->dh);
+  const bool shareS = c->cfg.encdec_share == SAN_SHARE_S;
+  int rc;
+  LAUNCH(c, launch_step_begin(tokens, c->last_tok, nullptr, c->hist, T, c->t_dev, B, c->stream));
+  LAUNCH(c, launch_embed(c->dt, c->hist, T, np, c->tgt_emb, c->pe, nullptr, c->x, M, d, c->V,
+                         (float)std::sqrt((double)d), c->stream));
+  const int Ld = (int)c->dec.size();
+  for (int n = 0; n < Ld; ++n) {
+    DecLayer& L = c->dec[n];
+    const bool head = L.self_head == n;
+    if (head) {
+      if ((rc = gemm(c, c->x, d, L.w_self, L.b_self, M, 3 * d, d, 0, 0, c->qkv, 3 * d))) return rc;
+    } else {
+      if ((rc = gemm(c, c->x, d, L.w_self, L.b_self, M, d, d, 0, 0, (char*)c->qkv + (size_t)2 * d * c->esz, 3 * d)))
+        return rc;
+    }
+    {
+      AttnParams a{};
+      a.q = c->qkv; a.ldq = 3 * d;
+      a.K = (char*)c->qkv + (size_t)d * c->esz; a.ldk = 3 * d;
+      a.V = (char*)c->qkv + (size_t)2 * d * c->esz; a.ldv = 3 * d;
+      a.S_buf = c->dec[L.self_head].S_self; a.ldS = T;
+      a.out = c->ab; a.ldo = d;
+      a.n_fixed = np; a.rows = M; a.groups = B; a.rpg = np; a.slot_stride = np; a.causal = np;
+      a.H = c->H; a.dh = c->dh; a.lmax = np; a.scale = scale;
+      a.apply = head ? 0 : 1;
+      a.emit = head && n + 1 < Ld && c->dec[n + 1].self_head == n;
+      LAUNCH(c, launch_attention(c->dt, a, c->stream));
+    }
+    if ((rc = gemm_ln(c, c->ab, d, L.wo, L.bo, M, d, c->x, L.ln1g, L.ln1b, c->x, nullptr))) return rc;
+    const bool chead = L.ctx_head == n;
+    DecLayer& Hd = c->dec[L.ctx_head];
+    const void* A = Hd.A_ctx;
+    if (chead || shareS) {
+      AttnParams a{};
+      if (chead) {
+        if ((rc = gemm(c, c->x, d, L.wq_c, L.bq_c, M, d, d, 0, 0, c->qkv, d))) return rc;
+        a.q = c->qkv; a.ldq = d;
+        a.K = L.mem; a.ldk = 2 * d;
+        a.V = (char*)L.mem + (size_t)d * c->esz; a.ldv = 2 * d;
+        a.out = L.A_ctx;
+        a.emit = shareS && n + 1 < Ld && c->dec[n + 1].ctx_head == n;
+      } else {
+        a.V = L.mem; a.ldv = d;
+        a.out = c->ab;
+        a.apply = 1;
+        A = c->ab;
+      }
+      a.S_buf = Hd.S_ctx; a.ldS = c->cfg.max_src_len;
+      a.ldo = d;
+      a.len = c->src_len; a.rows = M; a.groups = c->batch; a.rpg = c->cfg.beam * np; a.slot_stride = c->max_src;
+      a.H = c->H; a.dh = c->dh; a.lmax = c->max_src; a.scale = scale;
+      LAUNCH(c, launch_attention(c->dt, a, c->stream));
+    }
+    if ((rc = gemm_ln(c, A, d, L.wo_c, L.bo_c, M, d, c->x, L.ln2g, L.ln2b, c->x, nullptr))) return rc;
+    if ((rc = ffn_block(c, &L, nullptr, M, nullptr))) return rc;
+  }
+  // logits of the last position of every hypothesis
+  return gemm(c, (char*)c->x + (size_t)(np - 1) * d * c->esz, np * d, c->w_out, nullptr, B, c->V, d, 0, 1, logits,
+              c->V);
+}
+
+int san_decode_step(san_ctx* c, const int32_t* tokens_dev, float* logits_dev) {
+  if (!c) return SAN_EINVAL;
+  if (!tokens_dev || !logits_dev) return fail(c, SAN_EINVAL, "san_decode_step: null argument");
+  if (c->t < 0) return fail(c, SAN_ESTATE, "san_decode_step before san_encode");
+  if (c->t >= c->cfg.max_tgt_len) return fail(c, SAN_ECAPACITY, "san_decode_step: max_tgt_len steps already decoded");
+  c->launches = 0;
+  int rc = c->cfg.use_cache ? decode_cached(c, tokens_dev, logits_dev) : decode_uncached(c, tokens_dev, logits_dev);
+  if (rc) return rc;
+  LAUNCH(c, launch_bump(c->t_dev, c->stream));
+  c->t += 1;
+  return SAN_OK;
+}
+
+int san_topk(san_ctx* c, const float* logits_dev, const float* cum_score_dev, int32_t k, int32_t* out_token_dev,
+             int32_t* out_parent_dev, float* out_score_dev) {
+  if (!c) return SAN_EINVAL;
+  if (!logits_dev || !cum_score_dev || !out_token_dev || !out_parent_dev || !out_score_dev)
+    return fail(c, SAN_EINVAL, "san_topk: null argument");
+  if (k < 1 || k > 32 || k > c->V) return fail(c, SAN_EINVAL, "san_topk: k must be in [1, min(32, vocab)]");
+  if (c->t < 0) return fail(c, SAN_ESTATE, "san_topk before san_encode");
+  HIP_TRY(c, launch_topk(logits_dev, cum_score_dev, c->last_tok, c->cfg.eos_id, c->batch, c->cfg.beam, c->V, k,
+                         c->cand_lp, c->cand_idx, out_token_dev, out_parent_dev, out_score_dev, c->stream));
+  return SAN_OK;
+}
+
+int san_beam_reorder(san_ctx* c, const int32_t* parent_idx_dev) {
+  if (!c) return SAN_EINVAL;
+  if (!parent_idx_dev) return fail(c, SAN_EINVAL, "san_beam_reorder: null argument");
+  if (c->t < 0) return fail(c, SAN_ESTATE, "san_beam_reorder before san_encode");
+  if (c->cfg.beam == 1) return SAN_OK;   // a sentence has a single row: nothing can move
+  const int T = c->cfg.max_tgt_len;
+  if (!c->cfg.use_cache) {
+    HIP_TRY(c, launch_reorder_table(c->hist, T, parent_idx_dev, c->t_dev, c->batch, c->cfg.beam, T, c->stream));
+  } else if (c->cfg.self_kind == SAN_SELF_AAN) {
+    for (DecLayer& L : c->dec)
+      HIP_TRY(c, launch_reorder_rows(L.aan_sum, parent_idx_dev, 1, c->batch, c->cfg.beam, c->d, c->stream));
+  } else {
+    // the caches stay where they are; only the per-row table of which cache row
+    // holds each past position is permuted
+    HIP_TRY(c, launch_reorder_table(c->anc, T, parent_idx_dev, c->t_dev, c->batch, c->cfg.beam, T, c->stream));
+  }
+  return SAN_OK;
+}
+
+int san_debug_get(san_ctx* c, int32_t what, int32_t layer, void* dst_dev, size_t cap) {
+  if (!c) return SAN_EINVAL;
+  if (!c->cfg.debug) return fail(c, SAN_ESTATE, "san_debug_get needs cfg.debug = 1");
+  if (c->t < 1) return fail(c, SAN_ESTATE, "san_debug_get before the first decode step");
+  if (!dst_dev || layer < 0 || layer >= (int)c->dec.size()) return fail(c, SAN_EINVAL, "san_debug_get: bad argument");
+  const int B = c->batch * c->cfg.beam;
+  DecLayer& L = c->dec[layer];
+  const float* src = nullptr;
+  switch (what) {
+    case SAN_DBG_S_SELF: {
+      if (c->cfg.self_kind == SAN_SELF_AAN) return fail(c, SAN_EINVAL, "no self-attention weights with AAN");
+      const size_t need = (size_t)B * c->H * c->t * 4;
+      if (cap < need) return fail(c, SAN_EINVAL, "san_debug_get: destination too small");
+      HIP_TRY(c, launch_compact_S(c->dec[L.self_head].S_self, c->cfg.max_tgt_len, (float*)dst_dev, B * c->H, c->t,
+                                  c->stream));
+      return SAN_OK;
+    }
+    case SAN_DBG_S_CTX: {
+      const size_t need = (size_t)B * c->H * c->max_src * 4;
+      if (cap < need) return fail(c, SAN_EINVAL, "san_debug_get: destination too small");
+      HIP_TRY(c, launch_compact_S(c->dec[L.ctx_head].S_ctx, c->cfg.max_src_len, (float*)dst_dev, B * c->H, c->max_src,
+                                  c->stream));
+      return SAN_OK;
+    }
+    case SAN_DBG_A_SELF: src = L.dbg_A_self; break;
+    case SAN_DBG_A_CTX: src = L.dbg_A_ctx; break;
+    case SAN_DBG_HIDDEN: src = L.dbg_hidden; break;
+    default: return fail(c, SAN_EINVAL, "san_debug_get: unknown tensor");
+  }
+  const size_t need = (size_t)B * c->d * 4;
+  if (cap < need) return fail(c, SAN_EINVAL, "san_debug_get: destination too small");
+  HIP_TRY(c, hipMemcpyAsync(dst_dev, src, need, hipMemcpyDeviceToDevice, c->stream));
+  return SAN_OK;
+}
+
+int32_t san_step(const san_ctx* c) { return c ? c->t : -1; }
+size_t san_device_bytes(const san_ctx* c, int32_t which) { return !c ? 0 : (which == 0 ? c->weight_bytes : c->state_bytes); }
+int32_t san_last_launch_count(const san_ctx* c) { return c ? c->launches : 0; }
+
+}  // extern "C"

@@ -1,0 +1,159 @@
+"""Test-side driver: runs the HIP library and the CPU oracle in lock-step on the
+same seeded inputs and compares them.  Only tests / smoke / bench import this."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import san_oracle as so
+from paper_1906_11024_amd import binding as sb
+from paper_1906_11024_amd import workloads as wl
+
+
+def make_gpu(cfg, weights, self_pi=None, encdec_pi=None, share="A", beam=None, steps=None,
+             use_cache=1, debug=0, eos_id=-1, max_batch=None, max_src_len=None):
+    sc = sb.make_config(cfg, beam=beam, max_tgt_len=steps, use_cache=use_cache, debug=debug, eos_id=eos_id,
+                        max_batch=max_batch, max_src_len=max_src_len,
+                        encdec_share=sb.SAN_SHARE_S if share == "S" else sb.SAN_SHARE_A)
+    blob = wl.pack_weights(cfg, weights)
+    return sb.San(sc, blob, self_pi if self_pi is not None else cfg["self_pi"],
+                  encdec_pi if encdec_pi is not None else cfg["encdec_pi"])
+
+
+def make_oracle(cfg, weights, self_pi=None, encdec_pi=None, share="A", eos_id=-1, max_len=None):
+    return so.SanOracle(cfg, weights, self_pi if self_pi is not None else cfg["self_pi"],
+                        encdec_pi if encdec_pi is not None else cfg["encdec_pi"],
+                        encdec_share=share, eos_id=eos_id, max_len=max_len)
+
+
+def rel_err_rows(got, ref):
+    """per row: max_v |got - ref| / max(max_v |ref|, 1e-6)"""
+    num = np.abs(got.astype(np.float64) - ref).max(axis=-1)
+    den = np.maximum(np.abs(ref).max(axis=-1), 1e-6)
+    return num / den
+
+
+class Lockstep:
+    """GPU decodes every sentence; the oracle decodes `subset` of them (sentences
+    never interact) and is forced onto the GPU's beam choices after each step, so
+    that one near-tie cannot cascade.  Each step records the logits error on the
+    subset's rows and checks that the GPU's beam choice is a valid top-k of the
+    oracle's scores within `tie_tol`."""
+
+    def __init__(self, gpu, orc, src, lens, beam, subset=None, bos_id=wl.BOS_ID):
+        import torch
+        self.torch = torch
+        self.gpu, self.orc, self.beam = gpu, orc, beam
+        batch = src.shape[0]
+        self.subset = np.arange(batch) if subset is None else np.asarray(subset)
+        self.batch = batch
+        B = batch * beam
+        self.B = B
+        dev = "cuda"
+        self.src_d = torch.from_numpy(np.ascontiguousarray(src)).to(dev)
+        self.len_d = torch.from_numpy(np.ascontiguousarray(lens)).to(dev)
+        gpu.encode(self.src_d, self.len_d)
+        orc.encode(src[self.subset], lens[self.subset])
+        V = gpu.cfg.vocab
+        self.V = V
+        self.tokens = torch.full((B,), bos_id, dtype=torch.int32, device=dev)
+        cum = np.full(B, -np.inf, dtype=np.float32)
+        cum[0::beam] = 0.0
+        self.cum = torch.from_numpy(cum).to(dev)
+        self.logits = torch.empty((B, V), dtype=torch.float32, device=dev)
+        self.o_tok = torch.empty((batch, beam), dtype=torch.int32, device=dev)
+        self.o_par = torch.empty((batch, beam), dtype=torch.int32, device=dev)
+        self.o_sc = torch.empty((batch, beam), dtype=torch.float32, device=dev)
+        # rows of the subset inside the GPU batch
+        self.rows = (self.subset[:, None] * beam + np.arange(beam)[None, :]).reshape(-1)
+        self.log = {"logit_err": [], "exact": [], "margin": [], "tokens": [], "parents": [], "scores": []}
+
+    def step(self, tie_tol, forced_tokens=None):
+        torch, gpu, orc, beam = self.torch, self.gpu, self.orc, self.beam
+        rows, V = self.rows, self.V
+        gpu.decode_step(self.tokens, self.logits)
+        tok_in = self.tokens.cpu().numpy()
+        lo = orc.decode_step(tok_in[rows])
+        lg = self.logits[torch.from_numpy(rows).to("cuda")].cpu().numpy()
+        assert np.isfinite(lg).all()
+        self.last_gpu_logits, self.last_orc_logits = lg, lo
+        self.log["logit_err"].append(float(rel_err_rows(lg, lo).max()))
+        gpu.topk(self.logits, self.cum, beam, self.o_tok, self.o_par, self.o_sc)
+        tok_g, par_g, sc_g = (t.cpu().numpy() for t in (self.o_tok, self.o_par, self.o_sc))
+        cum_np = self.cum.cpu().numpy().astype(np.float64)
+        tok_o, par_o, sc_o, margin = orc.topk(lo, cum_np[rows], beam, last_tokens=tok_in[rows])
+        lp_o = so.log_softmax(lo)
+        if orc.eos_id >= 0:
+            done = tok_in[rows] == orc.eos_id
+            lp_o[done, :] = -np.inf
+            lp_o[done, orc.eos_id] = 0.0
+        exact = True
+        for i, b in enumerate(self.subset):
+            pl = par_g[b] - b * beam                       # local beam index of each pick
+            assert ((pl >= 0) & (pl < beam)).all() and ((tok_g[b] >= 0) & (tok_g[b] < V)).all()
+            flat = pl * V + tok_g[b]
+            assert len(set(flat.tolist())) == beam, "duplicate candidate"
+            s_true = cum_np[par_g[b]] + lp_o[i * beam + pl, tok_g[b]]
+            live = np.isfinite(sc_o[i])
+            assert np.array_equal(np.isfinite(s_true), live)
+            assert np.all(np.abs(s_true[live] - sc_o[i][live]) <= tie_tol), (b, s_true, sc_o[i])
+            assert np.all(np.abs(sc_g[b][live] - s_true[live]) <= tie_tol), (b, sc_g[b], s_true)
+            same = np.array_equal(tok_g[b], tok_o[i]) and np.array_equal(pl, par_o[i] - i * beam)
+            if margin[i] > 2 * tie_tol and np.all(np.abs(np.diff(sc_o[i][live])) > 2 * tie_tol):
+                assert same, (b, tok_g[b], tok_o[i], par_g[b], par_o[i])
+            exact &= bool(same)
+        self.log["exact"].append(exact)
+        self.log["margin"].append(float(np.min(margin)))
+        # both sides follow the GPU's choice
+        parent_g = self.o_par.reshape(-1)
+        gpu.beam_reorder(parent_g)
+        par_local = (par_g[self.subset] - self.subset[:, None] * beam
+                     + np.arange(len(self.subset))[:, None] * beam).reshape(-1)
+        orc.beam_reorder(par_local)
+        self.tokens = self.o_tok.reshape(-1).clone() if forced_tokens is None else forced_tokens
+        self.cum = self.o_sc.reshape(-1).clone()
+        self.log["tokens"].append(tok_g.copy())
+        self.log["parents"].append(par_g.copy())
+        self.log["scores"].append(sc_g.copy())
+        return lg, lo
+
+
+def gpu_free_run(gpu, src, lens, beam, steps, bos_id=wl.BOS_ID, keep_logits=False):
+    """GPU-only search; returns per-step tokens / parents / scores (numpy)."""
+    import torch
+    batch = src.shape[0]
+    B, V = batch * beam, gpu.cfg.vocab
+    gpu.encode(torch.from_numpy(np.ascontiguousarray(src)).cuda(), torch.from_numpy(np.ascontiguousarray(lens)).cuda())
+    tokens = torch.full((B,), bos_id, dtype=torch.int32, device="cuda")
+    cum = np.full(B, -np.inf, dtype=np.float32)
+    cum[0::beam] = 0.0
+    cum = torch.from_numpy(cum).cuda()
+    logits = torch.empty((B, V), dtype=torch.float32, device="cuda")
+    o_tok = torch.empty((batch, beam), dtype=torch.int32, device="cuda")
+    o_par = torch.empty((batch, beam), dtype=torch.int32, device="cuda")
+    o_sc = torch.empty((batch, beam), dtype=torch.float32, device="cuda")
+    out = {"tokens": [], "parents": [], "scores": [], "logits": []}
+    for _ in range(steps):
+        gpu.decode_step(tokens, logits)
+        gpu.topk(logits, cum, beam, o_tok, o_par, o_sc)
+        gpu.beam_reorder(o_par.reshape(-1))
+        tokens = o_tok.reshape(-1).clone()
+        cum = o_sc.reshape(-1).clone()
+        out["tokens"].append(o_tok.reshape(-1).cpu().numpy())
+        out["parents"].append(o_par.reshape(-1).cpu().numpy())
+        out["scores"].append(o_sc.reshape(-1).cpu().numpy())
+        if keep_logits:
+            out["logits"].append(logits.cpu().numpy())
+    return out
+
+
+def pick_seed_with_margin(cfg, self_pi, encdec_pi, share, steps, beam, min_margin, sharp=1.0, tries=20):
+    """First seed whose oracle search never meets a top-k margin below
+    min_margin (so fp32 rounding cannot flip a beam decision)."""
+    for seed in range(tries):
+        w = wl.make_weights(cfg, seed=seed, sharp=sharp)
+        src, lens = wl.make_source(cfg, seed)
+        orc = make_oracle(cfg, w, self_pi, encdec_pi, share)
+        out = orc.search(src, lens, steps, beam)
+        if out["margin"] > min_margin:
+            return seed, w, src, lens, out
+    raise RuntimeError("no seed with a safe margin")

@@ -1,0 +1,96 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, sizes the weight blob like the generator, and rejects bad
+configurations and policies before touching a device.  No compute calls."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1906_11024_amd import binding as sb
+from paper_1906_11024_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(sb.LIB_PATH):
+        from paper_1906_11024_amd import build
+        build.build(verbose=False)
+    return sb.lib()
+
+
+def test_exports_match_header(lib):
+    hdr = open(os.path.join(ROOT, "include", "san.h")).read()
+    declared = re.findall(r"SAN_API\s+[\w\s\*]+?\b(san_\w+)\s*\(", hdr)
+    assert len(declared) >= 10
+    assert sorted(declared) == sorted(sb.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_config_struct_matches_header(lib):
+    hdr = open(os.path.join(ROOT, "include", "san.h")).read()
+    body = hdr[hdr.index("typedef struct {"):hdr.index("} san_config;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = []
+    for decl in re.findall(r"(?:int32_t|float)\s+([^;]+);", body):
+        names += [n.strip() for n in decl.split(",")]
+    assert names == [f[0] for f in sb.SanConfig._fields_]
+    assert C.sizeof(sb.SanConfig) == 4 * len(names)
+
+
+@pytest.mark.parametrize("name", list(wl.CONFIGS))
+def test_weight_bytes_matches_generator(lib, name):
+    cfg = wl.get_config(name)
+    n = sum(int(np.prod(s)) for _, s, _ in wl.tensor_specs(cfg))
+    assert sb.weight_bytes(sb.make_config(cfg)) == n * (2 if cfg["dtype"] == "bf16" else 4)
+
+
+def _init(lib, sc, self_pi, ctx_pi, nbytes=None):
+    nbytes = sb.weight_bytes(sc) if nbytes is None else nbytes
+    blob = np.zeros(max(nbytes, 4), dtype=np.uint8)
+    sp = (C.c_int32 * max(1, len(self_pi)))(*self_pi)
+    ep = (C.c_int32 * max(1, len(ctx_pi)))(*ctx_pi)
+    pol = sb.SanPolicy(len(self_pi), C.cast(sp, C.POINTER(C.c_int32)), len(ctx_pi), C.cast(ep, C.POINTER(C.c_int32)))
+    h = C.c_void_p()
+    rc = lib.san_init(C.byref(sc), blob.ctypes.data_as(C.c_void_p), nbytes, C.byref(pol), None, C.byref(h))
+    assert rc != 0 and not h.value
+    return rc, lib.san_last_error(None).decode()
+
+
+@pytest.mark.parametrize("field,value", [("d_model", 100), ("d_model", 4096), ("n_heads", 3), ("n_heads", 64),
+                                         ("d_ff", 100), ("vocab", 1001), ("beam", 0), ("beam", 33),
+                                         ("dtype", 7), ("self_kind", 2), ("encdec_share", 5), ("max_tgt_len", 0),
+                                         ("ln_eps", 0.0), ("n_dec_layers", 0)])
+def test_bad_config_is_einval(lib, field, value):
+    sc = sb.make_config(wl.get_config("tiny"))
+    setattr(sc, field, value)
+    assert sb.weight_bytes(sc) == 0
+    rc, msg = _init(lib, sc, [2], [2], nbytes=16)
+    assert rc == sb.SAN_EINVAL and msg
+
+
+def test_blob_size_mismatch_is_einval(lib):
+    sc = sb.make_config(wl.get_config("tiny"))
+    rc, msg = _init(lib, sc, [2], [2], nbytes=sb.weight_bytes(sc) - 4)
+    assert rc == sb.SAN_EINVAL and "bytes" in msg
+
+
+@pytest.mark.parametrize("spi,cpi", [([1], [2]), ([2], [3]), ([0, 2], [2]), ([2], []), ([3], [2]), ([2], [1, -1, 2])])
+def test_bad_policy_is_epolicy(lib, spi, cpi):
+    """Sec. 3.3: the block sizes must sum to the number of layers."""
+    sc = sb.make_config(wl.get_config("tiny"))
+    rc, msg = _init(lib, sc, spi, cpi)
+    assert rc == sb.SAN_EPOLICY and "policy" in msg
+
+
+def test_uncached_aan_rejected_and_null_handles(lib):
+    sc = sb.make_config(wl.get_config("tiny", self_kind="aan"), use_cache=0)
+    rc, _ = _init(lib, sc, [1, 1], [2], nbytes=16)
+    assert rc == sb.SAN_EINVAL
+    assert lib.san_step(None) == -1 and lib.san_device_bytes(None, 0) == 0
+    assert lib.san_decode_step(None, None, None) == sb.SAN_EINVAL
+    lib.san_free(None)
