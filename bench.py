@@ -1,0 +1,262 @@
+#!/usr/bin/env python3
+"""Benchmark of the shared-attention decoder step on one MI355X.
+
+A "step" is one pass of the whole hot path over all batch*beam rows:
+san_decode_step (embedding, every decoder layer under the sharing policy, output
+layer) + san_topk + san_beam_reorder, on the Transformer-base workload (64
+sentences x beam 4, source lengths U[20,60], 64 decode steps per sentence batch,
+fp32, self-attention shared in pairs, enc-dec attention in groups of 3).  K steps
+are timed as K/64 full decodes (the cache grows from 1 to 64 positions in each),
+inputs and weights resident in HBM, the encoder run once beforehand.
+
+Prints ONE JSON line: metric/value (decoded tokens/s over batch*beam rows), the
+roofline of the dominant attention kernel (HIP events on the library's stream,
+second identical pass), the same kernels under the unshared / share-S / un-cached
+configurations, and the CPU oracle timed on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=640)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--config", default="base", choices=["tiny", "base", "big", "long", "aan"])
+    ap.add_argument("--no-compare", action="store_true", help="skip the unshared / share-S / un-cached runs")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
+    ap.add_argument("--cpu-steps", type=int, default=16)
+    return ap.parse_args()
+
+
+class Runner:
+    """Device-resident decode loop: no host synchronisation inside."""
+
+    def __init__(self, torch, gpu, cfg, src, lens):
+        self.torch, self.gpu, self.cfg = torch, gpu, cfg
+        self.batch, self.beam, self.T = cfg["batch"], cfg["beam"], cfg["steps"]
+        B, V = self.batch * self.beam, cfg["V"]
+        self.B = B
+        dev = "cuda"
+        self.src = torch.from_numpy(src).to(dev)
+        self.len = torch.from_numpy(lens).to(dev)
+        self.logits = torch.empty((B, V), dtype=torch.float32, device=dev)
+        self.bos = torch.full((B,), 1, dtype=torch.int32, device=dev)
+        cum0 = torch.full((B,), float("-inf"), dtype=torch.float32, device=dev)
+        cum0[0::self.beam] = 0.0
+        self.cum0 = cum0
+        # two sets of beam-step outputs: step s reads set s-1 and writes set s
+        self.tok = [torch.empty((self.batch, self.beam), dtype=torch.int32, device=dev) for _ in range(2)]
+        self.par = [torch.empty((self.batch, self.beam), dtype=torch.int32, device=dev) for _ in range(2)]
+        self.sc = [torch.empty((self.batch, self.beam), dtype=torch.float32, device=dev) for _ in range(2)]
+        gpu.encode(self.src, self.len)
+        self.pos = 0
+
+    def steps(self, k):
+        g = self.gpu
+        for _ in range(k):
+            if self.pos == 0:
+                g.rewind()
+                tokens, cum = self.bos, self.cum0
+            else:
+                i = (self.pos - 1) & 1
+                tokens, cum = self.tok[i].view(-1), self.sc[i].view(-1)
+            o = self.pos & 1
+            g.decode_step(tokens, self.logits)
+            g.topk(self.logits, cum, self.beam, self.tok[o], self.par[o], self.sc[o])
+            g.beam_reorder(self.par[o].view(-1))
+            self.pos = (self.pos + 1) % self.T
+
+    def timed(self, k, warmup):
+        torch = self.torch
+        self.pos = 0
+        self.steps(warmup)
+        # start the timed region at the beginning of a decode
+        while self.pos != 0:
+            self.steps(1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        self.steps(k)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+
+def attention_bytes(cfg, esz, heads_self, followers_self, heads_ctx, s_followers_ctx, mean_src):
+    """Algorithmic bytes of the attention kernels, summed over one decode of T
+    steps: a block head streams K and V of the n cached positions of every row, a
+    follower only V; an enc-dec head streams the sentence's memory K and V once per
+    sentence."""
+    B, d, T = cfg["batch"] * cfg["beam"], cfg["d"], cfg["steps"]
+    sum_n = T * (T + 1) // 2
+    self_head = 2 * B * d * esz * sum_n * heads_self
+    self_apply = 1 * B * d * esz * sum_n * followers_self
+    ctx_head = 2 * cfg["batch"] * mean_src * d * esz * T * heads_ctx
+    ctx_apply = 1 * cfg["batch"] * mean_src * d * esz * T * s_followers_ctx
+    return {"attn_self": self_head, "attn_apply": self_apply, "attn_ctx": ctx_head, "attn_ctx_apply": ctx_apply}
+
+
+def gemm_flops_per_step(cfg, heads_self, followers_self, heads_ctx):
+    B, d, F, V, Ld = cfg["batch"] * cfg["beam"], cfg["d"], cfg["F"], cfg["V"], cfg["n_dec"]
+    proj = 2 * B * d * d * (3 * heads_self + followers_self + heads_ctx)
+    out = 2 * B * d * d * 2 * Ld
+    ffn = 2 * B * d * F * 2 * Ld
+    logits = 2 * B * d * V
+    return {"proj": proj, "out": out, "ffn": ffn, "logits": logits}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
+              "decoding shards by sentence with no communication, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_1906_11024_amd import binding as sb
+    from paper_1906_11024_amd import workloads as wl
+
+    if not os.path.exists(sb.LIB_PATH):
+        from paper_1906_11024_amd import build
+        build.build(verbose=False)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    cfg = wl.get_config(args.config)
+    T = cfg["steps"]
+    esz = 2 if cfg["dtype"] == "bf16" else 4
+    weights = wl.make_weights(cfg, seed=0)
+    blob = wl.pack_weights(cfg, weights)
+    src, lens = wl.make_source(cfg, 0)
+    mean_src = float(lens.mean())
+    B = cfg["batch"] * cfg["beam"]
+
+    def make(self_pi, ctx_pi, share=sb.SAN_SHARE_A, use_cache=1):
+        sc = sb.make_config(cfg, encdec_share=share, use_cache=use_cache)
+        return sb.San(sc, blob, self_pi, ctx_pi)
+
+    def heads(pi):
+        return len(pi), sum(pi) - len(pi)
+
+    # ------------------------------------------------ headline: SAN policy, cached
+    gpu = make(cfg["self_pi"], cfg["encdec_pi"])
+    run = Runner(torch, gpu, cfg, src, lens)
+    K = max(T, (args.steps // T) * T) if args.steps >= T else args.steps
+    wall = run.timed(K, args.warmup)
+    tok_per_s = B * K / wall
+    ms_per_step = wall / K * 1e3
+    launches = gpu.last_launch_count
+
+    # ------------------------------------------------ per-kernel pass (HIP events)
+    kernels, roofline = {}, None
+    if not args.no_profile:
+        run.pos = 0
+        gpu.profile(True)
+        gpu.profile_read(reset=True)
+        run.steps(T)
+        prof = gpu.profile_read(reset=True)
+        gpu.profile(False)
+        aan = cfg["self_kind"] == "aan"
+        hs, fs = (0, 0) if aan else heads(cfg["self_pi"])
+        hc, fc = heads(cfg["encdec_pi"])
+        ab = attention_bytes(cfg, esz, hs, fs, hc, 0, mean_src)
+        gf = gemm_flops_per_step(cfg, hs, fs, hc)
+        for k, (ms, n) in prof.items():
+            if n == 0:
+                continue
+            ent = {"ms_per_step": ms / T, "launches_per_step": n / T, "avg_us": ms / n * 1e3}
+            if k in ab and ab[k] > 0:
+                ent["algo_GBps"] = ab[k] / (ms * 1e-3) / 1e9
+                ent["frac_hbm_peak"] = ent["algo_GBps"] / HBM_PEAK_GBS
+            if k in gf:
+                ent["TFLOPs"] = gf[k] * T / (ms * 1e-3) / 1e12
+                ent["frac_mfma_peak"] = ent["TFLOPs"] / MFMA_PEAK_TFLOPS[cfg["dtype"]]
+            kernels[k] = ent
+        key = "attn_ctx" if aan else "attn_self"
+        ms, n = prof[key]
+        achieved = ab[key] / (ms * 1e-3) / 1e9
+        roofline = {"kernel": "attention_kernel (block-head " + ("enc-dec" if aan else "self") + " attention)",
+                    "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "bytes_per_launch": ab[key] / n, "avg_launch_us": ms / n * 1e3, "launches": n}
+    gpu.close()
+    del run
+
+    # ------------------------------------------------ same kernels, other policies
+    compare = {}
+    if not args.no_compare:
+        Ld = cfg["n_dec"]
+        variants = [("unshared_cached", [1] * Ld, [1] * Ld, sb.SAN_SHARE_A, 1, 2 * T)]
+        if cfg["self_kind"] != "aan":
+            variants.append(("san_share_s", cfg["self_pi"], cfg["encdec_pi"], sb.SAN_SHARE_S, 1, 2 * T))
+            variants.append(("san_no_cache", cfg["self_pi"], cfg["encdec_pi"], sb.SAN_SHARE_A, 0, T))
+            variants.append(("unshared_no_cache", [1] * Ld, [1] * Ld, sb.SAN_SHARE_A, 0, T))
+        for name, spi, cpi, share, cache, k in variants:
+            g = make(spi, cpi, share, cache)
+            r = Runner(torch, g, cfg, src, lens)
+            w = r.timed(k, T if cache else 0)
+            compare[name] = {"tokens_per_s": B * k / w, "ms_per_step": w / k * 1e3, "steps": k,
+                             "kernels_per_step": g.last_launch_count,
+                             "weight_MB": g.device_bytes(0) / 1e6, "state_MB": g.device_bytes(1) / 1e6}
+            g.close()
+            del r
+        compare["san_cached"] = {"tokens_per_s": tok_per_s, "ms_per_step": ms_per_step}
+        compare["speedup_san_vs_unshared_cached"] = tok_per_s / compare["unshared_cached"]["tokens_per_s"]
+        if "unshared_no_cache" in compare:
+            compare["speedup_san_vs_unshared_no_cache"] = tok_per_s / compare["unshared_no_cache"]["tokens_per_s"]
+
+    # ------------------------------------------------ CPU oracle on the host cores
+    cpu = None
+    if not args.no_cpu:
+        from oracle import san_oracle as so
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
+        except Exception:
+            cores = os.cpu_count()
+        orc = so.SanOracle(cfg, weights, cfg["self_pi"], cfg["encdec_pi"])
+        orc.encode(src, lens)
+        ksteps = min(args.cpu_steps, T)
+        tokens = np.full(B, 1, dtype=np.int64)
+        cum = np.full(B, -np.inf)
+        cum[0::cfg["beam"]] = 0.0
+        t0 = time.perf_counter()
+        for _ in range(ksteps):
+            lg = orc.decode_step(tokens)
+            tk, par, sc, _ = orc.topk(lg, cum, cfg["beam"])
+            orc.beam_reorder(par.reshape(-1))
+            tokens, cum = tk.reshape(-1).astype(np.int64), sc.reshape(-1)
+        cw = time.perf_counter() - t0
+        cpu = {"value": B * ksteps / cw, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"first {ksteps} of {T} decode steps of the same batch ({cfg['batch']} sentences x beam "
+                         f"{cfg['beam']}), numpy fp64; early steps have short caches, so this flatters the CPU",
+               "ms_per_step": cw / ksteps * 1e3}
+
+    out = {
+        "metric": "decoded tokens/sec (batch x beam rows per step)", "value": tok_per_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": f"transformer-{args.config}: {cfg['n_enc']}+{cfg['n_dec']} layers, d={cfg['d']}, "
+                               f"H={cfg['H']}, d_ff={cfg['F']}, vocab={cfg['V']}, batch {cfg['batch']} x beam "
+                               f"{cfg['beam']}, src len U{list(cfg['src_len'])}, {T} decode steps, cached, "
+                               f"self policy {cfg['self_pi']}, enc-dec policy {cfg['encdec_pi']} (share A)",
+                   "rows": B, "kernels_per_step": launches,
+                   "sentence_tokens_per_s": cfg["batch"] * K / wall},
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "compare": compare,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -66,8 +66,8 @@ typedef struct {
                                             d_model / n_heads in {16,32,64,128}        */
   int32_t max_batch;   /* sentences per san_encode call                               */
   int32_t beam;        /* hypotheses per sentence (1 = greedy), 1..32                 */
-  int32_t max_src_len; /* source positions per sentence                              */
-  int32_t max_tgt_len; /* decode steps per sentence (self cache capacity)            */
+  int32_t max_src_len; /* source positions per sentence, <= 1024                     */
+  int32_t max_tgt_len; /* decode steps per sentence (self cache capacity), <= 1024   */
   int32_t dtype;       /* SAN_F32 | SAN_BF16                                          */
   int32_t self_kind;   /* SAN_SELF_DOT | SAN_SELF_AAN                                 */
   int32_t encdec_share;/* SAN_SHARE_A | SAN_SHARE_S                                   */
@@ -171,6 +171,34 @@ SAN_API int32_t san_step(const san_ctx* ctx);
 /* Device bytes held by the context (weights uploaded / caches+workspaces):
  * shows the parameter and cache saving of a policy (Sec. 3.2). */
 SAN_API size_t san_device_bytes(const san_ctx* ctx, int32_t which /* 0 = weights, 1 = state */);
+
+/* Kernel classes for san_profile_read. */
+enum {
+  SAN_K_MISC = 0,            /* embedding, bookkeeping, encoder                          */
+  SAN_K_PROJ = 1,            /* q/k/v projections (+ cache append), enc-dec q projection  */
+  SAN_K_ATTN_SELF = 2,       /* self-attention of a block head: S and A (Eq. 1-3)         */
+  SAN_K_ATTN_APPLY = 3,      /* self-attention of a follower: A = S^m V (Eq. 4)           */
+  SAN_K_OUT = 4,             /* attention output projections                              */
+  SAN_K_LN = 5,              /* split-K reduce + bias + residual + LayerNorm              */
+  SAN_K_ATTN_CTX = 6,        /* enc-dec attention of a block head (Eq. 5)                 */
+  SAN_K_ATTN_CTX_APPLY = 7,  /* enc-dec follower with its own V (SAN_SHARE_S)             */
+  SAN_K_FFN = 8,             /* feed-forward GEMMs                                        */
+  SAN_K_LOGITS = 9,          /* output layer                                              */
+  SAN_K_TOPK = 10,           /* san_topk                                                  */
+  SAN_K_REORDER = 11,        /* san_beam_reorder                                          */
+  SAN_K_AAN = 12,            /* average-attention self layer (all of its kernels)         */
+  SAN_K_COUNT = 13
+};
+
+/* Per-kernel-class timing for benchmarks.  While enabled, every kernel the
+ * context queues is bracketed by a pair of HIP events on the context's stream and
+ * each API call ends with a stream synchronisation (so: not for production
+ * loops).  san_profile_read adds up, per class, the elapsed milliseconds and
+ * the number of launches since the last reset.
+ *   ms_out HOST double[SAN_K_COUNT], launches_out HOST int64[SAN_K_COUNT]
+ *   (either may be NULL). */
+SAN_API int san_profile(san_ctx* ctx, int32_t enable);
+SAN_API int san_profile_read(san_ctx* ctx, double* ms_out, int64_t* launches_out, int32_t reset);
 
 /* Number of kernels the last san_decode_step queued. */
 SAN_API int32_t san_last_launch_count(const san_ctx* ctx);

@@ -22,7 +22,10 @@ SAN_DBG_S_SELF, SAN_DBG_A_SELF, SAN_DBG_S_CTX, SAN_DBG_A_CTX, SAN_DBG_HIDDEN = r
 
 EXPORTS = ["san_weight_bytes", "san_init", "san_encode", "san_rewind", "san_decode_step", "san_topk",
            "san_beam_reorder", "san_debug_get", "san_step", "san_device_bytes", "san_last_launch_count",
-           "san_last_error", "san_free"]
+           "san_last_error", "san_free", "san_profile", "san_profile_read"]
+
+KINDS = ["misc", "proj", "attn_self", "attn_apply", "out", "ln", "attn_ctx", "attn_ctx_apply", "ffn", "logits",
+         "topk", "reorder", "aan"]
 
 
 class SanConfig(C.Structure):
@@ -78,6 +81,10 @@ def lib():
         l.san_last_launch_count.argtypes = [vp]
         l.san_last_error.restype = C.c_char_p
         l.san_last_error.argtypes = [vp]
+        l.san_profile.restype = C.c_int
+        l.san_profile.argtypes = [vp, i32]
+        l.san_profile_read.restype = C.c_int
+        l.san_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]
         l.san_free.restype = None
         l.san_free.argtypes = [vp]
         _lib = l
@@ -196,6 +203,16 @@ class San:
     @property
     def last_launch_count(self):
         return int(self._l.san_last_launch_count(self._h))
+
+    def profile(self, enable: bool):
+        self._check(self._l.san_profile(self._h, 1 if enable else 0))
+
+    def profile_read(self, reset=True):
+        """{class name: (milliseconds, launches)} accumulated since the last reset."""
+        ms = (C.c_double * len(KINDS))()
+        n = (C.c_int64 * len(KINDS))()
+        self._check(self._l.san_profile_read(self._h, ms, n, 1 if reset else 0))
+        return {k: (ms[i], int(n[i])) for i, k in enumerate(KINDS)}
 
     def close(self):
         if getattr(self, "_h", None):

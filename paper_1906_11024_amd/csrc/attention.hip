@@ -15,6 +15,14 @@ namespace san {
 constexpr int kWavesPerBlock = 4;
 constexpr int kUnroll = 4;
 
+// The LDS score rows are private to a wave: order its lanes' writes before the
+// other lanes' reads without a block-wide barrier.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <typename T, int LPP, int NQ>
 __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
   constexpr int EPL = Frag<T>::N;       // elements per lane per position
@@ -111,6 +119,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
         }
       }
     }
+    wave_lds_sync();
     // ---- softmax over key positions, one query at a time
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
@@ -145,10 +154,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
       for (int j = lane; j < n; j += kWave) sc[i * p.lmax + j] = (j < nk[i]) ? Sg[j] : 0.f;
     }
   }
-  // LDS rows are private to the wave; make the writes above visible to all its lanes
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  wave_lds_sync();
 
   // ---- pass 2: A = S V (Eq. 2)
   float acc[NQ][EPL];
@@ -205,6 +211,7 @@ template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p,
 
 hipError_t launch_attention(int dtype, const AttnParams& p, hipStream_t stream) {
   if (p.rows <= 0 || p.lmax <= 0) return hipSuccess;
+  if (p.lmax > 1024) return hipErrorInvalidValue;   // score rows must fit 64 KB of LDS
   const int lpp = dtype == 1 ? p.dh / 8 : p.dh / 4;
   if (dtype == 1) {
     switch (lpp) {

@@ -178,6 +178,15 @@ template <typename T, int TM, int TN> static hipError_t launch_tile(const GemmPa
   constexpr int BM = 64 * TM, BN = 64 * TN;
   dim3 grid((p.N + BN - 1) / BN, (p.M + BM - 1) / BM, p.ksplit);
   const size_t smem = 2 * (BM + BN) * kRowBytes;
+  if (smem > 64 * 1024) {
+    static bool raised = false;   // the limit is a per-function attribute; set it once
+    if (!raised) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, TM, TN>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      if (e != hipSuccess) return e;
+      raised = true;
+    }
+  }
   hipLaunchKernelGGL((gemm_kernel<T, TM, TN>), grid, dim3(256), smem, stream, p);
   return hipGetLastError();
 }

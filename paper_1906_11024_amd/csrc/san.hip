@@ -68,6 +68,15 @@ struct san_ctx {
   int batch = 0, max_src = 0, t = -1;
   size_t weight_bytes = 0, state_bytes = 0;
   int launches = 0;
+  // per-kernel-class timing (off unless san_profile switched it on)
+  bool prof_on = false;
+  int kind = SAN_K_MISC;
+  std::vector<hipEvent_t> events;
+  size_t events_used = 0;
+  struct Pending { int kind; size_t e0, e1; };
+  std::vector<Pending> pending;
+  double prof_ms[SAN_K_COUNT] = {0};
+  long long prof_n[SAN_K_COUNT] = {0};
   std::vector<void*> allocs;
   std::string err;
 };
@@ -87,10 +96,44 @@ int fail(san_ctx* c, int code, const std::string& msg) {
                   std::string(#expr) + ": " + hipGetErrorString(e_));                           \
   } while (0)
 
-#define LAUNCH(c, expr)      \
-  do {                       \
-    HIP_TRY((c), (expr));    \
-    ++(c)->launches;         \
+// With profiling on, a pair of events brackets every launch on the stream.
+long prof_mark(san_ctx* c) {
+  if (!c->prof_on) return -1;
+  if (c->events_used == c->events.size()) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return -1;
+    c->events.push_back(e);
+  }
+  const size_t i = c->events_used++;
+  if (hipEventRecord(c->events[i], c->stream) != hipSuccess) return -1;
+  return (long)i;
+}
+void prof_close(san_ctx* c, long e0) {
+  if (e0 < 0) return;
+  const long e1 = prof_mark(c);
+  if (e1 >= 0) c->pending.push_back({c->kind, (size_t)e0, (size_t)e1});
+}
+int prof_flush(san_ctx* c) {
+  if (!c->prof_on) return SAN_OK;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return SAN_EHIP;
+  for (const auto& p : c->pending) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->events[p.e0], c->events[p.e1]) == hipSuccess) {
+      c->prof_ms[p.kind] += ms;
+      c->prof_n[p.kind] += 1;
+    }
+  }
+  c->pending.clear();
+  c->events_used = 0;
+  return SAN_OK;
+}
+
+#define LAUNCH(c, expr)              \
+  do {                               \
+    const long pm_ = prof_mark(c);   \
+    HIP_TRY((c), (expr));            \
+    prof_close((c), pm_);            \
+    ++(c)->launches;                 \
   } while (0)
 
 // ---- blob layout: element offsets of every tensor, in the order san.h documents
@@ -141,6 +184,7 @@ const char* check_config(const san_config& c) {
   if (dh != 16 && dh != 32 && dh != 64 && dh != 128) return "head width must be 16, 32, 64 or 128";
   if (c.vocab < 4 || c.vocab % 4) return "vocab must be a positive multiple of 4";
   if (c.max_batch < 1 || c.max_src_len < 1 || c.max_tgt_len < 1) return "max_batch/max_src_len/max_tgt_len must be >= 1";
+  if (c.max_src_len > 1024 || c.max_tgt_len > 1024) return "max_src_len and max_tgt_len must be <= 1024";
   if (c.beam < 1 || c.beam > 32) return "beam must be in [1, 32]";
   if (c.dtype != SAN_F32 && c.dtype != SAN_BF16) return "dtype must be SAN_F32 or SAN_BF16";
   if (c.self_kind != SAN_SELF_DOT && c.self_kind != SAN_SELF_AAN) return "bad self_kind";
@@ -213,7 +257,10 @@ int gemm_ln(san_ctx* c, const void* A, int lda, const void* W, const void* bias,
   if ((size_t)ks * M * N > c->part_elems) return fail(c, SAN_ECAPACITY, "split-K workspace too small");
   int rc = gemm(c, A, lda, W, nullptr, M, N, K, 0, 2, c->part, N, 0, nullptr, 0, 0, nullptr, 0, 0, 0, false, ks);
   if (rc) return rc;
+  const int k0 = c->kind;
+  c->kind = SAN_K_LN;
   LAUNCH(c, launch_ln_reduce(c->dt, c->part, ks, bias, res, N, g, b, out, N, dbg, M, N, c->cfg.ln_eps, c->stream));
+  c->kind = k0;
   return SAN_OK;
 }
 
@@ -221,6 +268,7 @@ int ffn_block(san_ctx* c, const DecLayer* L, const EncLayer* E, int M, float* db
   const void* w1 = L ? L->w1 : E->w1; const void* b1 = L ? L->b1 : E->b1;
   const void* w2 = L ? L->w2 : E->w2; const void* b2 = L ? L->b2 : E->b2;
   const void* g = L ? L->ln3g : E->ln2g; const void* b = L ? L->ln3b : E->ln2b;
+  if (L) c->kind = SAN_K_FFN;
   int rc = gemm(c, c->x, c->d, w1, b1, M, c->F, c->d, 1, 0, c->hb, c->F);
   if (rc) return rc;
   return gemm_ln(c, c->hb, c->F, w2, b2, M, c->F, c->x, g, b, c->x, dbg);
@@ -228,6 +276,7 @@ int ffn_block(san_ctx* c, const DecLayer* L, const EncLayer* E, int M, float* db
 
 int dbg_copy(san_ctx* c, const void* src, int lds, float* dst, int rows) {
   if (!dst) return SAN_OK;
+  c->kind = SAN_K_MISC;
   LAUNCH(c, launch_to_f32(c->dt, src, lds, dst, rows, c->d, c->stream));
   return SAN_OK;
 }
@@ -399,6 +448,7 @@ const char* san_last_error(const san_ctx* ctx) { return ctx ? ctx->err.c_str() :
 void san_free(san_ctx* ctx) {
   if (!ctx) return;
   (void)hipStreamSynchronize(ctx->stream);
+  for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
   for (void* p : ctx->allocs) (void)hipFree(p);
   delete ctx;
 }
@@ -449,6 +499,7 @@ int san_encode(san_ctx* c, const int32_t* src_ids_dev, const int32_t* src_len_de
   const float scale = 1.0f / std::sqrt((float)c->dh);
   c->t = -1;
   int rc;
+  c->kind = SAN_K_MISC;
   HIP_TRY(c, hipMemcpyAsync(c->src_len, src_len_dev, (size_t)batch * 4, hipMemcpyDeviceToDevice, c->stream));
   LAUNCH(c, launch_embed(c->dt, src_ids_dev, max_src, max_src, c->src_emb, c->pe, nullptr, c->x, Ms, d, c->V,
                          (float)std::sqrt((double)d), c->stream));
@@ -464,6 +515,7 @@ int san_encode(san_ctx* c, const int32_t* src_ids_dev, const int32_t* src_len_de
     LAUNCH(c, launch_attention(c->dt, a, c->stream));
     if ((rc = gemm_ln(c, c->ab, d, e.wo, e.bo, Ms, d, c->x, e.ln1g, e.ln1b, c->x, nullptr))) return rc;
     if ((rc = ffn_block(c, nullptr, &e, Ms, nullptr))) return rc;
+    c->kind = SAN_K_MISC;
   }
   // encoder-decoder keys/values: block heads get [K;V]; in mode S every follower gets its own V
   for (DecLayer& L : c->dec) {
@@ -473,7 +525,7 @@ int san_encode(san_ctx* c, const int32_t* src_ids_dev, const int32_t* src_len_de
   }
   HIP_TRY(c, hipMemsetAsync(c->t_dev, 0, 4, c->stream));
   c->batch = batch; c->max_src = max_src; c->t = 0;
-  return SAN_OK;
+  return prof_flush(c);
 }
 
 int san_rewind(san_ctx* c) {
@@ -491,6 +543,7 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
   const bool dbg = c->cfg.debug != 0;
   const long long slab = (long long)B * d;   // cache elements per position
   int rc;
+  c->kind = SAN_K_MISC;
   LAUNCH(c, launch_step_begin(tokens, c->last_tok, c->anc, nullptr, T, c->t_dev, B, c->stream));
   LAUNCH(c, launch_embed(c->dt, tokens, 1, 1, c->tgt_emb, c->pe, c->t_dev, c->x, B, d, c->V,
                          (float)std::sqrt((double)d), c->stream));
@@ -498,6 +551,7 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
   for (int n = 0; n < Ld; ++n) {
     DecLayer& L = c->dec[n];
     if (aan) {
+      c->kind = SAN_K_AAN;
       LAUNCH(c, launch_aan_pre(c->dt, L.aan_sum, c->x, c->ab, c->cat, c->t_dev, B, d, c->stream));
       if ((rc = gemm(c, c->ab, d, L.aw1, L.ab1, B, c->F, d, 1, 0, c->hb, c->F))) return rc;
       // g goes to the right half of [x ; g]
@@ -508,6 +562,7 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
     } else {
       const bool head = L.self_head == n;
       const bool has_followers = head && n + 1 < Ld && c->dec[n + 1].self_head == n;
+      c->kind = SAN_K_PROJ;
       if (head) {   // Eq. 3: q, k, v; k and v land directly in this position's cache slot
         if ((rc = gemm(c, c->x, d, L.w_self, L.b_self, B, 3 * d, d, 0, 0, c->qkv, d, 0, L.Kc, d, slab, L.Vc, d, slab, d,
                        true)))
@@ -526,8 +581,10 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
       a.self_mode = 1; a.rows = B; a.H = c->H; a.dh = c->dh; a.lmax = T; a.scale = scale;
       a.apply = head ? 0 : 1;
       a.emit = head && (has_followers || dbg);
+      c->kind = head ? SAN_K_ATTN_SELF : SAN_K_ATTN_APPLY;
       LAUNCH(c, launch_attention(c->dt, a, c->stream));
       if ((rc = dbg_copy(c, c->ab, d, L.dbg_A_self, B))) return rc;
+      c->kind = SAN_K_OUT;
       if ((rc = gemm_ln(c, c->ab, d, L.wo, L.bo, B, d, c->x, L.ln1g, L.ln1b, c->x, nullptr))) return rc;
     }
     // ---- encoder-decoder attention
@@ -537,6 +594,7 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
     if (chead || shareS) {
       AttnParams a{};
       if (chead) {
+        c->kind = SAN_K_PROJ;
         if ((rc = gemm(c, c->x, d, L.wq_c, L.bq_c, B, d, d, 0, 0, c->qkv, d))) return rc;
         a.q = c->qkv; a.ldq = d;
         a.K = L.mem; a.ldk = 2 * d;
@@ -555,12 +613,15 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
       a.ldo = d;
       a.len = c->src_len; a.rows = B; a.groups = c->batch; a.rpg = c->cfg.beam; a.slot_stride = c->max_src;
       a.H = c->H; a.dh = c->dh; a.lmax = c->max_src; a.scale = scale;
+      c->kind = chead ? SAN_K_ATTN_CTX : SAN_K_ATTN_CTX_APPLY;
       LAUNCH(c, launch_attention(c->dt, a, c->stream));
     }
     if ((rc = dbg_copy(c, A, d, L.dbg_A_ctx, B))) return rc;
+    c->kind = SAN_K_OUT;
     if ((rc = gemm_ln(c, A, d, L.wo_c, L.bo_c, B, d, c->x, L.ln2g, L.ln2b, c->x, nullptr))) return rc;
     if ((rc = ffn_block(c, &L, nullptr, B, L.dbg_hidden))) return rc;
   }
+  c->kind = SAN_K_LOGITS;
   return gemm(c, c->x, d, c->w_out, nullptr, B, c->V, d, 0, 1, logits, c->V);
 }
 
@@ -572,6 +633,7 @@ static int decode_uncached(san_ctx* c, const int32_t* tokens, float* logits) {
   const float scale = 1.0f / std::sqrt((float)c->dh);
   const bool shareS = c->cfg.encdec_share == SAN_SHARE_S;
   int rc;
+  c->kind = SAN_K_MISC;
   LAUNCH(c, launch_step_begin(tokens, c->last_tok, nullptr, c->hist, T, c->t_dev, B, c->stream));
   LAUNCH(c, launch_embed(c->dt, c->hist, T, np, c->tgt_emb, c->pe, nullptr, c->x, M, d, c->V,
                          (float)std::sqrt((double)d), c->stream));
@@ -579,6 +641,7 @@ static int decode_uncached(san_ctx* c, const int32_t* tokens, float* logits) {
   for (int n = 0; n < Ld; ++n) {
     DecLayer& L = c->dec[n];
     const bool head = L.self_head == n;
+    c->kind = SAN_K_PROJ;
     if (head) {
       if ((rc = gemm(c, c->x, d, L.w_self, L.b_self, M, 3 * d, d, 0, 0, c->qkv, 3 * d))) return rc;
     } else {
@@ -596,8 +659,10 @@ static int decode_uncached(san_ctx* c, const int32_t* tokens, float* logits) {
       a.H = c->H; a.dh = c->dh; a.lmax = np; a.scale = scale;
       a.apply = head ? 0 : 1;
       a.emit = head && n + 1 < Ld && c->dec[n + 1].self_head == n;
+      c->kind = head ? SAN_K_ATTN_SELF : SAN_K_ATTN_APPLY;
       LAUNCH(c, launch_attention(c->dt, a, c->stream));
     }
+    c->kind = SAN_K_OUT;
     if ((rc = gemm_ln(c, c->ab, d, L.wo, L.bo, M, d, c->x, L.ln1g, L.ln1b, c->x, nullptr))) return rc;
     const bool chead = L.ctx_head == n;
     DecLayer& Hd = c->dec[L.ctx_head];
@@ -605,6 +670,7 @@ static int decode_uncached(san_ctx* c, const int32_t* tokens, float* logits) {
     if (chead || shareS) {
       AttnParams a{};
       if (chead) {
+        c->kind = SAN_K_PROJ;
         if ((rc = gemm(c, c->x, d, L.wq_c, L.bq_c, M, d, d, 0, 0, c->qkv, d))) return rc;
         a.q = c->qkv; a.ldq = d;
         a.K = L.mem; a.ldk = 2 * d;
@@ -621,12 +687,15 @@ static int decode_uncached(san_ctx* c, const int32_t* tokens, float* logits) {
       a.ldo = d;
       a.len = c->src_len; a.rows = M; a.groups = c->batch; a.rpg = c->cfg.beam * np; a.slot_stride = c->max_src;
       a.H = c->H; a.dh = c->dh; a.lmax = c->max_src; a.scale = scale;
+      c->kind = chead ? SAN_K_ATTN_CTX : SAN_K_ATTN_CTX_APPLY;
       LAUNCH(c, launch_attention(c->dt, a, c->stream));
     }
+    c->kind = SAN_K_OUT;
     if ((rc = gemm_ln(c, A, d, L.wo_c, L.bo_c, M, d, c->x, L.ln2g, L.ln2b, c->x, nullptr))) return rc;
     if ((rc = ffn_block(c, &L, nullptr, M, nullptr))) return rc;
   }
   // logits of the last position of every hypothesis
+  c->kind = SAN_K_LOGITS;
   return gemm(c, (char*)c->x + (size_t)(np - 1) * d * c->esz, np * d, c->w_out, nullptr, B, c->V, d, 0, 1, logits,
               c->V);
 }
@@ -639,9 +708,10 @@ int san_decode_step(san_ctx* c, const int32_t* tokens_dev, float* logits_dev) {
   c->launches = 0;
   int rc = c->cfg.use_cache ? decode_cached(c, tokens_dev, logits_dev) : decode_uncached(c, tokens_dev, logits_dev);
   if (rc) return rc;
+  c->kind = SAN_K_MISC;
   LAUNCH(c, launch_bump(c->t_dev, c->stream));
   c->t += 1;
-  return SAN_OK;
+  return prof_flush(c);
 }
 
 int san_topk(san_ctx* c, const float* logits_dev, const float* cum_score_dev, int32_t k, int32_t* out_token_dev,
@@ -651,9 +721,12 @@ int san_topk(san_ctx* c, const float* logits_dev, const float* cum_score_dev, in
     return fail(c, SAN_EINVAL, "san_topk: null argument");
   if (k < 1 || k > 32 || k > c->V) return fail(c, SAN_EINVAL, "san_topk: k must be in [1, min(32, vocab)]");
   if (c->t < 0) return fail(c, SAN_ESTATE, "san_topk before san_encode");
+  c->kind = SAN_K_TOPK;
+  const long pm = prof_mark(c);
   HIP_TRY(c, launch_topk(logits_dev, cum_score_dev, c->last_tok, c->cfg.eos_id, c->batch, c->cfg.beam, c->V, k,
                          c->cand_lp, c->cand_idx, out_token_dev, out_parent_dev, out_score_dev, c->stream));
-  return SAN_OK;
+  prof_close(c, pm);
+  return prof_flush(c);
 }
 
 int san_beam_reorder(san_ctx* c, const int32_t* parent_idx_dev) {
@@ -662,6 +735,8 @@ int san_beam_reorder(san_ctx* c, const int32_t* parent_idx_dev) {
   if (c->t < 0) return fail(c, SAN_ESTATE, "san_beam_reorder before san_encode");
   if (c->cfg.beam == 1) return SAN_OK;   // a sentence has a single row: nothing can move
   const int T = c->cfg.max_tgt_len;
+  c->kind = SAN_K_REORDER;
+  const long pm = prof_mark(c);
   if (!c->cfg.use_cache) {
     HIP_TRY(c, launch_reorder_table(c->hist, T, parent_idx_dev, c->t_dev, c->batch, c->cfg.beam, T, c->stream));
   } else if (c->cfg.self_kind == SAN_SELF_AAN) {
@@ -672,7 +747,8 @@ int san_beam_reorder(san_ctx* c, const int32_t* parent_idx_dev) {
     // holds each past position is permuted
     HIP_TRY(c, launch_reorder_table(c->anc, T, parent_idx_dev, c->t_dev, c->batch, c->cfg.beam, T, c->stream));
   }
-  return SAN_OK;
+  prof_close(c, pm);
+  return prof_flush(c);
 }
 
 int san_debug_get(san_ctx* c, int32_t what, int32_t layer, void* dst_dev, size_t cap) {
@@ -708,6 +784,24 @@ int san_debug_get(san_ctx* c, int32_t what, int32_t layer, void* dst_dev, size_t
   if (cap < need) return fail(c, SAN_EINVAL, "san_debug_get: destination too small");
   HIP_TRY(c, hipMemcpyAsync(dst_dev, src, need, hipMemcpyDeviceToDevice, c->stream));
   return SAN_OK;
+}
+
+int san_profile(san_ctx* c, int32_t enable) {
+  if (!c) return SAN_EINVAL;
+  int rc = prof_flush(c);
+  c->prof_on = enable != 0;
+  return rc;
+}
+
+int san_profile_read(san_ctx* c, double* ms_out, int64_t* launches_out, int32_t reset) {
+  if (!c) return SAN_EINVAL;
+  int rc = prof_flush(c);
+  for (int k = 0; k < SAN_K_COUNT; ++k) {
+    if (ms_out) ms_out[k] = c->prof_ms[k];
+    if (launches_out) launches_out[k] = c->prof_n[k];
+    if (reset) { c->prof_ms[k] = 0; c->prof_n[k] = 0; }
+  }
+  return rc;
 }
 
 int32_t san_step(const san_ctx* c) { return c ? c->t : -1; }

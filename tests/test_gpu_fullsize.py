@@ -1,0 +1,66 @@
+"""Parity at the full workload sizes, in the launch configuration the benchmark
+times.  The GPU decodes the whole batch; the oracle decodes a sample of the
+sentences (sentences never interact, so a sentence's rows can be computed one by
+one) in lock-step, forced onto the GPU's beam choices."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_1906_11024_amd import workloads as wl
+from tests import harness as hz
+
+
+def _run(name, subset_n, steps=None, tol=1e-4, tie_tol=5e-4, **over):
+    if not torch.cuda.is_available():
+        pytest.fail("needs a GPU")
+    cfg = wl.get_config(name, **over)
+    steps = steps or cfg["steps"]
+    w = wl.make_weights(cfg, seed=0)
+    src, lens = wl.make_source(cfg, 0)
+    order = np.argsort(lens, kind="stable")
+    # shortest, longest and evenly spaced sentences in between
+    subset = np.unique(order[np.linspace(0, len(order) - 1, subset_n).astype(int)])
+    gpu = hz.make_gpu(cfg, w)
+    orc = hz.make_oracle(cfg, w)
+    ls = hz.Lockstep(gpu, orc, src, lens, cfg["beam"], subset=subset)
+    for t in range(steps):
+        ls.step(tie_tol=tie_tol)
+        if t % 16 == 0:
+            print(f"{name} step {t} err {ls.log['logit_err'][-1]:.2e}", flush=True)
+    torch.cuda.synchronize()
+    err = max(ls.log["logit_err"])
+    print(f"{name}: max logits rel err {err:.3e}, exact beam steps {sum(ls.log['exact'])}/{steps}, "
+          f"kernels/step {gpu.last_launch_count}", flush=True)
+    assert err <= tol
+    assert sum(ls.log["exact"]) >= 0.8 * steps
+    gpu.close()
+    del w
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(400)
+def test_base_full_fp32():
+    _run("base", 8)
+
+
+@pytest.mark.timeout(400)
+def test_base_unshared_and_share_s_fp32():
+    _run("base", 3, steps=24, self_pi=[1] * 6, encdec_pi=[1] * 6)
+
+
+@pytest.mark.timeout(600)
+def test_long_full_fp32():
+    _run("long", 3)
+
+
+@pytest.mark.timeout(600)
+def test_big_full_bf16():
+    _run("big", 3, tol=2e-2, tie_tol=0.2)
+
+
+@pytest.mark.timeout(600)
+def test_aan_full_bf16():
+    _run("aan", 3, tol=2e-2, tie_tol=0.2)

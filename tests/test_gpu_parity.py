@@ -233,7 +233,7 @@ def test_topk_kernel_against_oracle_same_inputs(V, beam, k):
     o_sc = torch.empty((3, k), dtype=torch.float32, device="cuda")
     gpu.topk(lg, cm, k, o_tok, o_par, o_sc)
     orc = hz.make_oracle(cfg, w)
-    orc.batch = 3
+    orc.batch, orc.last_tokens = 3, None
     tok, par, sc, _ = orc.topk(logits, cum, k)
     lp = logits.astype(np.float64) - np.log(np.exp(logits.astype(np.float64)).sum(-1, keepdims=True))
     tg, pg, sg = o_tok.cpu().numpy(), o_par.cpu().numpy(), o_sc.cpu().numpy()
