@@ -13,7 +13,7 @@
 namespace san {
 
 constexpr int kWavesPerBlock = 4;
-constexpr int kUnroll = 4;
+constexpr int kUnroll = 8;
 
 // The LDS score rows are private to a wave: order its lanes' writes before the
 // other lanes' reads without a block-wide barrier.
@@ -23,11 +23,27 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// 16-byte fragment -> fp32 values
+__device__ __forceinline__ void widen(const uint4& raw, float (&out)[4]) {
+  out[0] = __uint_as_float(raw.x); out[1] = __uint_as_float(raw.y);
+  out[2] = __uint_as_float(raw.z); out[3] = __uint_as_float(raw.w);
+}
+__device__ __forceinline__ void widen(const uint4& raw, float (&out)[8]) {
+  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    out[2 * i] = __uint_as_float(w[i] << 16);
+    out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+}
+
 template <typename T, int LPP, int NQ>
 __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
   constexpr int EPL = Frag<T>::N;       // elements per lane per position
   constexpr int PPL = kWave / LPP;      // positions per load instruction
   constexpr int DH = LPP * EPL;
+  constexpr int U = kUnroll;            // load instructions per chunk
+  constexpr int CH = PPL * U;           // positions per chunk
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
   const int c = lane % LPP, g = lane / LPP;
@@ -46,19 +62,22 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
   long long slot_base = 0;
   if (p.self_mode) {
     const int r = rest;
+    // slot of key j: position-major cache, row taken from the ancestry table.  The
+    // whole table row is fetched (entries past the current step are never used),
+    // so these loads do not wait for the step counter.
+    for (int j = threadIdx.x; j < p.lmax; j += blockDim.x) slots[j] = j * p.rows + p.anc[(size_t)r * p.ld_anc + j];
     n = *p.t_dev + 1;
     n = min(n, p.lmax);
     qrow[0] = r;
     nk[0] = n;
 #pragma unroll
     for (int i = 1; i < NQ; ++i) { qrow[i] = -1; nk[i] = 0; }
-    // slot of key j: position-major cache, row taken from the ancestry table
-    for (int j = threadIdx.x; j < n; j += blockDim.x) slots[j] = j * p.rows + p.anc[(size_t)r * p.ld_anc + j];
     __syncthreads();
   } else {
-    const int nqb = (p.rpg + NQ - 1) / NQ;
-    const int qb = rest % nqb;
-    const int grp = rest / nqb;
+    // blocks of one group (= the beams of a sentence) are numbered a multiple of
+    // 8 apart where possible, so that they land on the same XCD and share its L2
+    const int qb = rest / p.groups;   // query block inside the group
+    const int grp = rest % p.groups;
     slot_base = (long long)grp * p.slot_stride;
     const int nfull = p.len ? max(0, min(p.len[grp], p.lmax)) : p.n_fixed;
     n = 0;
@@ -82,8 +101,27 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
   const T* Qp = reinterpret_cast<const T*>(p.q);
   T* Op = reinterpret_cast<T*>(p.out);
   const int col = h * DH + c * EPL;
+  const bool self_mode = p.self_mode != 0;
 
-  auto slot_of = [&](int j) -> long long { return p.self_mode ? (long long)slots[j] : slot_base + j; };
+  // One chunk = U load instructions = CH positions; positions past n-1 re-read
+  // position n-1 (never out of bounds) and are ignored later.
+  auto load_chunk = [&](const T* base, long long ld, int j0, uint4 (&buf)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int j = min(j0 + u * PPL + g, n - 1);
+      const long long slot = self_mode ? (long long)slots[j] : slot_base + j;
+      buf[u] = *reinterpret_cast<const uint4*>(base + slot * ld + col);
+    }
+  };
+
+  // Software pipeline: while chunk i is being consumed the loads of chunk i+1 are
+  // in flight, and the first V chunk is requested before any score is computed,
+  // so a short stream costs a single memory round trip.
+  uint4 kb0[U], kb1[U], vb0[U], vb1[U];
+  if (n > 0) {
+    if (!p.apply) load_chunk(Kp, p.ldk, 0, kb0);
+    load_chunk(Vp, p.ldv, 0, vb0);
+  }
 
   if (!p.apply) {
     // ---- pass 1: scores (Eq. 1, numerator)
@@ -99,24 +137,28 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
         for (int e = 0; e < EPL; ++e) qf[i][e] = 0.f;
       }
     }
-    for (int j0 = 0; j0 < n; j0 += PPL * kUnroll) {
-      float kf[kUnroll][EPL];
+    auto scores = [&](int j0, const uint4 (&buf)[U]) {
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u) {
-        const int j = min(j0 + u * PPL + g, n - 1);
-        load_frag(Kp + slot_of(j) * p.ldk + col, kf[u]);
-      }
-#pragma unroll
-      for (int u = 0; u < kUnroll; ++u) {
+      for (int u = 0; u < U; ++u) {
         const int j = j0 + u * PPL + g;
+        float kf[EPL];
+        widen(buf[u], kf);
 #pragma unroll
         for (int i = 0; i < NQ; ++i) {
           float dot = 0.f;
 #pragma unroll
-          for (int e = 0; e < EPL; ++e) dot = fmaf(qf[i][e], kf[u][e], dot);
-          dot = xor_sum<1, LPP>(dot);
+          for (int e = 0; e < EPL; ++e) dot = fmaf(qf[i][e], kf[e], dot);
+          dot = lanes_sum<LPP>(dot);
           if (c == 0 && j < n) sc[i * p.lmax + j] = (j < nk[i]) ? dot : -INFINITY;
         }
+      }
+    };
+    for (int j0 = 0; j0 < n; j0 += 2 * CH) {
+      if (j0 + CH < n) load_chunk(Kp, p.ldk, j0 + CH, kb1);
+      scores(j0, kb0);
+      if (j0 + CH < n) {
+        if (j0 + 2 * CH < n) load_chunk(Kp, p.ldk, j0 + 2 * CH, kb0);
+        scores(j0 + CH, kb1);
       }
     }
     wave_lds_sync();
@@ -162,24 +204,28 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
   for (int i = 0; i < NQ; ++i)
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[i][e] = 0.f;
-  for (int j0 = 0; j0 < n; j0 += PPL * kUnroll) {
-    float vf[kUnroll][EPL];
+  auto weighted = [&](int j0, const uint4 (&buf)[U]) {
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int j = min(j0 + u * PPL + g, n - 1);
-      load_frag(Vp + slot_of(j) * p.ldv + col, vf[u]);
-    }
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
+    for (int u = 0; u < U; ++u) {
       const int j = j0 + u * PPL + g;
       if (j < n) {
+        float vf[EPL];
+        widen(buf[u], vf);
 #pragma unroll
         for (int i = 0; i < NQ; ++i) {
           const float w = sc[i * p.lmax + j];
 #pragma unroll
-          for (int e = 0; e < EPL; ++e) acc[i][e] = fmaf(w, vf[u][e], acc[i][e]);
+          for (int e = 0; e < EPL; ++e) acc[i][e] = fmaf(w, vf[e], acc[i][e]);
         }
       }
+    }
+  };
+  for (int j0 = 0; j0 < n; j0 += 2 * CH) {
+    if (j0 + CH < n) load_chunk(Vp, p.ldv, j0 + CH, vb1);
+    weighted(j0, vb0);
+    if (j0 + CH < n) {
+      if (j0 + 2 * CH < n) load_chunk(Vp, p.ldv, j0 + 2 * CH, vb0);
+      weighted(j0 + CH, vb1);
     }
   }
 #pragma unroll
@@ -196,9 +242,11 @@ template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p,
     const size_t smem = sizeof(float) * kWavesPerBlock * p.lmax + sizeof(int) * p.lmax;
     dim3 grid((unsigned)(p.rows * nhg));
     hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(256), smem, stream, p);
-  } else if (p.rpg == 1) {
+  } else if (p.rpg <= 32) {
+    // few queries per stream (the beams of a sentence): one wave per query keeps
+    // enough waves in flight; the queries' re-reads of the stream hit in L2
     const size_t smem = sizeof(float) * kWavesPerBlock * p.lmax;
-    dim3 grid((unsigned)(p.groups * nhg));
+    dim3 grid((unsigned)(p.groups * p.rpg * nhg));
     hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(256), smem, stream, p);
   } else {
     const int nqb = (p.rpg + 3) / 4;

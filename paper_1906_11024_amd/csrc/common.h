@@ -83,6 +83,33 @@ __device__ __forceinline__ void store4(bf16_t* p, float4 v) {
   *reinterpret_cast<uint2*>(p) = o;
 }
 
+// DPP moves inside a row of 16 lanes (no LDS traffic, unlike a bpermute shuffle).
+template <int CTRL> __device__ __forceinline__ float dpp_mov(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm [1,0,3,2]: lane ^ 1
+constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm [2,3,0,1]: lane ^ 2
+constexpr int kDppRowHalfMirror = 0x141; // lane i <-> 7 - i inside each 8 lanes
+constexpr int kDppRowMirror = 0x140;     // lane i <-> 15 - i inside each 16 lanes
+
+// Sum / max over aligned groups of N lanes (N = 2, 4, 8, 16); every lane of the
+// group gets the result.
+template <int N> __device__ __forceinline__ float group_sum(float v) {
+  static_assert(N == 1 || N == 2 || N == 4 || N == 8 || N == 16, "group size");
+  if (N >= 2) v += dpp_mov<kDppQuadSwap1>(v);
+  if (N >= 4) v += dpp_mov<kDppQuadSwap2>(v);
+  if (N >= 8) v += dpp_mov<kDppRowHalfMirror>(v);
+  if (N >= 16) v += dpp_mov<kDppRowMirror>(v);
+  return v;
+}
+template <int N> __device__ __forceinline__ float group_max(float v) {
+  if (N >= 2) v = fmaxf(v, dpp_mov<kDppQuadSwap1>(v));
+  if (N >= 4) v = fmaxf(v, dpp_mov<kDppQuadSwap2>(v));
+  if (N >= 8) v = fmaxf(v, dpp_mov<kDppRowHalfMirror>(v));
+  if (N >= 16) v = fmaxf(v, dpp_mov<kDppRowMirror>(v));
+  return v;
+}
+
 // Reductions over the lanes whose ids differ only in the bits of `mask_bits`
 // (a contiguous run of xor strides from `lo` up to, not including, `hi`).
 template <int LO, int HI> __device__ __forceinline__ float xor_sum(float v) {
@@ -90,11 +117,18 @@ template <int LO, int HI> __device__ __forceinline__ float xor_sum(float v) {
   for (int s = LO; s < HI; s <<= 1) v += __shfl_xor(v, s, kWave);
   return v;
 }
-__device__ __forceinline__ float wave_sum(float v) { return xor_sum<1, kWave>(v); }
+__device__ __forceinline__ float wave_sum(float v) { return xor_sum<16, kWave>(group_sum<16>(v)); }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int s = 1; s < kWave; s <<= 1) v = fmaxf(v, __shfl_xor(v, s, kWave));
+  v = group_max<16>(v);
+  v = fmaxf(v, __shfl_xor(v, 16, kWave));
+  v = fmaxf(v, __shfl_xor(v, 32, kWave));
   return v;
+}
+// sum over aligned groups of LPP lanes (LPP up to 32)
+template <int LPP> __device__ __forceinline__ float lanes_sum(float v) {
+  if (LPP <= 16) return group_sum<(LPP <= 16 ? LPP : 16)>(v);
+  v = group_sum<16>(v);
+  return v + __shfl_xor(v, 16, kWave);
 }
 
 }  // namespace san

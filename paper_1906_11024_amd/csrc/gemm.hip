@@ -1,13 +1,20 @@
 // Projection / FFN / output-layer GEMMs on CDNA4 matrix cores.
 //
 // out[m][n] = sum_k A[m][k] * W[n][k]: both operands are contiguous along k, so a
-// lane's MFMA operand fragment is one 16-byte load.  A block of 4 waves (2x2)
-// owns a (64*TM) x (64*TN) tile of the output; k is walked in chunks of 128 bytes
-// per row, staged global -> registers -> LDS (double buffered, rows padded to 144
-// bytes so that the 16-byte fragment reads of 16 neighbouring lanes hit all 64
-// banks once).  The weight rows feed the MFMA "A" side and the activation rows
-// the "B" side, so a lane ends up with 4 consecutive output columns of one
-// output row, which makes the epilogue's bias loads and stores 16-byte wide.
+// lane's MFMA operand fragment is one 16-byte load.  A block of WM x WN waves
+// owns a (32*WM*TM) x (32*WN*TN) tile of the output; k is walked in chunks of 128
+// bytes per row.  Decode-time GEMMs are small (M = batch*beam rows) and therefore
+// latency-bound, so the kernel is built to keep many loads in flight: a queue of
+// D chunks lives in registers (global loads issued D chunks ahead), each chunk is
+// then staged through one of two LDS buffers (rows padded to 144 bytes so that the
+// 16-byte fragment reads of 16 neighbouring lanes hit all 64 banks once), and
+// GEMMs with few output tiles are split along k across blocks: every block writes
+// fp32 partials, the last block to arrive at a tile (an atomic ticket) adds them
+// up in a fixed order -- so results do not depend on arrival order -- and runs the
+// epilogue (bias, ReLU, scatter into the q buffer / key cache / value cache).
+// The weight rows feed the MFMA "A" side and the activation rows the "B" side, so
+// a lane ends up with 4 consecutive output columns of one output row, which makes
+// the epilogue's bias loads and stores 16-byte wide.
 #include "common.h"
 #include "kernels.h"
 
@@ -15,75 +22,88 @@ namespace san {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte fragment as a first-class vector
 
 constexpr int kChunkBytes = 128;  // k-extent of one LDS stage, per row
 constexpr int kRowBytes = 144;    // padded LDS row
 
-template <typename T> __device__ __forceinline__ void mma_frag(f32x16& acc, const uint4& w, const uint4& x);
+template <typename T> __device__ __forceinline__ void mma_frag(f32x16& acc, const u32x4& w, const u32x4& x);
 
 // fp32: a 16-byte fragment is 4 k-values -> 4 rank-2 updates (32x32x2).  Lanes
 // 0-31 carry k = 0..3 of the 32-byte sub-step, lanes 32-63 carry k = 4..7; the
 // pairing of k-values inside an instruction is irrelevant as both operands use it.
-template <> __device__ __forceinline__ void mma_frag<float>(f32x16& acc, const uint4& w, const uint4& x) {
+template <> __device__ __forceinline__ void mma_frag<float>(f32x16& acc, const u32x4& w, const u32x4& x) {
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(w.x), __uint_as_float(x.x), acc, 0, 0, 0);
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(w.y), __uint_as_float(x.y), acc, 0, 0, 0);
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(w.z), __uint_as_float(x.z), acc, 0, 0, 0);
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(w.w), __uint_as_float(x.w), acc, 0, 0, 0);
 }
 // bf16: a 16-byte fragment is 8 k-values -> one 32x32x16 instruction.
-template <> __device__ __forceinline__ void mma_frag<bf16_t>(f32x16& acc, const uint4& w, const uint4& x) {
-  union U { uint4 u; bf16x8 b; };
-  U a, b;
-  a.u = w;
-  b.u = x;
-  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.b, b.b, acc, 0, 0, 0);
+template <> __device__ __forceinline__ void mma_frag<bf16_t>(f32x16& acc, const u32x4& w, const u32x4& x) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x), acc, 0, 0, 0);
 }
 
-template <typename T, int TM, int TN>
-__global__ __launch_bounds__(256) void gemm_kernel(GemmParams p) {
-  constexpr int BM = 64 * TM, BN = 64 * TN;
+template <typename T, int WM, int WN, int TM, int TN, int KW, int D>
+__global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
+  constexpr int NG = WM * WN * 64;                   // threads of one k-group
+  constexpr int BM = 32 * WM * TM, BN = 32 * WN * TN;
   constexpr int EPC = kChunkBytes / (int)sizeof(T);  // elements per chunk
-  constexpr int LA = BM / 32, LB = BN / 32;          // 16-byte loads per thread per chunk
+  constexpr int RPP = NG / 8;                        // rows covered by one pass of 16-byte loads
+  constexpr int LA = BM / RPP, LB = BN / RPP;        // 16-byte loads per thread per chunk
+  constexpr int STAGE = 2 * (BM + BN) * kRowBytes;   // LDS bytes of one k-group (double buffered)
+  static_assert(BM % RPP == 0 && BN % RPP == 0 && D % 2 == 0, "tile shape");
+  static_assert(KW == 1 || (KW - 1) * (WM * WN) * TM * TN * 16 * 64 * 4 <= KW * STAGE, "reduction fits the stages");
   extern __shared__ __align__(16) unsigned char smem[];
-  unsigned char* Xs = smem;                                // [2][BM][144]
-  unsigned char* Ws = smem + 2 * BM * kRowBytes;           // [2][BN][144]
+  __shared__ int s_last;
 
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
-  const int wm = wid & 1, wn = wid >> 1;
+  const int kg = wid / (WM * WN), w_in = wid % (WM * WN);   // k-group, wave inside the group
+  const int tg = tid % NG;
+  const int wm = w_in % WM, wn = w_in / WM;
   const int l32 = lane & 31, kh = lane >> 5;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  unsigned char* Xs = smem + kg * STAGE;           // [2][BM][144]
+  unsigned char* Ws = Xs + 2 * BM * kRowBytes;     // [2][BN][144]
 
   const int nchunks = p.K / EPC;
   const int cps = (nchunks + p.ksplit - 1) / p.ksplit;
   const int c_begin = blockIdx.z * cps;
   const int c_end = min(nchunks, c_begin + cps);
+  // inside the block the chunks are dealt round-robin to the KW k-groups; every
+  // group runs the same number of iterations so that the barriers line up
+  const int iters = (max(c_end - c_begin, 0) + KW - 1) / KW;
 
   const T* A = reinterpret_cast<const T*>(p.A);
   const T* W = reinterpret_cast<const T*>(p.W);
-  const int lrow = tid >> 3, lseg = tid & 7;  // this thread's row (0..31) and 16-byte segment of a chunk
+  const int lrow = tg >> 3, lseg = tg & 7;  // this thread's row and 16-byte segment of a chunk
+  const T* a_ptr[LA];
+  const T* w_ptr[LB];
+#pragma unroll
+  for (int i = 0; i < LA; ++i)
+    a_ptr[i] = A + (size_t)min(m0 + lrow + RPP * i, p.M - 1) * p.lda + lseg * (16 / sizeof(T));
+#pragma unroll
+  for (int i = 0; i < LB; ++i)
+    w_ptr[i] = W + (size_t)min(n0 + lrow + RPP * i, p.N - 1) * p.K + lseg * (16 / sizeof(T));
 
-  uint4 xa[LA], wb[LB];
-  auto load_global = [&](int c) {
-    const size_t koff = (size_t)c * EPC + lseg * (16 / sizeof(T));
-#pragma unroll
-    for (int i = 0; i < LA; ++i) {
-      const int m = min(m0 + lrow + 32 * i, p.M - 1);
-      xa[i] = *reinterpret_cast<const uint4*>(A + (size_t)m * p.lda + koff);
-    }
-#pragma unroll
-    for (int i = 0; i < LB; ++i) {
-      const int n = min(n0 + lrow + 32 * i, p.N - 1);
-      wb[i] = *reinterpret_cast<const uint4*>(W + (size_t)n * p.K + koff);
-    }
-  };
-  auto store_lds = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < LA; ++i)
-      *reinterpret_cast<uint4*>(Xs + (buf * BM + lrow + 32 * i) * kRowBytes + lseg * 16) = xa[i];
-#pragma unroll
-    for (int i = 0; i < LB; ++i)
-      *reinterpret_cast<uint4*>(Ws + (buf * BN + lrow + 32 * i) * kRowBytes + lseg * 16) = wb[i];
-  };
+  // Register queue of chunks in flight (macros, not lambdas, so that every index
+  // is a compile-time constant and the queue stays in registers).
+  u32x4 qa[D][LA], qw[D][LB];
+#define SAN_CHUNK(i_) (c_begin + kg + KW * (i_))
+#define SAN_LOAD_GLOBAL(c_, s_)                                                              \
+  do {                                                                                       \
+    const size_t koff_ = (size_t)(c_) * EPC;                                                 \
+    _Pragma("unroll") for (int i_ = 0; i_ < LA; ++i_)                                        \
+        qa[s_][i_] = *reinterpret_cast<const u32x4*>(a_ptr[i_] + koff_);                     \
+    _Pragma("unroll") for (int i_ = 0; i_ < LB; ++i_)                                        \
+        qw[s_][i_] = *reinterpret_cast<const u32x4*>(w_ptr[i_] + koff_);                     \
+  } while (0)
+#define SAN_STORE_LDS(buf_, s_)                                                              \
+  do {                                                                                       \
+    _Pragma("unroll") for (int i_ = 0; i_ < LA; ++i_)                                        \
+        *reinterpret_cast<u32x4*>(Xs + ((buf_) * BM + lrow + RPP * i_) * kRowBytes + lseg * 16) = qa[s_][i_]; \
+    _Pragma("unroll") for (int i_ = 0; i_ < LB; ++i_)                                        \
+        *reinterpret_cast<u32x4*>(Ws + ((buf_) * BN + lrow + RPP * i_) * kRowBytes + lseg * 16) = qw[s_][i_]; \
+  } while (0)
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -93,117 +113,219 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmParams p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  if (c_begin < c_end) {
-    load_global(c_begin);
-    store_lds(0);
-  }
-  __syncthreads();
-  for (int c = c_begin; c < c_end; ++c) {
-    const int buf = (c - c_begin) & 1;
-    if (c + 1 < c_end) load_global(c + 1);
-    const unsigned char* xs = Xs + (buf * BM + wm * 32 * TM + l32) * kRowBytes + kh * 16;
-    const unsigned char* ws = Ws + (buf * BN + wn * 32 * TN + l32) * kRowBytes + kh * 16;
 #pragma unroll
-    for (int sub = 0; sub < 4; ++sub) {
-      uint4 xf[TM], wf[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) xf[i] = *reinterpret_cast<const uint4*>(xs + i * 32 * kRowBytes + sub * 32);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) wf[j] = *reinterpret_cast<const uint4*>(ws + j * 32 * kRowBytes + sub * 32);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) mma_frag<T>(acc[i][j], wf[j], xf[i]);
-    }
-    if (c + 1 < c_end) store_lds(buf ^ 1);
-    __syncthreads();
-  }
+  for (int s = 0; s < D; ++s)
+    if (s < iters && SAN_CHUNK(s) < c_end) SAN_LOAD_GLOBAL(SAN_CHUNK(s), s);
 
-  // ---- epilogue.  acc[i][j][v]: output row m = tile_m + l32, column
-  // n = tile_n + (v/4)*8 + kh*4 + (v%4).
-  const int t = p.t_dev ? *p.t_dev : 0;
-  const T* bias = reinterpret_cast<const T*>(p.bias);
+  for (int ib = 0; ib < iters; ib += D) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int m = m0 + wm * 32 * TM + i * 32 + l32;
-    if (m >= p.M) continue;
+    for (int s = 0; s < D; ++s) {
+      const int it = ib + s;
+      if (it < iters) {
+        const bool live = SAN_CHUNK(it) < c_end;   // the last round may be short for some groups
+        const int buf = s & 1;                     // D is even, so iteration parity == slot parity
+        if (live) SAN_STORE_LDS(buf, s);           // waits for this chunk's loads only
+        if (it + D < iters && SAN_CHUNK(it + D) < c_end) SAN_LOAD_GLOBAL(SAN_CHUNK(it + D), s);
+        __syncthreads();                           // one barrier per round: the other buffer is still being read
+        if (live) {
+          const unsigned char* xs = Xs + (buf * BM + wm * 32 * TM + l32) * kRowBytes + kh * 16;
+          const unsigned char* ws = Ws + (buf * BN + wn * 32 * TN + l32) * kRowBytes + kh * 16;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
+          for (int sub = 0; sub < 4; ++sub) {
+            u32x4 xf[TM], wf[TN];
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n = n0 + wn * 32 * TN + j * 32 + g * 8 + kh * 4;
-        if (n >= p.N) continue;
-        float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-        if (p.out_kind == 2) {
-          float* dst = reinterpret_cast<float*>(p.out[0]) + ((size_t)blockIdx.z * p.M + m) * p.N + n;
-          if (n + 3 < p.N) {
-            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-          } else {
-            for (int e = 0; e < 4 && n + e < p.N; ++e) dst[e] = v[e];
-          }
-          continue;
-        }
-        const bool full = (n + 3 < p.N);
-        if (bias) {
-          for (int e = 0; e < 4; ++e)
-            if (n + e < p.N) v[e] += to_f32(bias[n + e]);
-        }
-        if (p.relu) {
-          for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
-        }
-        const int s = n / p.seg_w;       // segments are multiples of 4 columns wide
-        const int nn = n - s * p.seg_w;
-        const size_t off = (size_t)t * p.tstride[s] + (size_t)m * p.ldo[s] + nn;
-        if (p.out_kind == 1) {
-          float* dst = reinterpret_cast<float*>(p.out[s]) + off;
-          if (full) {
-            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-          } else {
-            for (int e = 0; e < 4 && n + e < p.N; ++e) dst[e] = v[e];
-          }
-        } else {
-          T* dst = reinterpret_cast<T*>(p.out[s]) + off;
-          if (full) {
-            store4(dst, make_float4(v[0], v[1], v[2], v[3]));
-          } else {
-            for (int e = 0; e < 4 && n + e < p.N; ++e) dst[e] = from_f32<T>(v[e]);
+            for (int i = 0; i < TM; ++i) xf[i] = *reinterpret_cast<const u32x4*>(xs + i * 32 * kRowBytes + sub * 32);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) wf[j] = *reinterpret_cast<const u32x4*>(ws + j * 32 * kRowBytes + sub * 32);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+              for (int j = 0; j < TN; ++j) mma_frag<T>(acc[i][j], wf[j], xf[i]);
           }
         }
       }
     }
   }
+#undef SAN_CHUNK
+#undef SAN_LOAD_GLOBAL
+#undef SAN_STORE_LDS
+
+  if (KW > 1) {
+    // ---- add up the k-groups through LDS, in group order (deterministic)
+    __syncthreads();   // all stages are dead now
+    float* red = reinterpret_cast<float*>(smem);   // [KW-1][waves per group][TM*TN*16][64]
+    if (kg > 0) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            red[((((kg - 1) * (WM * WN) + w_in) * (TM * TN) + i * TN + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+    }
+    __syncthreads();
+    if (kg > 0) return;
+#pragma unroll
+    for (int g = 1; g < KW; ++g)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            acc[i][j][v] += red[((((g - 1) * (WM * WN) + w_in) * (TM * TN) + i * TN + j) * 16 + v) * 64 + lane];
+  }
+
+  // acc[i][j][v]: output row m = tile_m + l32, column n = tile_n + (v/4)*8 + kh*4 + (v%4).
+  const bool n_vec = (p.N % 4) == 0;
+  if (p.out_kind == 2 || p.ksplit > 1) {
+    // ---- fp32 partials [ksplit][M][N]
+    float* part = p.out_kind == 2 ? reinterpret_cast<float*>(p.out[0]) : p.part;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int m = m0 + (wm * TM + i) * 32 + l32;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n = n0 + (wn * TN + j) * 32 + g * 8 + kh * 4;
+          if (m < p.M && n < p.N) {
+            float* dst = part + ((size_t)blockIdx.z * p.M + m) * p.N + n;
+            if (n_vec) {
+              *reinterpret_cast<float4*>(dst) =
+                  make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+            } else {
+              _Pragma("unroll") for (int e = 0; e < 4; ++e) if (n + e < p.N) dst[e] = acc[i][j][4 * g + e];
+            }
+          }
+        }
+    }
+    if (p.out_kind == 2) return;
+    // ---- ticket: the last block of this tile reduces and runs the epilogue
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+      int* cnt = p.counters + blockIdx.y * gridDim.x + blockIdx.x;
+      const int old = atomicAdd(cnt, 1);
+      const int last = (old == p.ksplit - 1);
+      if (last) *cnt = 0;   // ready for the next launch
+      s_last = last;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int m = m0 + (wm * TM + i) * 32 + l32;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n = n0 + (wn * TN + j) * 32 + g * 8 + kh * 4;
+          float s4[4] = {0.f, 0.f, 0.f, 0.f};
+          if (m < p.M && n < p.N) {
+            for (int z = 0; z < p.ksplit; ++z) {   // fixed order: deterministic sums
+              const float* src = part + ((size_t)z * p.M + m) * p.N + n;
+              if (n_vec) {
+                const float4 v = *reinterpret_cast<const float4*>(src);
+                s4[0] += v.x; s4[1] += v.y; s4[2] += v.z; s4[3] += v.w;
+              } else {
+                _Pragma("unroll") for (int e = 0; e < 4; ++e) if (n + e < p.N) s4[e] += src[e];
+              }
+            }
+          }
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] = s4[e];
+        }
+    }
+  }
+
+  // ---- epilogue: bias, ReLU, scatter into up to three column segments
+  const int t = p.t_dev ? *p.t_dev : 0;
+  const T* bias = reinterpret_cast<const T*>(p.bias);
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = m0 + (wm * TM + i) * 32 + l32;
+    if (m >= p.M) continue;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n = n0 + (wn * TN + j) * 32 + g * 8 + kh * 4;
+        if (n >= p.N) continue;
+        float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        const bool full = (n + 3 < p.N);
+        if (bias) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (n + e < p.N) v[e] += to_f32(bias[n + e]);
+        }
+        if (p.relu) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+        }
+        const int s = n / p.seg_w;   // segments are multiples of 4 columns wide
+        const int nn = n - s * p.seg_w;
+        void* obase = s == 0 ? p.out[0] : (s == 1 ? p.out[1] : p.out[2]);
+        const int ldo = s == 0 ? p.ldo[0] : (s == 1 ? p.ldo[1] : p.ldo[2]);
+        const long long ts = s == 0 ? p.tstride[0] : (s == 1 ? p.tstride[1] : p.tstride[2]);
+        const size_t off = (size_t)t * ts + (size_t)m * ldo + nn;
+        if (p.out_kind == 1) {
+          float* dst = reinterpret_cast<float*>(obase) + off;
+          if (full && n_vec) {
+            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+          } else {
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) if (n + e < p.N) dst[e] = v[e];
+          }
+        } else {
+          T* dst = reinterpret_cast<T*>(obase) + off;
+          if (full && n_vec) {
+            store4(dst, make_float4(v[0], v[1], v[2], v[3]));
+          } else {
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) if (n + e < p.N) dst[e] = from_f32<T>(v[e]);
+          }
+        }
+      }
+    }
+  }
+  // exactly one block per tile gets here (the only one, or the last of a split)
+  if (p.bump && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *p.bump = *p.bump + 1;
 }
 
-template <typename T, int TM, int TN> static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
-  constexpr int BM = 64 * TM, BN = 64 * TN;
+template <typename T, int WM, int WN, int TM, int TN, int KW, int D>
+static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
+  constexpr int BM = 32 * WM * TM, BN = 32 * WN * TN;
   dim3 grid((p.N + BN - 1) / BN, (p.M + BM - 1) / BM, p.ksplit);
-  const size_t smem = 2 * (BM + BN) * kRowBytes;
+  const size_t smem = (size_t)KW * 2 * (BM + BN) * kRowBytes;
+  if (KW > 1 && p.ksplit > 1 && p.out_kind != 2) return hipErrorInvalidValue;  // ticket path is single-group
   if (smem > 64 * 1024) {
     static bool raised = false;   // the limit is a per-function attribute; set it once
     if (!raised) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, TM, TN>),
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, WM, WN, TM, TN, KW, D>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
       if (e != hipSuccess) return e;
       raised = true;
     }
   }
-  hipLaunchKernelGGL((gemm_kernel<T, TM, TN>), grid, dim3(256), smem, stream, p);
+  hipLaunchKernelGGL((gemm_kernel<T, WM, WN, TM, TN, KW, D>), grid, dim3(WM * WN * KW * 64), smem, stream, p);
   return hipGetLastError();
 }
 
-static int pick_tile(int M, int N) {
-  // 128x128 tiles only when they still give every CU at least ~2 blocks.
-  const long blocks128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-  return blocks128 >= 512 ? 2 : 1;
+// Tile choice: 0 = 64x64 (2x2 waves), 1 = 128x128 (2x2 waves, 2x2 tiles each),
+// 2 = 256x64 (4x1 waves: every weight row is fetched by one block only).
+int gemm_pick_tile(int M, int N) {
+  if (M >= 256 && (long)((M + 255) / 256) * ((N + 63) / 64) >= 256) return 2;
+  return 0;
 }
 
 int gemm_pick_ksplit(int M, int N, int K, int dtype) {
+  if (gemm_pick_tile(M, N) != 0) return 1;
   const int epc = dtype == 1 ? 64 : 32;
   const int nchunks = K / epc;
   const long blocks = (long)((M + 63) / 64) * ((N + 63) / 64);
   int ks = 1;
-  // aim for >= 256 blocks (one per CU), keep at least 4 chunks of k per block
-  while (blocks * ks < 256 && nchunks / (ks * 2) >= 4 && ks < 16) ks *= 2;
+  // aim for >= 256 blocks (one per CU), keep at least 2 chunks of k per block
+  while (blocks * ks < 256 && nchunks / (ks * 2) >= 2 && ks < 16) ks *= 2;
   return ks;
 }
 
@@ -211,11 +333,34 @@ hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
   if (p.M <= 0 || p.N <= 0) return hipSuccess;
   const int epc = dtype == 1 ? 64 : 32;
   if (p.K <= 0 || p.K % epc != 0 || p.ksplit < 1 || p.seg_w % 4 != 0) return hipErrorInvalidValue;
-  const int tile = pick_tile(p.M, p.N);
-  if (dtype == 1) {
-    return tile == 2 ? launch_tile<bf16_t, 2, 2>(p, stream) : launch_tile<bf16_t, 1, 1>(p, stream);
+  const bool ticket = p.ksplit > 1 && p.out_kind != 2;
+  if (ticket) {
+    const long tiles = (long)((p.M + 63) / 64) * ((p.N + 63) / 64);
+    if (!p.part || !p.counters || tiles > kGemmCounters) return hipErrorInvalidValue;
   }
-  return tile == 2 ? launch_tile<float, 2, 2>(p, stream) : launch_tile<float, 1, 1>(p, stream);
+  const int tile = p.ksplit > 1 ? 0 : gemm_pick_tile(p.M, p.N);
+  // A wave's MFMA chain over the whole k range is what bounds a small GEMM, and
+  // only waves on different SIMDs run their chains in parallel.  When 64x64 tiles
+  // would leave most SIMDs idle, use smaller tiles and deal each tile's k range to
+  // 2 or 4 wave groups (reduced through LDS), aiming at ~one wave per SIMD:
+  //   shape 1: 64x32 tiles, 2 waves x 2 k-groups;  shape 2: 32x32 tiles, 1 wave x 4 k-groups.
+  const int chunks = (p.K / epc + p.ksplit - 1) / p.ksplit;
+  const long tiles64 = (long)((p.M + 63) / 64) * ((p.N + 63) / 64) * p.ksplit;
+  int shape = 0;
+  if (tile == 0 && !ticket) {
+    if (tiles64 <= 64 && chunks >= 8) shape = 2;
+    else if (tiles64 <= 192 && chunks >= 4) shape = 1;
+  }
+  if (dtype == 1) {
+    if (tile == 2) return launch_tile<bf16_t, 4, 1, 2, 2, 1, 2>(p, stream);
+    if (shape == 2) return launch_tile<bf16_t, 1, 1, 1, 1, 4, 4>(p, stream);
+    if (shape == 1) return launch_tile<bf16_t, 2, 1, 1, 1, 2, 4>(p, stream);
+    return launch_tile<bf16_t, 2, 2, 1, 1, 1, 4>(p, stream);
+  }
+  if (tile == 2) return launch_tile<float, 4, 1, 2, 2, 1, 2>(p, stream);
+  if (shape == 2) return launch_tile<float, 1, 1, 1, 1, 4, 4>(p, stream);
+  if (shape == 1) return launch_tile<float, 2, 1, 1, 1, 2, 4>(p, stream);
+  return launch_tile<float, 2, 2, 1, 1, 1, 4>(p, stream);
 }
 
 }  // namespace san

@@ -13,6 +13,11 @@ namespace san {
 // out[s] + (*t_dev) * tstride[s] + m * ldo[s] + (n - s*seg_w).
 //   out_kind 0: store as T;  1: store fp32;  2: fp32 split-K partials
 //   [ksplit][M][N] at out[0] (no bias, no ReLU; the consumer reduces them).
+//   ksplit > 1 with out_kind 0/1: the blocks of a tile write partials to `part`
+//   ([ksplit][M][N] fp32) and the last one to arrive (ticket in `counters`, one
+//   int per 64x64 tile, all zero between launches) reduces them and stores.
+//   bump: if not null, *bump is incremented once by the kernel (step counter).
+constexpr int kGemmCounters = 4096;
 struct GemmParams {
   const void* A; int lda;
   const void* W;              // [N][K]
@@ -20,11 +25,13 @@ struct GemmParams {
   void* out[3]; int ldo[3]; long long tstride[3];
   int seg_w;
   const int* t_dev;           // nullptr: no step offset
+  float* part; int* counters; int* bump;
   int M, N, K;                // K % (128 / sizeof(T)) == 0
   int relu, out_kind, ksplit;
 };
 hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream);
-// tile edge (rows of A per block) the launcher would pick; used to size split-K
+// split factor that fills the chip for an M x N x K product (1 when the tiles
+// alone already do)
 int gemm_pick_ksplit(int M, int N, int K, int dtype);
 
 // ------------------------------------------------------------------ attention
@@ -61,8 +68,11 @@ hipError_t launch_attention(int dtype, const AttnParams& p, hipStream_t stream);
 // ------------------------------------------------------------------ row-wise
 // x[r] = emb[clamp(tok)] * scale + pe[pos]; row r = hyp*rpg + i reads token
 // tok[hyp*tok_stride + i]; pos = *t_dev when t_dev != nullptr, else i.
+// With last_tok / anc given (cached decoding, rpg == 1) the kernel also does the
+// step's bookkeeping: last_tok[r] = tok[r], anc[r*ld_anc + t] = r.
 hipError_t launch_embed(int dtype, const int* tok, int tok_stride, int rpg, const void* emb, const float* pe,
-                        const int* t_dev, void* x, int rows, int d, int vocab, float scale, hipStream_t stream);
+                        const int* t_dev, void* x, int rows, int d, int vocab, float scale, int* last_tok,
+                        int* anc, int ld_anc, hipStream_t stream);
 
 // out[m] = LayerNorm(sum_s part[s][m] + bias + res[m]) * g + b  (row-wise over n)
 hipError_t launch_ln_reduce(int dtype, const float* part, int nsplit, const void* bias, const void* res, int ldr,

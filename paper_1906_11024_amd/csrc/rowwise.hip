@@ -11,13 +11,17 @@ namespace san {
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const int* tok, int tok_stride, int rpg, const T* emb,
                                                     const float* pe, const int* t_dev, T* x, int rows, int d,
-                                                    int vocab, float scale) {
+                                                    int vocab, float scale, int* last_tok, int* anc, int ld_anc) {
   const int r = blockIdx.x;
   if (r >= rows) return;
   const int hyp = r / rpg, i = r % rpg;
   int id = tok[(size_t)hyp * tok_stride + i];
-  id = min(max(id, 0), vocab - 1);
   const int pos = t_dev ? *t_dev : i;
+  if (threadIdx.x == 0) {
+    if (last_tok) last_tok[r] = id;
+    if (anc && pos < ld_anc) anc[(size_t)r * ld_anc + pos] = r;
+  }
+  id = min(max(id, 0), vocab - 1);
   const T* e = emb + (size_t)id * d;
   const float* pp = pe + (size_t)pos * d;
   for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
@@ -30,15 +34,16 @@ __global__ __launch_bounds__(256) void embed_kernel(const int* tok, int tok_stri
 }
 
 hipError_t launch_embed(int dtype, const int* tok, int tok_stride, int rpg, const void* emb, const float* pe,
-                        const int* t_dev, void* x, int rows, int d, int vocab, float scale, hipStream_t stream) {
+                        const int* t_dev, void* x, int rows, int d, int vocab, float scale, int* last_tok,
+                        int* anc, int ld_anc, hipStream_t stream) {
   if (rows <= 0) return hipSuccess;
   const int threads = d / 4 >= 256 ? 256 : (d / 4 >= 128 ? 128 : 64);
   if (dtype == 1)
     hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(rows), dim3(threads), 0, stream, tok, tok_stride, rpg,
-                       (const bf16_t*)emb, pe, t_dev, (bf16_t*)x, rows, d, vocab, scale);
+                       (const bf16_t*)emb, pe, t_dev, (bf16_t*)x, rows, d, vocab, scale, last_tok, anc, ld_anc);
   else
     hipLaunchKernelGGL(embed_kernel<float>, dim3(rows), dim3(threads), 0, stream, tok, tok_stride, rpg,
-                       (const float*)emb, pe, t_dev, (float*)x, rows, d, vocab, scale);
+                       (const float*)emb, pe, t_dev, (float*)x, rows, d, vocab, scale, last_tok, anc, ld_anc);
   return hipGetLastError();
 }
 
@@ -93,20 +98,27 @@ __global__ __launch_bounds__(256) void ln_reduce_kernel(const float* part, int n
   for (int it = 0; it < kLnMaxIter; ++it) {
     const int c = it * 256 + lane * 4;
     if (c < n) {
+      // bias and residual first, then the partials four at a time: all of these
+      // loads are independent, so they overlap instead of queueing up one by one
       float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-      for (int s = 0; s < nsplit; ++s) {
-        const float4 pv = *reinterpret_cast<const float4*>(part + ((size_t)s * M + m) * n + c);
-        a.x += pv.x; a.y += pv.y; a.z += pv.z; a.w += pv.w;
-      }
-      if (bias) {
-        const float4 bv = load4(bias + c);
-        a.x += bv.x; a.y += bv.y; a.z += bv.z; a.w += bv.w;
-      }
+      if (bias) a = load4(bias + c);
       if (res) {
         const float4 rv = load4(res + (size_t)m * ldr + c);
         a.x += rv.x; a.y += rv.y; a.z += rv.z; a.w += rv.w;
       }
-      v[it][0] = a.x; v[it][1] = a.y; v[it][2] = a.z; v[it][3] = a.w;
+      float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+      const float* pp = part + (size_t)m * n + c;
+      const size_t ps = (size_t)M * n;
+      for (int s = 0; s < nsplit; s += 4) {
+        float4 pv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          pv[u] = (s + u < nsplit) ? *reinterpret_cast<const float4*>(pp + (size_t)(s + u) * ps)
+                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { sum.x += pv[u].x; sum.y += pv[u].y; sum.z += pv[u].z; sum.w += pv[u].w; }
+      }
+      v[it][0] = sum.x + a.x; v[it][1] = sum.y + a.y; v[it][2] = sum.z + a.z; v[it][3] = sum.w + a.w;
     }
   }
   layer_norm_row<T>(v, n, lane, gamma, beta, eps, out + (size_t)m * ldo, out_f32 ? out_f32 + (size_t)m * n : nullptr);

@@ -61,6 +61,7 @@ struct san_ctx {
   void *x = nullptr, *qkv = nullptr, *ab = nullptr, *hb = nullptr, *cat = nullptr;
   float* part = nullptr;
   size_t part_elems = 0;
+  int* counters = nullptr;   // split-K tickets, all zero between launches
   int *t_dev = nullptr, *anc = nullptr, *hist = nullptr, *last_tok = nullptr, *src_len = nullptr;
   float* cand_lp = nullptr;
   int* cand_idx = nullptr;
@@ -234,7 +235,8 @@ int wtensor(san_ctx* c, void** dst, const void* blob, size_t off, size_t n) {
 // ------------------------------------------------------------ kernel plumbing
 int gemm(san_ctx* c, const void* A, int lda, const void* W, const void* bias, int M, int N, int K, int relu,
          int out_kind, void* o0, int ld0, long long ts0 = 0, void* o1 = nullptr, int ld1 = 0, long long ts1 = 0,
-         void* o2 = nullptr, int ld2 = 0, long long ts2 = 0, int seg_w = 0, bool use_t = false, int ksplit = 1) {
+         void* o2 = nullptr, int ld2 = 0, long long ts2 = 0, int seg_w = 0, bool use_t = false, int ksplit = 0,
+         bool bump = false) {
   GemmParams p{};
   p.A = A; p.lda = lda; p.W = W; p.bias = bias;
   p.out[0] = o0; p.out[1] = o1; p.out[2] = o2;
@@ -242,7 +244,11 @@ int gemm(san_ctx* c, const void* A, int lda, const void* W, const void* bias, in
   p.tstride[0] = ts0; p.tstride[1] = ts1; p.tstride[2] = ts2;
   p.seg_w = seg_w > 0 ? seg_w : (1 << 30);
   p.t_dev = use_t ? c->t_dev : nullptr;
-  p.M = M; p.N = N; p.K = K; p.relu = relu; p.out_kind = out_kind; p.ksplit = ksplit;
+  p.bump = bump ? c->t_dev : nullptr;
+  p.M = M; p.N = N; p.K = K; p.relu = relu; p.out_kind = out_kind;
+  if (ksplit == 0) ksplit = 1;
+  p.ksplit = ksplit;
+  p.part = c->part; p.counters = c->counters;
   LAUNCH(c, launch_gemm(c->dt, p, c->stream));
   return SAN_OK;
 }
@@ -421,6 +427,8 @@ static int build_ctx(san_ctx* c, const Blob& bl, const void* blob, const std::ve
     c->part_elems = mrows * 2 * d;
     if (c->part_elems < (size_t)4 << 20) c->part_elems = (size_t)4 << 20;
     TRY(dalloc(c, (void**)&c->part, c->part_elems * 4, false));
+    TRY(dalloc(c, (void**)&c->counters, kGemmCounters * 4, false));
+    HIP_TRY(c, hipMemset(c->counters, 0, kGemmCounters * 4));
     TRY(dalloc(c, (void**)&c->t_dev, 256, false));
     TRY(dalloc(c, (void**)&c->anc, (size_t)c->rows_max * T * 4, false));
     if (nocache) TRY(dalloc(c, (void**)&c->hist, (size_t)c->rows_max * T * 4, false));
@@ -502,7 +510,7 @@ int san_encode(san_ctx* c, const int32_t* src_ids_dev, const int32_t* src_len_de
   c->kind = SAN_K_MISC;
   HIP_TRY(c, hipMemcpyAsync(c->src_len, src_len_dev, (size_t)batch * 4, hipMemcpyDeviceToDevice, c->stream));
   LAUNCH(c, launch_embed(c->dt, src_ids_dev, max_src, max_src, c->src_emb, c->pe, nullptr, c->x, Ms, d, c->V,
-                         (float)std::sqrt((double)d), c->stream));
+                         (float)std::sqrt((double)d), nullptr, nullptr, 0, c->stream));
   for (const EncLayer& e : c->enc) {
     if ((rc = gemm(c, c->x, d, e.wqkv, e.bqkv, Ms, 3 * d, d, 0, 0, c->qkv, 3 * d))) return rc;
     AttnParams a{};
@@ -544,9 +552,8 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
   const long long slab = (long long)B * d;   // cache elements per position
   int rc;
   c->kind = SAN_K_MISC;
-  LAUNCH(c, launch_step_begin(tokens, c->last_tok, c->anc, nullptr, T, c->t_dev, B, c->stream));
   LAUNCH(c, launch_embed(c->dt, tokens, 1, 1, c->tgt_emb, c->pe, c->t_dev, c->x, B, d, c->V,
-                         (float)std::sqrt((double)d), c->stream));
+                         (float)std::sqrt((double)d), c->last_tok, c->anc, T, c->stream));
   const int Ld = (int)c->dec.size();
   for (int n = 0; n < Ld; ++n) {
     DecLayer& L = c->dec[n];
@@ -556,7 +563,9 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
       if ((rc = gemm(c, c->ab, d, L.aw1, L.ab1, B, c->F, d, 1, 0, c->hb, c->F))) return rc;
       // g goes to the right half of [x ; g]
       if ((rc = gemm(c, c->hb, c->F, L.aw2, L.ab2, B, d, c->F, 0, 0, (char*)c->cat + (size_t)d * c->esz, 2 * d))) return rc;
-      if ((rc = gemm(c, c->cat, 2 * d, L.awg, nullptr, B, 2 * d, 2 * d, 0, 2, c->part, 2 * d))) return rc;
+      if ((rc = gemm(c, c->cat, 2 * d, L.awg, nullptr, B, 2 * d, 2 * d, 0, 2, c->part, 2 * d, 0, nullptr, 0, 0, nullptr, 0, 0,
+                     0, false, 1)))
+        return rc;
       LAUNCH(c, launch_aan_post(c->dt, c->part, L.abg, c->cat, L.ln1g, L.ln1b, c->x, L.dbg_A_self, B, d,
                                 c->cfg.ln_eps, c->stream));
     } else {
@@ -622,7 +631,8 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
     if ((rc = ffn_block(c, &L, nullptr, B, L.dbg_hidden))) return rc;
   }
   c->kind = SAN_K_LOGITS;
-  return gemm(c, c->x, d, c->w_out, nullptr, B, c->V, d, 0, 1, logits, c->V);
+  return gemm(c, c->x, d, c->w_out, nullptr, B, c->V, d, 0, 1, logits, c->V, 0, nullptr, 0, 0, nullptr, 0, 0, 0, false,
+              0, true);
 }
 
 // Nothing cached: every position of every hypothesis is recomputed (rows =
@@ -636,7 +646,7 @@ static int decode_uncached(san_ctx* c, const int32_t* tokens, float* logits) {
   c->kind = SAN_K_MISC;
   LAUNCH(c, launch_step_begin(tokens, c->last_tok, nullptr, c->hist, T, c->t_dev, B, c->stream));
   LAUNCH(c, launch_embed(c->dt, c->hist, T, np, c->tgt_emb, c->pe, nullptr, c->x, M, d, c->V,
-                         (float)std::sqrt((double)d), c->stream));
+                         (float)std::sqrt((double)d), nullptr, nullptr, 0, c->stream));
   const int Ld = (int)c->dec.size();
   for (int n = 0; n < Ld; ++n) {
     DecLayer& L = c->dec[n];
@@ -697,7 +707,7 @@ static int decode_uncached(san_ctx* c, const int32_t* tokens, float* logits) {
   // logits of the last position of every hypothesis
   c->kind = SAN_K_LOGITS;
   return gemm(c, (char*)c->x + (size_t)(np - 1) * d * c->esz, np * d, c->w_out, nullptr, B, c->V, d, 0, 1, logits,
-              c->V);
+              c->V, 0, nullptr, 0, 0, nullptr, 0, 0, 0, false, 0, true);
 }
 
 int san_decode_step(san_ctx* c, const int32_t* tokens_dev, float* logits_dev) {
@@ -708,9 +718,7 @@ int san_decode_step(san_ctx* c, const int32_t* tokens_dev, float* logits_dev) {
   c->launches = 0;
   int rc = c->cfg.use_cache ? decode_cached(c, tokens_dev, logits_dev) : decode_uncached(c, tokens_dev, logits_dev);
   if (rc) return rc;
-  c->kind = SAN_K_MISC;
-  LAUNCH(c, launch_bump(c->t_dev, c->stream));
-  c->t += 1;
+  c->t += 1;   // the device-side counter was advanced by the output-layer kernel
   return prof_flush(c);
 }
 
