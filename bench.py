@@ -26,6 +26,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+# HBM bytes per launch (fetch + write) of the dominant attention kernel, from two
+# rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE) of this script with
+# --calib-copy-mb 512, each scaled by what the same counter reads for that plain
+# 512 MiB copy (FETCH_SIZE x2.000, WRITE_SIZE x1.000); see profiles/.
+MEASURED_TRAFFIC = {"base": {"attn_self": 34.91e6 + 0.82e6}}
 
 
 def parse():
@@ -38,6 +43,9 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--cpu-steps", type=int, default=16)
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="also run one plain device-to-device copy of this many MiB (a kernel of known "
+                         "traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -158,14 +166,26 @@ def main():
     launches = gpu.last_launch_count
 
     # ------------------------------------------------ per-kernel pass (HIP events)
+    # Second, identical pass over one decode with every launch bracketed by event
+    # markers on the library's stream.  A marker pair costs about 2 us of stream
+    # time per launch; that cost is estimated as (sum of bracketed times - unmarked
+    # wall time of the same decode) / launches and taken off every launch, so that
+    # the per-kernel figures add up to the unmarked step time (the decode is
+    # GPU-bound: kernels run back to back).  rocprofv3 --kernel-trace gives the
+    # same per-kernel averages (profiles/).
     kernels, roofline = {}, None
     if not args.no_profile:
+        wall_T = run.timed(T, 0)          # unmarked time of exactly one decode
         run.pos = 0
         gpu.profile(True)
         gpu.profile_read(reset=True)
         run.steps(T)
         prof = gpu.profile_read(reset=True)
         gpu.profile(False)
+        raw_ms = sum(ms for ms, n in prof.values())
+        n_pairs = sum(n for ms, n in prof.values())
+        marker_us = max(0.0, (raw_ms - wall_T * 1e3) / n_pairs * 1e3)
+        prof = {k: (max(ms - n * marker_us * 1e-3, 0.0), n) for k, (ms, n) in prof.items()}
         aan = cfg["self_kind"] == "aan"
         hs, fs = (0, 0) if aan else heads(cfg["self_pi"])
         hc, fc = heads(cfg["encdec_pi"])
@@ -185,10 +205,12 @@ def main():
         key = "attn_ctx" if aan else "attn_self"
         ms, n = prof[key]
         achieved = ab[key] / (ms * 1e-3) / 1e9
+        traffic = MEASURED_TRAFFIC.get(args.config, {}).get(key)
         roofline = {"kernel": "attention_kernel (block-head " + ("enc-dec" if aan else "self") + " attention)",
                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                    "bytes_per_launch": ab[key] / n, "avg_launch_us": ms / n * 1e3, "launches": n}
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                    "bytes_per_launch": ab[key] / n, "avg_launch_us": ms / n * 1e3, "launches": n,
+                    "event_marker_us_removed_per_launch": marker_us}
     gpu.close()
     del run
 
@@ -241,6 +263,15 @@ def main():
                "sample": f"first {ksteps} of {T} decode steps of the same batch ({cfg['batch']} sentences x beam "
                          f"{cfg['beam']}), numpy fp64; early steps have short caches, so this flatters the CPU",
                "ms_per_step": cw / ksteps * 1e3}
+
+    if args.calib_copy_mb:
+        n = args.calib_copy_mb * (1 << 20) // 4
+        a = torch.ones(n, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
 
     out = {
         "metric": "decoded tokens/sec (batch x beam rows per step)", "value": tok_per_s, "unit": "tokens/s",

@@ -194,7 +194,8 @@ enum {
  * context queues is bracketed by a pair of HIP events on the context's stream and
  * each API call ends with a stream synchronisation (so: not for production
  * loops).  san_profile_read adds up, per class, the elapsed milliseconds and
- * the number of launches since the last reset.
+ * the number of launches since the last reset.  The markers themselves cost
+ * about 2 us per bracketed launch, included in the figures.
  *   ms_out HOST double[SAN_K_COUNT], launches_out HOST int64[SAN_K_COUNT]
  *   (either may be NULL). */
 SAN_API int san_profile(san_ctx* ctx, int32_t enable);

@@ -162,6 +162,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
       }
     }
     wave_lds_sync();
+    if (CH < n) load_chunk(Vp, p.ldv, CH, vb1);   // second V chunk travels during the softmax
     // ---- softmax over key positions, one query at a time
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
@@ -188,6 +189,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
         for (int j = n + lane; j < p.ldS; j += kWave) Sg[j] = 0.f;
     }
   } else {
+    if (CH < n) load_chunk(Vp, p.ldv, CH, vb1);
     // ---- shared weights: S^{m+i} = S^m (Eq. 4)
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
@@ -220,12 +222,12 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
       }
     }
   };
-  for (int j0 = 0; j0 < n; j0 += 2 * CH) {
-    if (j0 + CH < n) load_chunk(Vp, p.ldv, j0 + CH, vb1);
+  for (int j0 = 0; j0 < n; j0 += 2 * CH) {   // V chunks are requested two chunks ahead
     weighted(j0, vb0);
+    if (j0 + 2 * CH < n) load_chunk(Vp, p.ldv, j0 + 2 * CH, vb0);
     if (j0 + CH < n) {
-      if (j0 + 2 * CH < n) load_chunk(Vp, p.ldv, j0 + 2 * CH, vb0);
       weighted(j0 + CH, vb1);
+      if (j0 + 3 * CH < n) load_chunk(Vp, p.ldv, j0 + 3 * CH, vb1);
     }
   }
 #pragma unroll

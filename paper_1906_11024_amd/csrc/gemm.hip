@@ -311,10 +311,11 @@ static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
   return hipGetLastError();
 }
 
-// Tile choice: 0 = 64x64 (2x2 waves), 1 = 128x128 (2x2 waves, 2x2 tiles each),
-// 2 = 256x64 (4x1 waves: every weight row is fetched by one block only).
+// Tile choice: 0 = 64x64 or smaller (2x2 waves and the k-group shapes below),
+// 1 = 128x128 (2x2 waves, 2x2 MFMA tiles each) once that still gives ~one block
+// per CU; measured best of {256x64, 128x64, 128x128, 256x128} on the output layer.
 int gemm_pick_tile(int M, int N) {
-  if (M >= 256 && (long)((M + 255) / 256) * ((N + 63) / 64) >= 256) return 2;
+  if (M >= 128 && (long)((M + 127) / 128) * ((N + 127) / 128) >= 200) return 1;
   return 0;
 }
 
@@ -352,12 +353,12 @@ hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
     else if (tiles64 <= 192 && chunks >= 4) shape = 1;
   }
   if (dtype == 1) {
-    if (tile == 2) return launch_tile<bf16_t, 4, 1, 2, 2, 1, 2>(p, stream);
+    if (tile == 1) return launch_tile<bf16_t, 2, 2, 2, 2, 1, 2>(p, stream);
     if (shape == 2) return launch_tile<bf16_t, 1, 1, 1, 1, 4, 4>(p, stream);
     if (shape == 1) return launch_tile<bf16_t, 2, 1, 1, 1, 2, 4>(p, stream);
     return launch_tile<bf16_t, 2, 2, 1, 1, 1, 4>(p, stream);
   }
-  if (tile == 2) return launch_tile<float, 4, 1, 2, 2, 1, 2>(p, stream);
+  if (tile == 1) return launch_tile<float, 2, 2, 2, 2, 1, 2>(p, stream);
   if (shape == 2) return launch_tile<float, 1, 1, 1, 1, 4, 4>(p, stream);
   if (shape == 1) return launch_tile<float, 2, 1, 1, 1, 2, 4>(p, stream);
   return launch_tile<float, 2, 2, 1, 1, 1, 4>(p, stream);

@@ -53,6 +53,13 @@ constexpr int kLnMaxIter = 8;  // n <= 8 * 256 = 2048 columns, one wave per row
 template <typename T>
 __device__ __forceinline__ void layer_norm_row(float (&v)[kLnMaxIter][4], int n, int lane, const T* gamma,
                                                const T* beta, float eps, T* out, float* out_f32) {
+  // gain and bias are requested first so that they arrive during the reductions
+  float4 gv[kLnMaxIter], bv[kLnMaxIter];
+#pragma unroll
+  for (int it = 0; it < kLnMaxIter; ++it) {
+    const int c = it * 256 + lane * 4;
+    if (c < n) { gv[it] = load4(gamma + c); bv[it] = load4(beta + c); }
+  }
   float s = 0.f;
 #pragma unroll
   for (int it = 0; it < kLnMaxIter; ++it) {
@@ -77,7 +84,7 @@ __device__ __forceinline__ void layer_norm_row(float (&v)[kLnMaxIter][4], int n,
   for (int it = 0; it < kLnMaxIter; ++it) {
     const int c = it * 256 + lane * 4;
     if (c < n) {
-      const float4 g = load4(gamma + c), b = load4(beta + c);
+      const float4 g = gv[it], b = bv[it];
       const float4 y = make_float4((v[it][0] - mean) * rstd * g.x + b.x, (v[it][1] - mean) * rstd * g.y + b.y,
                                    (v[it][2] - mean) * rstd * g.z + b.z, (v[it][3] - mean) * rstd * g.w + b.w);
       store4(out + c, y);

@@ -27,17 +27,27 @@ __device__ __forceinline__ Cand wave_best(Cand c) {
   return c;
 }
 
+// (max, sum of exp(x - max)) pairs combine associatively, so the log-sum-exp needs
+// a single exchange across the block.
+__device__ __forceinline__ void lse_merge(float& m, float& s, float om, float os) {
+  const float M = fmaxf(m, om);
+  if (M == -INFINITY) { s = 0.f; return; }
+  s = s * expf(m - M) + os * expf(om - M);
+  m = M;
+}
+
+constexpr int kMaxK = 32;
+
 template <bool REG>
 __global__ __launch_bounds__(kTopkThreads) void topk_row_kernel(const float* logits, const int* last_tok,
                                                                 int eos_id, int vocab, int k, float* cand_lp,
                                                                 int* cand_idx) {
-  __shared__ float red_v[kTopkThreads / kWave];
-  __shared__ int red_i[kTopkThreads / kWave];
-  __shared__ float bc_v;
-  __shared__ int bc_i;
+  constexpr int NW = kTopkThreads / kWave;
+  __shared__ float red_m[NW], red_s[NW];
+  __shared__ float wc_v[NW * kMaxK];   // every wave's k best values ...
+  __shared__ int wc_i[NW * kMaxK];     // ... and their word ids
   const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
   const float* x = logits + (size_t)row * vocab;
-  constexpr int NW = kTopkThreads / kWave;
   const int nit = (vocab + kTopkThreads - 1) / kTopkThreads;
 
   float reg[REG ? kTopkVpt : 1];
@@ -54,86 +64,123 @@ __global__ __launch_bounds__(kTopkThreads) void topk_row_kernel(const float* log
     return idx < vocab ? x[idx] : -INFINITY;
   };
 
-  // ---- max and log-sum-exp
-  float m = -INFINITY;
+  // ---- log-sum-exp of the row
+  float m = -INFINITY, s = 0.f;
   if (REG) {
 #pragma unroll
     for (int it = 0; it < kTopkVpt; ++it) m = fmaxf(m, reg[it]);
+#pragma unroll
+    for (int it = 0; it < kTopkVpt; ++it) s += (reg[it] == -INFINITY) ? 0.f : __expf(reg[it] - m);
   } else {
     for (int it = 0; it < nit; ++it) m = fmaxf(m, val(it));
-  }
-  m = wave_max(m);
-  if (lane == 0) red_v[wid] = m;
-  __syncthreads();
-  m = red_v[0];
-  for (int w = 1; w < NW; ++w) m = fmaxf(m, red_v[w]);
-  __syncthreads();
-  float s = 0.f;
-  if (REG) {
-#pragma unroll
-    for (int it = 0; it < kTopkVpt; ++it) s += (reg[it] == -INFINITY) ? 0.f : expf(reg[it] - m);
-  } else {
     for (int it = 0; it < nit; ++it) {
       const float v = val(it);
       s += (v == -INFINITY) ? 0.f : expf(v - m);
     }
   }
-  s = wave_sum(s);
-  if (lane == 0) red_v[wid] = s;
+#pragma unroll
+  for (int st = 1; st < kWave; st <<= 1) {
+    const float om = __shfl_xor(m, st, kWave), os = __shfl_xor(s, st, kWave);
+    lse_merge(m, s, om, os);
+  }
+  if (lane == 0) { red_m[wid] = m; red_s[wid] = s; }
+
+  // ---- each wave's k best, in order (value down, index up)
+  const bool finished = eos_id >= 0 && last_tok[row] == eos_id;
+  if (REG && k <= 4) {
+    // small k: every thread first sorts out its own 4 best (its values arrive in
+    // increasing index order, so a strict '>' keeps ties in index order); the k
+    // wave rounds then only look at the heads of these lists
+    float lv[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    int li[4] = {0x7fffffff, 0x7fffffff, 0x7fffffff, 0x7fffffff};
+#pragma unroll
+    for (int it = 0; it < kTopkVpt; ++it) {
+      const int idx = it * kTopkThreads + tid;
+      float v = reg[it];
+      int vi = idx < vocab ? idx : 0x7fffffff;
+      if (idx < vocab && v > lv[3]) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {   // insert, pushing the smaller ones down
+          if (v > lv[q]) {
+            const float tv = lv[q]; const int ti = li[q];
+            lv[q] = v; li[q] = vi; v = tv; vi = ti;
+          }
+        }
+      }
+    }
+    for (int round = 0; round < k; ++round) {
+      Cand best = {lv[0], li[0]};
+      best = wave_best(best);
+      if (lane == 0) { wc_v[wid * k + round] = best.v; wc_i[wid * k + round] = best.i; }
+      if (li[0] == best.i && best.i != 0x7fffffff) {   // the winner's owner pops its list
+        lv[0] = lv[1]; li[0] = li[1]; lv[1] = lv[2]; li[1] = li[2]; lv[2] = lv[3]; li[2] = li[3];
+        lv[3] = -INFINITY; li[3] = 0x7fffffff;
+      }
+    }
+  } else {
+    // general k: k rounds, each picking the best element after the previous pick
+    float pv = INFINITY;
+    int pi = -1;
+    for (int round = 0; round < k; ++round) {
+      Cand best = {-INFINITY, 0x7fffffff};
+      if (REG) {
+#pragma unroll
+        for (int it = 0; it < kTopkVpt; ++it) {
+          const int idx = it * kTopkThreads + tid;
+          const float v = reg[it];
+          const bool after = (v < pv) || (v == pv && idx > pi);
+          if (idx < vocab && after && better(v, idx, best.v, best.i)) { best.v = v; best.i = idx; }
+        }
+      } else {
+        for (int it = 0; it < nit; ++it) {
+          const int idx = it * kTopkThreads + tid;
+          const float v = val(it);
+          const bool after = (v < pv) || (v == pv && idx > pi);
+          if (idx < vocab && after && better(v, idx, best.v, best.i)) { best.v = v; best.i = idx; }
+        }
+      }
+      best = wave_best(best);
+      if (lane == 0) { wc_v[wid * k + round] = best.v; wc_i[wid * k + round] = best.i; }
+      pv = best.v;
+      pi = best.i;
+    }
+  }
   __syncthreads();
-  s = 0.f;
-  for (int w = 0; w < NW; ++w) s += red_v[w];
-  __syncthreads();
+  if (wid != 0) return;
+
+  m = red_m[0];
+  s = red_s[0];
+  for (int w = 1; w < NW; ++w) lse_merge(m, s, red_m[w], red_s[w]);   // same order in every lane
   const float lse = m + logf(s);
 
-  // ---- a finished hypothesis can only be extended by EOS at cost 0
-  if (eos_id >= 0 && last_tok[row] == eos_id) {
-    if (tid < k) {
-      int id = tid == 0 ? eos_id : (tid - 1 < eos_id ? tid - 1 : tid);
-      cand_lp[(size_t)row * k + tid] = tid == 0 ? 0.f : -INFINITY;
-      cand_idx[(size_t)row * k + tid] = id;
+  // a finished hypothesis can only be extended by EOS at cost 0
+  if (finished) {
+    if (lane < k) {
+      const int id = lane == 0 ? eos_id : (lane - 1 < eos_id ? lane - 1 : lane);
+      cand_lp[(size_t)row * k + lane] = lane == 0 ? 0.f : -INFINITY;
+      cand_idx[(size_t)row * k + lane] = id;
     }
     return;
   }
-
-  // ---- k rounds: best element strictly after the previous pick in the order
+  // ---- wave 0 merges the NW * k wave candidates
+  const int nc = NW * k;
   float pv = INFINITY;
   int pi = -1;
   for (int round = 0; round < k; ++round) {
     Cand best = {-INFINITY, 0x7fffffff};
-    if (REG) {
-#pragma unroll
-      for (int it = 0; it < kTopkVpt; ++it) {
-        const int idx = it * kTopkThreads + tid;
-        const float v = reg[it];
-        const bool after = (v < pv) || (v == pv && idx > pi);
-        if (idx < vocab && after && better(v, idx, best.v, best.i)) { best.v = v; best.i = idx; }
-      }
-    } else {
-      for (int it = 0; it < nit; ++it) {
-        const int idx = it * kTopkThreads + tid;
-        const float v = val(it);
-        const bool after = (v < pv) || (v == pv && idx > pi);
-        if (idx < vocab && after && better(v, idx, best.v, best.i)) { best.v = v; best.i = idx; }
-      }
+    for (int c = lane; c < nc; c += kWave) {
+      const float v = wc_v[c];
+      const int idx = wc_i[c];
+      const bool after = (v < pv) || (v == pv && idx > pi);
+      if (idx != 0x7fffffff && after && better(v, idx, best.v, best.i)) { best.v = v; best.i = idx; }
     }
     best = wave_best(best);
-    if (lane == 0) { red_v[wid] = best.v; red_i[wid] = best.i; }
-    __syncthreads();
-    if (wid == 0) {
-      Cand c = {lane < NW ? red_v[lane] : -INFINITY, lane < NW ? red_i[lane] : 0x7fffffff};
-      c = wave_best(c);
-      if (lane == 0) {
-        bc_v = c.v;
-        bc_i = c.i;
-        cand_lp[(size_t)row * k + round] = c.v - lse;
-        cand_idx[(size_t)row * k + round] = c.i;
-      }
+    if (lane == 0) {
+      cand_lp[(size_t)row * k + round] = best.v - lse;
+      cand_idx[(size_t)row * k + round] = best.i;
     }
-    __syncthreads();
-    pv = bc_v;
-    pi = bc_i;
-    __syncthreads();
+    pv = best.v;
+    pi = best.i;
   }
 }
 
