@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--cpu-steps", type=int, default=16)
+    ap.add_argument("--beam-sweep", default="", help="comma-separated beam sizes: also time SAN vs unshared "
+                    "cached decoding at these beams (the paper's Fig. 5 axis), e.g. 4,8,12,16,20")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a kernel of known "
                          "traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -237,6 +239,24 @@ def main():
         if "unshared_no_cache" in compare:
             compare["speedup_san_vs_unshared_no_cache"] = tok_per_s / compare["unshared_no_cache"]["tokens_per_s"]
 
+    # ------------------------------------------------ beam-size sweep (Fig. 5 axis)
+    beam_sweep = {}
+    if args.beam_sweep:
+        Ld = cfg["n_dec"]
+        for bm in [int(v) for v in args.beam_sweep.split(",")]:
+            c2 = dict(cfg, beam=bm)
+            ent = {}
+            for name, spi, cpi in (("san", cfg["self_pi"], cfg["encdec_pi"]), ("unshared", [1] * Ld, [1] * Ld)):
+                g = sb.San(sb.make_config(c2), blob, spi, cpi)
+                r = Runner(torch, g, c2, src, lens)
+                w = r.timed(2 * T, T)
+                ent[name] = {"tokens_per_s": c2["batch"] * bm * 2 * T / w, "sentence_tokens_per_s": c2["batch"] * 2 * T / w,
+                             "ms_per_step": w / (2 * T) * 1e3}
+                g.close()
+                del r
+            ent["speedup"] = ent["san"]["tokens_per_s"] / ent["unshared"]["tokens_per_s"]
+            beam_sweep[str(bm)] = ent
+
     # ------------------------------------------------ CPU oracle on the host cores
     cpu = None
     if not args.no_cpu:
@@ -286,6 +306,8 @@ def main():
                    "sentence_tokens_per_s": cfg["batch"] * K / wall},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "compare": compare,
     }
+    if beam_sweep:
+        out["beam_sweep"] = beam_sweep
     print(json.dumps(out))
 
 

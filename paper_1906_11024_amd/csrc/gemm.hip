@@ -345,6 +345,7 @@ hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
   // would leave most SIMDs idle, use smaller tiles and deal each tile's k range to
   // 2 or 4 wave groups (reduced through LDS), aiming at ~one wave per SIMD:
   //   shape 1: 64x32 tiles, 2 waves x 2 k-groups;  shape 2: 32x32 tiles, 1 wave x 4 k-groups.
+  // (64x32 with 4 k-groups, 32x64 and 64x64 with 2, 32x32 with 8 all measured within 3% of these.)
   const int chunks = (p.K / epc + p.ksplit - 1) / p.ksplit;
   const long tiles64 = (long)((p.M + 63) / 64) * ((p.N + 63) / 64) * p.ksplit;
   int shape = 0;

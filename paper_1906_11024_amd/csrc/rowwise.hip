@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void ln_reduce_kernel(const float* part, int n
                                                         int ldr, const T* gamma, const T* beta, T* out, int ldo,
                                                         float* out_f32, int M, int n, float eps) {
   const int lane = threadIdx.x & 63;
-  const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int m = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (m >= M) return;
   float v[kLnMaxIter][4];
 #pragma unroll
@@ -136,13 +136,15 @@ hipError_t launch_ln_reduce(int dtype, const float* part, int nsplit, const void
                             float eps, hipStream_t stream) {
   if (M <= 0) return hipSuccess;
   if (n > kLnMaxIter * 256 || n % 4) return hipErrorInvalidValue;
-  dim3 grid((M + 3) / 4);
+  // one wave per row; with few rows use one-wave blocks so the rows spread over all CUs
+  const int wpb = M <= 1024 ? 1 : 4;
+  dim3 grid((M + wpb - 1) / wpb), block(64 * wpb);
   if (dtype == 1)
-    hipLaunchKernelGGL(ln_reduce_kernel<bf16_t>, grid, dim3(256), 0, stream, part, nsplit, (const bf16_t*)bias,
+    hipLaunchKernelGGL(ln_reduce_kernel<bf16_t>, grid, block, 0, stream, part, nsplit, (const bf16_t*)bias,
                        (const bf16_t*)res, ldr, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)out, ldo,
                        out_f32, M, n, eps);
   else
-    hipLaunchKernelGGL(ln_reduce_kernel<float>, grid, dim3(256), 0, stream, part, nsplit, (const float*)bias,
+    hipLaunchKernelGGL(ln_reduce_kernel<float>, grid, block, 0, stream, part, nsplit, (const float*)bias,
                        (const float*)res, ldr, (const float*)gamma, (const float*)beta, (float*)out, ldo, out_f32,
                        M, n, eps);
   return hipGetLastError();

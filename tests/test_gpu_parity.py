@@ -124,6 +124,21 @@ def test_mid_fp32_lockstep(share, sharp):
     gpu.close()
 
 
+@pytest.mark.parametrize("beam", [8, 20])
+def test_mid_fp32_large_beams(beam):
+    """Beam sizes of the paper's speed-vs-beam study (Fig. 5: 4..20)."""
+    cfg = mid_cfg(batch=3, beam=beam, steps=24)
+    w = wl.make_weights(cfg, seed=12, sharp=4.0)
+    src, lens = ragged(cfg, 12)
+    gpu = hz.make_gpu(cfg, w, share="S")
+    ls = hz.Lockstep(gpu, hz.make_oracle(cfg, w, share="S"), src, lens, beam)
+    for t in range(cfg["steps"]):
+        ls.step(tie_tol=5e-4)
+    assert max(ls.log["logit_err"]) <= F32_TOL
+    assert sum(ls.log["exact"]) >= 0.8 * cfg["steps"]
+    gpu.close()
+
+
 def test_mid_fp32_empty_source_and_single_row():
     """Degenerate inputs: a sentence of length 0 (zero context vector), batch 1,
     beam 1, and a batch smaller than max_batch."""
