@@ -164,6 +164,27 @@ SAN_API int san_beam_reorder(san_ctx* ctx, const int32_t* parent_idx_dev);
  * Errors: SAN_ESTATE, SAN_EINVAL (layer, what, cap too small). */
 SAN_API int san_debug_get(san_ctx* ctx, int32_t what, int32_t layer, void* dst_dev, size_t cap);
 
+/* ---- Learning a sharing policy (Sec. 3.3) ----
+ * san_policy_accumulate: after a decode step of a context with cfg.debug = 1 (every
+ * layer's weights are kept), adds the Jensen-Shannon divergence (natural log)
+ * between the weights of every pair of decoder layers, for every row and head of
+ * that step, to running sums -- separately for self-attention (keys = the cached
+ * positions) and encoder-decoder attention (keys = the source positions).  Layers
+ * of one sharing block use the same weights and diverge by 0.
+ * san_policy_read: the [L][L] matrix (HOST, doubles) of mean divergences "per
+ * head, then averaged" (Sec. 3.1) and the number of (row, head) samples; which =
+ * 0 self-attention, 1 enc-dec.  Synchronises the stream.
+ * san_policy_search: host only.  Similarity mu(i,j) = ln 2 - JS(i,j); block
+ * similarity sim(m,n) = mean of mu over the ordered pairs i != j of layers m..n
+ * (Eq. 6); from layer 1 upwards take the biggest block with sim >= theta (a single
+ * layer always qualifies).  Writes the block sizes bottom-up to pi_out (HOST,
+ * room for n_layers) and their number to n_blocks_out.
+ * Errors: SAN_ESTATE (no debug copies / no step yet), SAN_EINVAL. */
+SAN_API int san_policy_accumulate(san_ctx* ctx);
+SAN_API int san_policy_read(san_ctx* ctx, int32_t which, double* js_out, int64_t* count_out, int32_t reset);
+SAN_API int san_policy_search(const double* js, int32_t n_layers, double theta, int32_t* pi_out,
+                              int32_t* n_blocks_out);
+
 /* Number of decode steps done since the last san_encode / san_rewind (-1 if
  * nothing is encoded). */
 SAN_API int32_t san_step(const san_ctx* ctx);

@@ -22,7 +22,8 @@ SAN_DBG_S_SELF, SAN_DBG_A_SELF, SAN_DBG_S_CTX, SAN_DBG_A_CTX, SAN_DBG_HIDDEN = r
 
 EXPORTS = ["san_weight_bytes", "san_init", "san_encode", "san_rewind", "san_decode_step", "san_topk",
            "san_beam_reorder", "san_debug_get", "san_step", "san_device_bytes", "san_last_launch_count",
-           "san_last_error", "san_free", "san_profile", "san_profile_read"]
+           "san_last_error", "san_free", "san_profile", "san_profile_read",
+           "san_policy_accumulate", "san_policy_read", "san_policy_search"]
 
 KINDS = ["misc", "proj", "attn_self", "attn_apply", "out", "ln", "attn_ctx", "attn_ctx_apply", "ffn", "logits",
          "topk", "reorder", "aan"]
@@ -85,6 +86,13 @@ def lib():
         l.san_profile.argtypes = [vp, i32]
         l.san_profile_read.restype = C.c_int
         l.san_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]
+        l.san_policy_accumulate.restype = C.c_int
+        l.san_policy_accumulate.argtypes = [vp]
+        l.san_policy_read.restype = C.c_int
+        l.san_policy_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]
+        l.san_policy_search.restype = C.c_int
+        l.san_policy_search.argtypes = [C.POINTER(C.c_double), i32, C.c_double, C.POINTER(C.c_int32),
+                                        C.POINTER(C.c_int32)]
         l.san_free.restype = None
         l.san_free.argtypes = [vp]
         _lib = l
@@ -102,6 +110,18 @@ def make_config(cfg: dict, *, max_batch=None, beam=None, max_src_len=None, max_t
         self_kind=SAN_SELF_AAN if cfg.get("self_kind") == "aan" else SAN_SELF_DOT,
         encdec_share=encdec_share, use_cache=use_cache, pad_id=0, bos_id=1, eos_id=eos_id,
         debug=debug, ln_eps=ln_eps)
+
+
+def policy_search(js: np.ndarray, theta: float) -> list:
+    """Greedy block search of Sec. 3.3 on a JS matrix (host code of the library)."""
+    js = np.ascontiguousarray(js, dtype=np.float64)
+    L = js.shape[0]
+    pi = (C.c_int32 * L)()
+    nb = C.c_int32()
+    rc = lib().san_policy_search(js.ctypes.data_as(C.POINTER(C.c_double)), L, float(theta), pi, C.byref(nb))
+    if rc != SAN_OK:
+        raise SanError(rc, "san_policy_search")
+    return list(pi[: nb.value])
 
 
 def weight_bytes(sc: SanConfig) -> int:
@@ -213,6 +233,18 @@ class San:
         n = (C.c_int64 * len(KINDS))()
         self._check(self._l.san_profile_read(self._h, ms, n, 1 if reset else 0))
         return {k: (ms[i], int(n[i])) for i, k in enumerate(KINDS)}
+
+    def policy_accumulate(self):
+        self._check(self._l.san_policy_accumulate(self._h))
+
+    def policy_read(self, which, reset=False):
+        """(mean JS matrix [L, L] as numpy float64, number of samples)"""
+        L = self.cfg.n_dec_layers
+        js = np.zeros((L, L), dtype=np.float64)
+        cnt = C.c_int64()
+        self._check(self._l.san_policy_read(self._h, which, js.ctypes.data_as(C.POINTER(C.c_double)),
+                                            C.byref(cnt), 1 if reset else 0))
+        return js, int(cnt.value)
 
     def close(self):
         if getattr(self, "_h", None):

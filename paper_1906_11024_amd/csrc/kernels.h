@@ -106,4 +106,18 @@ hipError_t launch_reorder_table(int* tab, int ld, const int* parent, const int* 
 hipError_t launch_reorder_rows(float* st, const int* parent, int layers, int batch, int beam, int d,
                                hipStream_t stream);
 
+// ------------------------------------------------------------- policy learning
+constexpr int kMaxPolicyLayers = 32;
+struct JsParams {
+  const float* S[kMaxPolicyLayers];   // per layer: weights [rows][H][ld]
+  int L, rows, H, ld;
+  const int* len; int rows_per_len;   // keys per row = len[row / rows_per_len] (nullptr: n_fixed)
+  int n_fixed;
+  float* part;                        // [pairs][rows*H]
+};
+// adds, for every layer pair, the sum over (row, head) of the JS divergence to acc[L][L]
+hipError_t launch_js_accumulate(const JsParams& p, double* acc, hipStream_t stream);
+// host: block sizes of the greedy search with threshold theta on a [L][L] JS matrix
+int policy_search(const double* js, int L, double theta, int32_t* pi, int32_t* n_blocks);
+
 }  // namespace san

@@ -62,6 +62,10 @@ struct san_ctx {
   float* part = nullptr;
   size_t part_elems = 0;
   int* counters = nullptr;   // split-K tickets, all zero between launches
+  // policy learning: running JS sums [2][L][L] (self, enc-dec), per-pair scratch, sample counts
+  double* js_acc = nullptr;
+  float* js_part = nullptr;
+  long long js_count[2] = {0, 0};
   int *t_dev = nullptr, *anc = nullptr, *hist = nullptr, *last_tok = nullptr, *src_len = nullptr;
   float* cand_lp = nullptr;
   int* cand_idx = nullptr;
@@ -810,6 +814,61 @@ int san_profile_read(san_ctx* c, double* ms_out, int64_t* launches_out, int32_t 
     if (reset) { c->prof_ms[k] = 0; c->prof_n[k] = 0; }
   }
   return rc;
+}
+
+int san_policy_accumulate(san_ctx* c) {
+  if (!c) return SAN_EINVAL;
+  if (!c->cfg.debug || !c->cfg.use_cache) return fail(c, SAN_ESTATE, "san_policy_accumulate needs cfg.debug = 1 and use_cache = 1");
+  if (c->t < 1) return fail(c, SAN_ESTATE, "san_policy_accumulate before the first decode step");
+  const int L = (int)c->dec.size(), B = c->batch * c->cfg.beam;
+  if (L > kMaxPolicyLayers) return fail(c, SAN_EINVAL, "too many decoder layers for policy statistics");
+  const size_t pairs = (size_t)L * (L - 1) / 2;
+  if (!c->js_acc) {
+    int rc = dalloc(c, (void**)&c->js_acc, 2 * (size_t)L * L * sizeof(double), false);
+    if (rc) return rc;
+    rc = dalloc(c, (void**)&c->js_part, (pairs ? pairs : 1) * (size_t)c->rows_max * c->H * 4, false);
+    if (rc) return rc;
+    HIP_TRY(c, hipMemsetAsync(c->js_acc, 0, 2 * (size_t)L * L * sizeof(double), c->stream));
+  }
+  JsParams p{};
+  p.L = L; p.rows = B; p.H = c->H; p.part = c->js_part;
+  if (c->cfg.self_kind == SAN_SELF_DOT) {
+    for (int n = 0; n < L; ++n) p.S[n] = c->dec[c->dec[n].self_head].S_self;
+    p.ld = c->cfg.max_tgt_len; p.len = nullptr; p.n_fixed = c->t;
+    HIP_TRY(c, launch_js_accumulate(p, c->js_acc, c->stream));
+    c->js_count[0] += (long long)B * c->H;
+  }
+  for (int n = 0; n < L; ++n) p.S[n] = c->dec[c->dec[n].ctx_head].S_ctx;
+  p.ld = c->cfg.max_src_len; p.len = c->src_len; p.rows_per_len = c->cfg.beam;
+  HIP_TRY(c, launch_js_accumulate(p, c->js_acc + (size_t)L * L, c->stream));
+  c->js_count[1] += (long long)B * c->H;
+  return SAN_OK;
+}
+
+int san_policy_read(san_ctx* c, int32_t which, double* js_out, int64_t* count_out, int32_t reset) {
+  if (!c) return SAN_EINVAL;
+  if (which != 0 && which != 1) return fail(c, SAN_EINVAL, "san_policy_read: which must be 0 (self) or 1 (enc-dec)");
+  const int L = (int)c->dec.size();
+  if (count_out) *count_out = c->js_count[which];
+  if (js_out) {
+    for (int i = 0; i < L * L; ++i) js_out[i] = 0.0;
+    if (c->js_acc && c->js_count[which] > 0) {
+      HIP_TRY(c, hipMemcpyAsync(js_out, c->js_acc + (size_t)which * L * L, (size_t)L * L * sizeof(double),
+                                hipMemcpyDeviceToHost, c->stream));
+      HIP_TRY(c, hipStreamSynchronize(c->stream));
+      for (int i = 0; i < L * L; ++i) js_out[i] /= (double)c->js_count[which];
+    }
+  }
+  if (reset && c->js_acc) {
+    HIP_TRY(c, hipMemsetAsync(c->js_acc + (size_t)which * L * L, 0, (size_t)L * L * sizeof(double), c->stream));
+    c->js_count[which] = 0;
+  }
+  return SAN_OK;
+}
+
+int san_policy_search(const double* js, int32_t n_layers, double theta, int32_t* pi_out, int32_t* n_blocks_out) {
+  if (!js || !pi_out || !n_blocks_out || n_layers < 1) return SAN_EINVAL;
+  return policy_search(js, n_layers, theta, pi_out, n_blocks_out);
 }
 
 int32_t san_step(const san_ctx* c) { return c ? c->t : -1; }

@@ -321,3 +321,51 @@ def test_state_and_capacity_errors():
         gpu.decode_step(tok, logits)
     assert e.value.code == sb.SAN_ECAPACITY
     gpu.close()
+
+
+# ---------------------------------------------------- policy statistics (Sec. 3.3)
+def test_js_divergence_between_layers_matches_oracle():
+    from oracle import policy_oracle as po
+    cfg = mid_cfg(steps=20, self_pi=[1, 1, 1, 1], encdec_pi=[1, 1, 1, 1])
+    w = wl.make_weights(cfg, seed=13, sharp=6.0)           # peaked weights: divergences well above 0
+    src, lens = ragged(cfg, 13)
+    gpu = hz.make_gpu(cfg, w, debug=1)
+    orc = hz.make_oracle(cfg, w)
+    ls = hz.Lockstep(gpu, orc, src, lens, cfg["beam"])
+    L = cfg["n_dec"]
+    want_self, want_ctx, count = np.zeros((L, L)), np.zeros((L, L)), 0
+    for t in range(cfg["steps"]):
+        # the oracle's weights of this step, before the beam step reorders anything
+        gpu.decode_step(ls.tokens, ls.logits)
+        gpu.policy_accumulate()
+        orc.decode_step(ls.tokens.cpu().numpy())
+        S_self = [orc.dump["S_self"][n] for n in range(L)]
+        S_ctx = [orc.dump["S_ctx"][n] for n in range(L)]
+        B, H = S_self[0].shape[:2]
+        want_self += po.layer_js_matrix(S_self) * B * H
+        want_ctx += po.layer_js_matrix(S_ctx) * B * H
+        count += B * H
+        # free-running greedy-like continuation on both sides with the oracle's choice
+        tok = torch.from_numpy(np.argsort(-orc.dump["hidden"][L - 1][:, :7], axis=-1)[:, 0].astype(np.int32) + 3).cuda()
+        ls.tokens = tok
+    js_self, n_self = gpu.policy_read(0)
+    js_ctx, n_ctx = gpu.policy_read(1)
+    assert n_self == count and n_ctx == count
+    want_self /= count
+    want_ctx /= count
+    assert want_self.max() > 1e-3 and want_ctx.max() > 1e-3
+    assert np.abs(js_self - want_self).max() <= 1e-4 * want_self.max() + 1e-7
+    assert np.abs(js_ctx - want_ctx).max() <= 1e-4 * want_ctx.max() + 1e-7
+    assert np.allclose(js_self, js_self.T) and np.allclose(np.diag(js_self), 0)
+    for theta in (0.2, 0.5, 0.65, 0.69):
+        assert sb.policy_search(js_self, theta) == po.greedy_policy(want_self, theta)
+    # layers of one block share their weights: divergence exactly 0 inside the block
+    gpu.close()
+    gpu = hz.make_gpu(cfg, w, [2, 2], [1, 3], debug=1)
+    hz.gpu_free_run(gpu, src, lens, cfg["beam"], 3)
+    gpu.policy_accumulate()
+    js, _ = gpu.policy_read(0)
+    assert js[0, 1] == 0 and js[2, 3] == 0 and js[0, 2] > 0
+    jc, _ = gpu.policy_read(1)
+    assert jc[1, 2] == 0 and jc[1, 3] == 0 and jc[0, 1] > 0
+    gpu.close()
