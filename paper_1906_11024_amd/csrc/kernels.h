@@ -74,8 +74,9 @@ hipError_t launch_embed(int dtype, const int* tok, int tok_stride, int rpg, cons
                         const int* t_dev, void* x, int rows, int d, int vocab, float scale, int* last_tok,
                         int* anc, int ld_anc, hipStream_t stream);
 
-// out[m] = LayerNorm(sum_s part[s][m] + bias + res[m]) * g + b  (row-wise over n)
-hipError_t launch_ln_reduce(int dtype, const float* part, int nsplit, const void* bias, const void* res, int ldr,
+// out[m] = LayerNorm(sum_s part[s][m] + bias + res[m]) * g + b  (row-wise over n);
+// part is [nsplit][M][ldp] and may point at a column offset of a wider buffer
+hipError_t launch_ln_reduce(int dtype, const float* part, int nsplit, int ldp, const void* bias, const void* res, int ldr,
                             const void* gamma, const void* beta, void* out, int ldo, float* out_f32, int M, int n,
                             float eps, hipStream_t stream);
 

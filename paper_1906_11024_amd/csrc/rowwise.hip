@@ -94,9 +94,9 @@ __device__ __forceinline__ void layer_norm_row(float (&v)[kLnMaxIter][4], int n,
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void ln_reduce_kernel(const float* part, int nsplit, const T* bias, const T* res,
-                                                        int ldr, const T* gamma, const T* beta, T* out, int ldo,
-                                                        float* out_f32, int M, int n, float eps) {
+__global__ __launch_bounds__(256) void ln_reduce_kernel(const float* part, int nsplit, int ldp, const T* bias,
+                                                        const T* res, int ldr, const T* gamma, const T* beta, T* out,
+                                                        int ldo, float* out_f32, int M, int n, float eps) {
   const int lane = threadIdx.x & 63;
   const int m = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (m >= M) return;
@@ -114,8 +114,8 @@ __global__ __launch_bounds__(256) void ln_reduce_kernel(const float* part, int n
         a.x += rv.x; a.y += rv.y; a.z += rv.z; a.w += rv.w;
       }
       float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-      const float* pp = part + (size_t)m * n + c;
-      const size_t ps = (size_t)M * n;
+      const float* pp = part + (size_t)m * ldp + c;
+      const size_t ps = (size_t)M * ldp;
       for (int s = 0; s < nsplit; s += 4) {
         float4 pv[4];
 #pragma unroll
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(256) void ln_reduce_kernel(const float* part, int n
   layer_norm_row<T>(v, n, lane, gamma, beta, eps, out + (size_t)m * ldo, out_f32 ? out_f32 + (size_t)m * n : nullptr);
 }
 
-hipError_t launch_ln_reduce(int dtype, const float* part, int nsplit, const void* bias, const void* res, int ldr,
+hipError_t launch_ln_reduce(int dtype, const float* part, int nsplit, int ldp, const void* bias, const void* res, int ldr,
                             const void* gamma, const void* beta, void* out, int ldo, float* out_f32, int M, int n,
                             float eps, hipStream_t stream) {
   if (M <= 0) return hipSuccess;
@@ -140,11 +140,11 @@ hipError_t launch_ln_reduce(int dtype, const float* part, int nsplit, const void
   const int wpb = M <= 1024 ? 1 : 4;
   dim3 grid((M + wpb - 1) / wpb), block(64 * wpb);
   if (dtype == 1)
-    hipLaunchKernelGGL(ln_reduce_kernel<bf16_t>, grid, block, 0, stream, part, nsplit, (const bf16_t*)bias,
+    hipLaunchKernelGGL(ln_reduce_kernel<bf16_t>, grid, block, 0, stream, part, nsplit, ldp, (const bf16_t*)bias,
                        (const bf16_t*)res, ldr, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)out, ldo,
                        out_f32, M, n, eps);
   else
-    hipLaunchKernelGGL(ln_reduce_kernel<float>, grid, block, 0, stream, part, nsplit, (const float*)bias,
+    hipLaunchKernelGGL(ln_reduce_kernel<float>, grid, block, 0, stream, part, nsplit, ldp, (const float*)bias,
                        (const float*)res, ldr, (const float*)gamma, (const float*)beta, (float*)out, ldo, out_f32,
                        M, n, eps);
   return hipGetLastError();

@@ -41,6 +41,12 @@ struct DecLayer {
   void* mem = nullptr;                        // head: [batch*max_src][2d]; follower (mode S): [..][d]
   float* S_ctx = nullptr;                     // head only
   void* A_ctx = nullptr;                      // head only: T [rows*][d]
+  // Eq. 5 blocks, cached decoding: the followers' output projections of the shared A are
+  // computed together with the head's (one GEMM over the stacked W_O of the block)
+  void* wo_blk = nullptr;                     // head only: [pi*d][d]
+  float* y_blk = nullptr;                     // head only: partials [ks][rows][pi*d]
+  size_t y_elems = 0;
+  int y_ks = 1, blk_size = 1;
   // feed-forward sub-layer
   void *w1 = nullptr, *b1 = nullptr, *w2 = nullptr, *b2 = nullptr, *ln3g = nullptr, *ln3b = nullptr;
   float *dbg_A_self = nullptr, *dbg_A_ctx = nullptr, *dbg_hidden = nullptr;
@@ -269,7 +275,7 @@ int gemm_ln(san_ctx* c, const void* A, int lda, const void* W, const void* bias,
   if (rc) return rc;
   const int k0 = c->kind;
   c->kind = SAN_K_LN;
-  LAUNCH(c, launch_ln_reduce(c->dt, c->part, ks, bias, res, N, g, b, out, N, dbg, M, N, c->cfg.ln_eps, c->stream));
+  LAUNCH(c, launch_ln_reduce(c->dt, c->part, ks, N, bias, res, N, g, b, out, N, dbg, M, N, c->cfg.ln_eps, c->stream));
   c->kind = k0;
   return SAN_OK;
 }
@@ -404,7 +410,19 @@ static int build_ctx(san_ctx* c, const Blob& bl, const void* blob, const std::ve
         TRY(wtensor(c, &L.bkv_c, blob, o.ctx.bv, d));
         TRY(dalloc(c, &L.mem, (size_t)c->rows_src_max * d * esz, false));
       }
-      TRY(wtensor(c, &L.wo_c, blob, o.ctx.wo, d * d));
+      {
+        int pi = 0;   // size of this layer's enc-dec block
+        for (int q = 0; q < Ld; ++q) pi += ctx_head[q] == L.ctx_head;
+        const bool stacked = pi > 1 && !shareS && !nocache;
+        if (stacked && L.ctx_head == n) {
+          L.blk_size = pi;
+          TRY(dalloc(c, &L.wo_blk, (size_t)pi * d * d * esz, true));
+          for (int q = 0; q < pi; ++q) TRY(upload(c, L.wo_blk, (size_t)q * d * d, blob, bl.dec[n + q].ctx.wo, d * d));
+          L.y_elems = (size_t)gemm_pick_ksplit(c->rows_max, pi * (int)d, (int)d, c->dt) * c->rows_max * pi * d;
+          TRY(dalloc(c, (void**)&L.y_blk, L.y_elems * 4, false));
+        }
+        if (!stacked) TRY(wtensor(c, &L.wo_c, blob, o.ctx.wo, d * d));
+      }
       TRY(wtensor(c, &L.bo_c, blob, o.ctx.bo, d));
       TRY(wtensor(c, &L.ln2g, blob, o.ln2.g, d));
       TRY(wtensor(c, &L.ln2b, blob, o.ln2.b, d));
@@ -631,7 +649,22 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
     }
     if ((rc = dbg_copy(c, A, d, L.dbg_A_ctx, B))) return rc;
     c->kind = SAN_K_OUT;
-    if ((rc = gemm_ln(c, A, d, L.wo_c, L.bo_c, B, d, c->x, L.ln2g, L.ln2b, c->x, nullptr))) return rc;
+    if (Hd.wo_blk) {
+      // A^{m+i} = A^m (Eq. 5): all output projections of the block in one GEMM at the head
+      const int N = Hd.blk_size * d;
+      if (chead) {
+        int ks = gemm_pick_ksplit(B, N, d, c->dt);
+        while (ks > 1 && (size_t)ks * B * N > Hd.y_elems) ks /= 2;
+        Hd.y_ks = ks;
+        if ((rc = gemm(c, A, d, Hd.wo_blk, nullptr, B, N, d, 0, 2, Hd.y_blk, N, 0, nullptr, 0, 0, nullptr, 0, 0, 0, false, ks)))
+          return rc;
+      }
+      c->kind = SAN_K_LN;
+      LAUNCH(c, launch_ln_reduce(c->dt, Hd.y_blk + (size_t)(n - L.ctx_head) * d, Hd.y_ks, N, L.bo_c, c->x, d, L.ln2g,
+                                 L.ln2b, c->x, d, nullptr, B, d, c->cfg.ln_eps, c->stream));
+    } else {
+      if ((rc = gemm_ln(c, A, d, L.wo_c, L.bo_c, B, d, c->x, L.ln2g, L.ln2b, c->x, nullptr))) return rc;
+    }
     if ((rc = ffn_block(c, &L, nullptr, B, L.dbg_hidden))) return rc;
   }
   c->kind = SAN_K_LOGITS;
