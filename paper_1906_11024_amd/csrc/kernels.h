@@ -76,9 +76,15 @@ hipError_t launch_embed(int dtype, const int* tok, int tok_stride, int rpg, cons
 
 // out[m] = LayerNorm(sum_s part[s][m] + bias + res[m]) * g + b  (row-wise over n);
 // part is [nsplit][M][ldp] and may point at a column offset of a wider buffer
+// stage2 (optional): a second update + LayerNorm applied to the first one's output
+// in the same launch: out = LN2(LN1(...) + sum_s part2[s][m] + bias2)
+struct LnStage2 {
+  const float* part; int nsplit, ldp;
+  const void *bias, *gamma, *beta;
+};
 hipError_t launch_ln_reduce(int dtype, const float* part, int nsplit, int ldp, const void* bias, const void* res, int ldr,
                             const void* gamma, const void* beta, void* out, int ldo, float* out_f32, int M, int n,
-                            float eps, hipStream_t stream);
+                            float eps, hipStream_t stream, const LnStage2* stage2 = nullptr);
 
 // start of a decode step: last_tok[r] = tok[r]; anc[r][t] = r; hist[r][t] = tok[r]
 hipError_t launch_step_begin(const int* tok, int* last_tok, int* anc, int* hist, int ld, const int* t_dev, int rows,

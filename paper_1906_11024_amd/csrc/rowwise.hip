@@ -50,7 +50,7 @@ hipError_t launch_embed(int dtype, const int* tok, int tok_stride, int rpg, cons
 // ------------------------------------------- reduce + bias + residual + LayerNorm
 constexpr int kLnMaxIter = 8;  // n <= 8 * 256 = 2048 columns, one wave per row
 
-template <typename T>
+template <typename T, bool STORE = true>
 __device__ __forceinline__ void layer_norm_row(float (&v)[kLnMaxIter][4], int n, int lane, const T* gamma,
                                                const T* beta, float eps, T* out, float* out_f32) {
   // gain and bias are requested first so that they arrive during the reductions
@@ -87,8 +87,12 @@ __device__ __forceinline__ void layer_norm_row(float (&v)[kLnMaxIter][4], int n,
       const float4 g = gv[it], b = bv[it];
       const float4 y = make_float4((v[it][0] - mean) * rstd * g.x + b.x, (v[it][1] - mean) * rstd * g.y + b.y,
                                    (v[it][2] - mean) * rstd * g.z + b.z, (v[it][3] - mean) * rstd * g.w + b.w);
-      store4(out + c, y);
-      if (out_f32) *reinterpret_cast<float4*>(out_f32 + c) = y;
+      if (STORE) {
+        store4(out + c, y);
+        if (out_f32) *reinterpret_cast<float4*>(out_f32 + c) = y;
+      } else {
+        v[it][0] = y.x; v[it][1] = y.y; v[it][2] = y.z; v[it][3] = y.w;
+      }
     }
   }
 }
@@ -96,7 +100,8 @@ __device__ __forceinline__ void layer_norm_row(float (&v)[kLnMaxIter][4], int n,
 template <typename T>
 __global__ __launch_bounds__(256) void ln_reduce_kernel(const float* part, int nsplit, int ldp, const T* bias,
                                                         const T* res, int ldr, const T* gamma, const T* beta, T* out,
-                                                        int ldo, float* out_f32, int M, int n, float eps) {
+                                                        int ldo, float* out_f32, int M, int n, float eps,
+                                                        LnStage2 s2) {
   const int lane = threadIdx.x & 63;
   const int m = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (m >= M) return;
@@ -128,25 +133,58 @@ __global__ __launch_bounds__(256) void ln_reduce_kernel(const float* part, int n
       v[it][0] = sum.x + a.x; v[it][1] = sum.y + a.y; v[it][2] = sum.z + a.z; v[it][3] = sum.w + a.w;
     }
   }
-  layer_norm_row<T>(v, n, lane, gamma, beta, eps, out + (size_t)m * ldo, out_f32 ? out_f32 + (size_t)m * n : nullptr);
+  if (s2.part) {
+    // second sub-layer without a GEMM of its own in between (an enc-dec follower
+    // whose projected context was computed at the block head): normalise in
+    // registers, add the second update, normalise again
+    layer_norm_row<T, false>(v, n, lane, gamma, beta, eps, nullptr, nullptr);
+#pragma unroll
+    for (int it = 0; it < kLnMaxIter; ++it) {
+      const int c = it * 256 + lane * 4;
+      if (c < n) {
+        float4 a = load4(reinterpret_cast<const T*>(s2.bias) + c);
+        const float* pp = s2.part + (size_t)m * s2.ldp + c;
+        const size_t ps = (size_t)M * s2.ldp;
+        for (int s = 0; s < s2.nsplit; s += 4) {
+          float4 pv[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            pv[u] = (s + u < s2.nsplit) ? *reinterpret_cast<const float4*>(pp + (size_t)(s + u) * ps)
+                                        : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) { a.x += pv[u].x; a.y += pv[u].y; a.z += pv[u].z; a.w += pv[u].w; }
+        }
+        // the first LayerNorm's output was rounded to the storage type when it was a
+        // separate launch; keep that rounding so both forms give the same bits
+        v[it][0] = to_f32(from_f32<T>(v[it][0])) + a.x; v[it][1] = to_f32(from_f32<T>(v[it][1])) + a.y;
+        v[it][2] = to_f32(from_f32<T>(v[it][2])) + a.z; v[it][3] = to_f32(from_f32<T>(v[it][3])) + a.w;
+      }
+    }
+    layer_norm_row<T, true>(v, n, lane, reinterpret_cast<const T*>(s2.gamma), reinterpret_cast<const T*>(s2.beta), eps,
+                            out + (size_t)m * ldo, out_f32 ? out_f32 + (size_t)m * n : nullptr);
+    return;
+  }
+  layer_norm_row<T, true>(v, n, lane, gamma, beta, eps, out + (size_t)m * ldo, out_f32 ? out_f32 + (size_t)m * n : nullptr);
 }
 
 hipError_t launch_ln_reduce(int dtype, const float* part, int nsplit, int ldp, const void* bias, const void* res, int ldr,
                             const void* gamma, const void* beta, void* out, int ldo, float* out_f32, int M, int n,
-                            float eps, hipStream_t stream) {
+                            float eps, hipStream_t stream, const LnStage2* stage2) {
   if (M <= 0) return hipSuccess;
   if (n > kLnMaxIter * 256 || n % 4) return hipErrorInvalidValue;
+  LnStage2 s2{};
+  if (stage2) s2 = *stage2;
   // one wave per row; with few rows use one-wave blocks so the rows spread over all CUs
   const int wpb = M <= 1024 ? 1 : 4;
   dim3 grid((M + wpb - 1) / wpb), block(64 * wpb);
   if (dtype == 1)
     hipLaunchKernelGGL(ln_reduce_kernel<bf16_t>, grid, block, 0, stream, part, nsplit, ldp, (const bf16_t*)bias,
                        (const bf16_t*)res, ldr, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)out, ldo,
-                       out_f32, M, n, eps);
+                       out_f32, M, n, eps, s2);
   else
     hipLaunchKernelGGL(ln_reduce_kernel<float>, grid, block, 0, stream, part, nsplit, ldp, (const float*)bias,
                        (const float*)res, ldr, (const float*)gamma, (const float*)beta, (float*)out, ldo, out_f32,
-                       M, n, eps);
+                       M, n, eps, s2);
   return hipGetLastError();
 }
 

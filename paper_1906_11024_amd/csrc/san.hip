@@ -266,13 +266,17 @@ int gemm(san_ctx* c, const void* A, int lda, const void* W, const void* bias, in
 // x_out = LayerNorm(res + A W^T + bias): split-K GEMM into fp32 partials, reduced
 // by the LayerNorm kernel.
 int gemm_ln(san_ctx* c, const void* A, int lda, const void* W, const void* bias, int M, int K, const void* res,
-            const void* g, const void* b, void* out, float* dbg) {
+            const void* g, const void* b, void* out, float* dbg, int* defer_ks = nullptr) {
   const int N = c->d;
   int ks = gemm_pick_ksplit(M, N, K, c->dt);
   while (ks > 1 && (size_t)ks * M * N > c->part_elems) ks /= 2;
   if ((size_t)ks * M * N > c->part_elems) return fail(c, SAN_ECAPACITY, "split-K workspace too small");
   int rc = gemm(c, A, lda, W, nullptr, M, N, K, 0, 2, c->part, N, 0, nullptr, 0, 0, nullptr, 0, 0, 0, false, ks);
   if (rc) return rc;
+  if (defer_ks) {   // the caller folds this LayerNorm into the next one
+    *defer_ks = ks;
+    return SAN_OK;
+  }
   const int k0 = c->kind;
   c->kind = SAN_K_LN;
   LAUNCH(c, launch_ln_reduce(c->dt, c->part, ks, N, bias, res, N, g, b, out, N, dbg, M, N, c->cfg.ln_eps, c->stream));
@@ -579,6 +583,8 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
   const int Ld = (int)c->dec.size();
   for (int n = 0; n < Ld; ++n) {
     DecLayer& L = c->dec[n];
+    bool fuse_ln = false;
+    int ks_self = 1;
     if (aan) {
       c->kind = SAN_K_AAN;
       LAUNCH(c, launch_aan_pre(c->dt, L.aan_sum, c->x, c->ab, c->cat, c->t_dev, B, d, c->stream));
@@ -616,7 +622,11 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
       LAUNCH(c, launch_attention(c->dt, a, c->stream));
       if ((rc = dbg_copy(c, c->ab, d, L.dbg_A_self, B))) return rc;
       c->kind = SAN_K_OUT;
-      if ((rc = gemm_ln(c, c->ab, d, L.wo, L.bo, B, d, c->x, L.ln1g, L.ln1b, c->x, nullptr))) return rc;
+      // an enc-dec follower of an Eq. 5 block has no kernel between its two
+      // LayerNorms: both run in one launch further down
+      fuse_ln = c->dec[L.ctx_head].wo_blk != nullptr && L.ctx_head != n;
+      if ((rc = gemm_ln(c, c->ab, d, L.wo, L.bo, B, d, c->x, L.ln1g, L.ln1b, c->x, nullptr, fuse_ln ? &ks_self : nullptr)))
+        return rc;
     }
     // ---- encoder-decoder attention
     const bool chead = L.ctx_head == n;
@@ -660,8 +670,14 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
           return rc;
       }
       c->kind = SAN_K_LN;
-      LAUNCH(c, launch_ln_reduce(c->dt, Hd.y_blk + (size_t)(n - L.ctx_head) * d, Hd.y_ks, N, L.bo_c, c->x, d, L.ln2g,
-                                 L.ln2b, c->x, d, nullptr, B, d, c->cfg.ln_eps, c->stream));
+      if (fuse_ln) {
+        LnStage2 s2{Hd.y_blk + (size_t)(n - L.ctx_head) * d, Hd.y_ks, N, L.bo_c, L.ln2g, L.ln2b};
+        LAUNCH(c, launch_ln_reduce(c->dt, c->part, ks_self, d, L.bo, c->x, d, L.ln1g, L.ln1b, c->x, d, nullptr, B, d,
+                                   c->cfg.ln_eps, c->stream, &s2));
+      } else {
+        LAUNCH(c, launch_ln_reduce(c->dt, Hd.y_blk + (size_t)(n - L.ctx_head) * d, Hd.y_ks, N, L.bo_c, c->x, d, L.ln2g,
+                                   L.ln2b, c->x, d, nullptr, B, d, c->cfg.ln_eps, c->stream));
+      }
     } else {
       if ((rc = gemm_ln(c, A, d, L.wo_c, L.bo_c, B, d, c->x, L.ln2g, L.ln2b, c->x, nullptr))) return rc;
     }
