@@ -79,12 +79,17 @@ typedef struct {
 } san_config;
 
 /* Sharing policy (Sec. 3.3): block sizes bottom-up; each list must sum to
- * n_dec_layers and hold only sizes >= 1.  With SAN_SELF_AAN self_pi is ignored. */
+ * n_dec_layers and hold only sizes >= 1.  With SAN_SELF_AAN self_pi is ignored.
+ * enc_pi (optional: n_enc = 0 or NULL means every encoder layer on its own) shares
+ * the encoder self-attention weights the same way (Tab. 5, "encoder-side SAN") and
+ * must sum to n_enc_layers. */
 typedef struct {
   int32_t n_self;
   const int32_t* self_pi; /* HOST */
   int32_t n_encdec;
   const int32_t* encdec_pi; /* HOST */
+  int32_t n_enc;
+  const int32_t* enc_pi; /* HOST, may be NULL */
 } san_policy;
 
 /* Size in bytes of the weight blob san_init expects for this configuration

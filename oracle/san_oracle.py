@@ -136,7 +136,7 @@ class SanOracle:
     only, per-layer V).  dtype: arithmetic type (float64 unless a pin says so)."""
 
     def __init__(self, cfg, weights, self_pi, encdec_pi, encdec_share="A",
-                 ln_eps=1e-5, eos_id=-1, max_len=None, dtype=np.float64):
+                 ln_eps=1e-5, eos_id=-1, max_len=None, dtype=np.float64, enc_pi=None):
         self.cfg = cfg
         self.dt = dtype
         self.w = {k: np.asarray(v, dtype=dtype) for k, v in weights.items()}
@@ -146,6 +146,8 @@ class SanOracle:
         self.aan = cfg.get("self_kind", "dot") == "aan"
         self.self_head = block_heads(self_pi, self.n_dec)
         self.ctx_head = block_heads(encdec_pi, self.n_dec)
+        # encoder-side sharing (Tab. 5): same rule on the encoder self-attention
+        self.enc_head = block_heads(enc_pi if enc_pi else [1] * self.n_enc, self.n_enc)
         assert encdec_share in ("A", "S")
         self.share = encdec_share
         self.eps = ln_eps
@@ -179,15 +181,21 @@ class SanOracle:
         x = self.w["src_emb"][src] * self.emb_scale + self.pe[:L][None]
         key_ok = (np.arange(L)[None, :] < self.src_len[:, None])      # [batch, L]
         mask = key_ok[:, None, None, :]                                # over [b,H,lq,lk]
+        S_enc = {}
         for i in range(self.n_enc):
             p = f"enc{i}.attn"
-            Q = split_heads(self._mha_proj(p, "q", x), self.H)
-            K = split_heads(self._mha_proj(p, "k", x), self.H)
             Vv = split_heads(self._mha_proj(p, "v", x), self.H)
-            S = attention_weights(Q, K, self.dh, mask)
+            if self.enc_head[i] == i:
+                Q = split_heads(self._mha_proj(p, "q", x), self.H)
+                K = split_heads(self._mha_proj(p, "k", x), self.H)
+                S_enc[i] = attention_weights(Q, K, self.dh, mask)
+            else:                                   # weights of the block head, own V
+                S_enc[i] = S_enc[self.enc_head[i]]
+            S = S_enc[i]
             A = merge_heads(attention_output(S, Vv))
             x = self._ln(f"enc{i}.ln1", x + self._mha_proj(p, "o", A))
             x = self._ln(f"enc{i}.ln2", x + self._ffn(f"enc{i}.ffn", x))
+        self.enc_S = S_enc
         self.enc_out = x                                               # [batch, L, d]
         # memory keys / values: K for block heads only; V for block heads, or for
         # every layer in mode 'S' (each follower keeps its own V projection).

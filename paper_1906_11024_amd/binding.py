@@ -38,7 +38,8 @@ class SanConfig(C.Structure):
 
 class SanPolicy(C.Structure):
     _fields_ = [("n_self", C.c_int32), ("self_pi", C.POINTER(C.c_int32)),
-                ("n_encdec", C.c_int32), ("encdec_pi", C.POINTER(C.c_int32))]
+                ("n_encdec", C.c_int32), ("encdec_pi", C.POINTER(C.c_int32)),
+                ("n_enc", C.c_int32), ("enc_pi", C.POINTER(C.c_int32))]
 
 
 class SanError(RuntimeError):
@@ -132,7 +133,7 @@ class San:
     """Thin handle around a san_ctx.  Tensor arguments are torch CUDA tensors
     (int32 / float32, contiguous); only their data pointers cross the boundary."""
 
-    def __init__(self, sc: SanConfig, blob: np.ndarray, self_pi, encdec_pi, stream=None):
+    def __init__(self, sc: SanConfig, blob: np.ndarray, self_pi, encdec_pi, stream=None, enc_pi=None):
         import torch
         self._torch = torch
         self._l = lib()
@@ -140,7 +141,10 @@ class San:
         blob = np.ascontiguousarray(blob).view(np.uint8)
         sp = (C.c_int32 * max(1, len(self_pi)))(*self_pi)
         ep = (C.c_int32 * max(1, len(encdec_pi)))(*encdec_pi)
-        pol = SanPolicy(len(self_pi), C.cast(sp, C.POINTER(C.c_int32)), len(encdec_pi), C.cast(ep, C.POINTER(C.c_int32)))
+        enc_pi = list(enc_pi) if enc_pi else []
+        np_ = (C.c_int32 * max(1, len(enc_pi)))(*enc_pi)
+        pol = SanPolicy(len(self_pi), C.cast(sp, C.POINTER(C.c_int32)), len(encdec_pi), C.cast(ep, C.POINTER(C.c_int32)),
+                        len(enc_pi), C.cast(np_, C.POINTER(C.c_int32)) if enc_pi else None)
         self.stream = stream if stream is not None else torch.cuda.current_stream()
         h = C.c_void_p()
         rc = self._l.san_init(C.byref(sc), blob.ctypes.data_as(C.c_void_p), blob.nbytes, C.byref(pol),

@@ -21,7 +21,10 @@ namespace {
 thread_local std::string g_init_error;
 
 struct EncLayer {
+  // wqkv: block head [3d][d] (q;k;v); follower of an encoder-side sharing block: [d][d] (v only)
   void *wqkv, *bqkv, *wo, *bo, *ln1g, *ln1b, *w1, *b1, *w2, *b2, *ln2g, *ln2b;
+  int head = 0;              // first layer of this layer's block
+  float* S = nullptr;        // block head with followers: weights [batch*max_src][H][max_src]
 };
 
 struct DecLayer {
@@ -304,7 +307,7 @@ int dbg_copy(san_ctx* c, const void* src, int lds, float* dst, int rows) {
 }  // namespace
 
 static int build_ctx(san_ctx* c, const Blob& bl, const void* blob, const std::vector<int>& self_head,
-                     const std::vector<int>& ctx_head) {
+                     const std::vector<int>& ctx_head, const std::vector<int>& enc_head) {
   const san_config* cfg = &c->cfg;
   const int esz = cfg->dtype == SAN_BF16 ? 2 : 4;
   const int Ld = cfg->n_dec_layers;
@@ -341,14 +344,22 @@ static int build_ctx(san_ctx* c, const Blob& bl, const void* blob, const std::ve
     for (int i = 0; i < cfg->n_enc_layers; ++i) {
       EncLayer& e = c->enc[i];
       const Blob::Enc& o = bl.enc[i];
-      TRY(dalloc(c, &e.wqkv, 3 * d * d * esz, true));
-      TRY(dalloc(c, &e.bqkv, 3 * d * esz, true));
-      TRY(upload(c, e.wqkv, 0, blob, o.attn.wq, d * d));
-      TRY(upload(c, e.wqkv, d * d, blob, o.attn.wk, d * d));
-      TRY(upload(c, e.wqkv, 2 * d * d, blob, o.attn.wv, d * d));
-      TRY(upload(c, e.bqkv, 0, blob, o.attn.bq, d));
-      TRY(upload(c, e.bqkv, d, blob, o.attn.bk, d));
-      TRY(upload(c, e.bqkv, 2 * d, blob, o.attn.bv, d));
+      e.head = enc_head[i];
+      if (e.head == i) {
+        TRY(dalloc(c, &e.wqkv, 3 * d * d * esz, true));
+        TRY(dalloc(c, &e.bqkv, 3 * d * esz, true));
+        TRY(upload(c, e.wqkv, 0, blob, o.attn.wq, d * d));
+        TRY(upload(c, e.wqkv, d * d, blob, o.attn.wk, d * d));
+        TRY(upload(c, e.wqkv, 2 * d * d, blob, o.attn.wv, d * d));
+        TRY(upload(c, e.bqkv, 0, blob, o.attn.bq, d));
+        TRY(upload(c, e.bqkv, d, blob, o.attn.bk, d));
+        TRY(upload(c, e.bqkv, 2 * d, blob, o.attn.bv, d));
+        if (i + 1 < cfg->n_enc_layers && enc_head[i + 1] == i)
+          TRY(dalloc(c, (void**)&e.S, (size_t)c->rows_src_max * c->H * cfg->max_src_len * 4, false));
+      } else {   // encoder-side sharing (Tab. 5): a follower keeps only its value projection
+        TRY(wtensor(c, &e.wqkv, blob, o.attn.wv, d * d));
+        TRY(wtensor(c, &e.bqkv, blob, o.attn.bv, d));
+      }
       TRY(wtensor(c, &e.wo, blob, o.attn.wo, d * d));
       TRY(wtensor(c, &e.bo, blob, o.attn.bo, d));
       TRY(wtensor(c, &e.ln1g, blob, o.ln1.g, d));
@@ -509,11 +520,17 @@ int san_init(const san_config* cfg, const void* weights_host, size_t weight_byte
   if (!policy_heads(policy->n_encdec, policy->encdec_pi, Ld, ctx_head))
     return fail(nullptr, SAN_EPOLICY, "enc-dec policy must be block sizes >= 1 that sum to n_dec_layers");
 
+  std::vector<int> enc_head;
+  if (policy->n_enc == 0 || !policy->enc_pi) {
+    for (int i = 0; i < cfg->n_enc_layers; ++i) enc_head.push_back(i);
+  } else if (!policy_heads(policy->n_enc, policy->enc_pi, cfg->n_enc_layers, enc_head)) {
+    return fail(nullptr, SAN_EPOLICY, "encoder policy must be block sizes >= 1 that sum to n_enc_layers");
+  }
   san_ctx* c = new (std::nothrow) san_ctx();
   if (!c) return fail(nullptr, SAN_ENOMEM, "host allocation failed");
   c->cfg = *cfg;
   c->stream = (hipStream_t)hip_stream;
-  const int rc = build_ctx(c, bl, weights_host, self_head, ctx_head);
+  const int rc = build_ctx(c, bl, weights_host, self_head, ctx_head, enc_head);
   if (rc) {
     g_init_error = c->err;
     for (void* p : c->allocs) (void)hipFree(p);
@@ -537,9 +554,18 @@ int san_encode(san_ctx* c, const int32_t* src_ids_dev, const int32_t* src_len_de
   HIP_TRY(c, hipMemcpyAsync(c->src_len, src_len_dev, (size_t)batch * 4, hipMemcpyDeviceToDevice, c->stream));
   LAUNCH(c, launch_embed(c->dt, src_ids_dev, max_src, max_src, c->src_emb, c->pe, nullptr, c->x, Ms, d, c->V,
                          (float)std::sqrt((double)d), nullptr, nullptr, 0, c->stream));
-  for (const EncLayer& e : c->enc) {
-    if ((rc = gemm(c, c->x, d, e.wqkv, e.bqkv, Ms, 3 * d, d, 0, 0, c->qkv, 3 * d))) return rc;
+  for (size_t li = 0; li < c->enc.size(); ++li) {
+    const EncLayer& e = c->enc[li];
+    const bool ehead = e.head == (int)li;
+    if (ehead) {
+      if ((rc = gemm(c, c->x, d, e.wqkv, e.bqkv, Ms, 3 * d, d, 0, 0, c->qkv, 3 * d))) return rc;
+    } else {
+      if ((rc = gemm(c, c->x, d, e.wqkv, e.bqkv, Ms, d, d, 0, 0, (char*)c->qkv + (size_t)2 * d * c->esz, 3 * d))) return rc;
+    }
     AttnParams a{};
+    a.S_buf = c->enc[e.head].S; a.ldS = c->cfg.max_src_len;
+    a.apply = ehead ? 0 : 1;
+    a.emit = ehead && e.S != nullptr;
     a.q = c->qkv; a.ldq = 3 * d;
     a.K = (char*)c->qkv + (size_t)d * c->esz; a.ldk = 3 * d;
     a.V = (char*)c->qkv + (size_t)2 * d * c->esz; a.ldv = 3 * d;

@@ -10,19 +10,19 @@ from paper_1906_11024_amd import workloads as wl
 
 
 def make_gpu(cfg, weights, self_pi=None, encdec_pi=None, share="A", beam=None, steps=None,
-             use_cache=1, debug=0, eos_id=-1, max_batch=None, max_src_len=None):
+             use_cache=1, debug=0, eos_id=-1, max_batch=None, max_src_len=None, enc_pi=None):
     sc = sb.make_config(cfg, beam=beam, max_tgt_len=steps, use_cache=use_cache, debug=debug, eos_id=eos_id,
                         max_batch=max_batch, max_src_len=max_src_len,
                         encdec_share=sb.SAN_SHARE_S if share == "S" else sb.SAN_SHARE_A)
     blob = wl.pack_weights(cfg, weights)
     return sb.San(sc, blob, self_pi if self_pi is not None else cfg["self_pi"],
-                  encdec_pi if encdec_pi is not None else cfg["encdec_pi"])
+                  encdec_pi if encdec_pi is not None else cfg["encdec_pi"], enc_pi=enc_pi)
 
 
-def make_oracle(cfg, weights, self_pi=None, encdec_pi=None, share="A", eos_id=-1, max_len=None):
+def make_oracle(cfg, weights, self_pi=None, encdec_pi=None, share="A", eos_id=-1, max_len=None, enc_pi=None):
     return so.SanOracle(cfg, weights, self_pi if self_pi is not None else cfg["self_pi"],
                         encdec_pi if encdec_pi is not None else cfg["encdec_pi"],
-                        encdec_share=share, eos_id=eos_id, max_len=max_len)
+                        encdec_share=share, eos_id=eos_id, max_len=max_len, enc_pi=enc_pi)
 
 
 def rel_err_rows(got, ref):

@@ -49,12 +49,13 @@ def test_weight_bytes_matches_generator(lib, name):
     assert sb.weight_bytes(sb.make_config(cfg)) == n * (2 if cfg["dtype"] == "bf16" else 4)
 
 
-def _init(lib, sc, self_pi, ctx_pi, nbytes=None):
+def _init(lib, sc, self_pi, ctx_pi, nbytes=None, enc_pi=()):
     nbytes = sb.weight_bytes(sc) if nbytes is None else nbytes
     blob = np.zeros(max(nbytes, 4), dtype=np.uint8)
     sp = (C.c_int32 * max(1, len(self_pi)))(*self_pi)
     ep = (C.c_int32 * max(1, len(ctx_pi)))(*ctx_pi)
-    pol = sb.SanPolicy(len(self_pi), C.cast(sp, C.POINTER(C.c_int32)), len(ctx_pi), C.cast(ep, C.POINTER(C.c_int32)))
+    pol = sb.SanPolicy(len(self_pi), C.cast(sp, C.POINTER(C.c_int32)), len(ctx_pi), C.cast(ep, C.POINTER(C.c_int32)),
+                       len(enc_pi), C.cast((C.c_int32 * max(1, len(enc_pi)))(*enc_pi), C.POINTER(C.c_int32)) if enc_pi else None)
     h = C.c_void_p()
     rc = lib.san_init(C.byref(sc), blob.ctypes.data_as(C.c_void_p), nbytes, C.byref(pol), None, C.byref(h))
     assert rc != 0 and not h.value
@@ -85,6 +86,13 @@ def test_bad_policy_is_epolicy(lib, spi, cpi):
     sc = sb.make_config(wl.get_config("tiny"))
     rc, msg = _init(lib, sc, spi, cpi)
     assert rc == sb.SAN_EPOLICY and "policy" in msg
+
+
+def test_bad_encoder_policy_is_epolicy(lib):
+    sc = sb.make_config(wl.get_config("tiny"))
+    for enc in ([1], [3], [2, 1], [0, 2]):
+        rc, msg = _init(lib, sc, [2], [2], enc_pi=enc)
+        assert rc == sb.SAN_EPOLICY and "encoder" in msg
 
 
 def test_uncached_aan_rejected_and_null_handles(lib):

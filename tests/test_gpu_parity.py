@@ -369,3 +369,25 @@ def test_js_divergence_between_layers_matches_oracle():
     jc, _ = gpu.policy_read(1)
     assert jc[1, 2] == 0 and jc[1, 3] == 0 and jc[0, 1] > 0
     gpu.close()
+
+
+# ------------------------------------------------- encoder-side sharing (Tab. 5)
+@pytest.mark.parametrize("dtype,tol", [("f32", F32_TOL), ("bf16", BF16_TOL)])
+def test_encoder_side_sharing_matches_oracle(dtype, tol):
+    cfg = mid_cfg(n_enc=4, steps=8, dtype=dtype)
+    w = wl.make_weights(cfg, seed=15, sharp=4.0)
+    src, lens = ragged(cfg, 15)
+    enc_pi = [1, 3]
+    gpu = hz.make_gpu(cfg, w, enc_pi=enc_pi)
+    ls = hz.Lockstep(gpu, hz.make_oracle(cfg, w, enc_pi=enc_pi), src, lens, cfg["beam"])
+    for t in range(cfg["steps"]):
+        ls.step(tie_tol=5e-4 if dtype == "f32" else 0.2)
+    assert max(ls.log["logit_err"]) <= tol
+    # it is a different model from the unshared encoder (the check above is not vacuous)
+    g2 = hz.make_gpu(cfg, w)
+    a = hz.gpu_free_run(gpu, src, lens, cfg["beam"], 2, keep_logits=True)["logits"][1]
+    b = hz.gpu_free_run(g2, src, lens, cfg["beam"], 2, keep_logits=True)["logits"][1]
+    assert np.abs(a - b).max() > 1e-3 * np.abs(a).max()
+    assert gpu.device_bytes(0) < g2.device_bytes(0)
+    gpu.close()
+    g2.close()

@@ -473,3 +473,35 @@ def test_workload_generator_is_seeded_and_shaped():
     src, lens = wl.make_source(wl.get_config("base"), 0)
     assert src.shape == (64, 60) and lens.min() >= 20 and lens.max() <= 60
     assert (src[np.arange(60)[None] >= lens[:, None]] == wl.PAD_ID).all() and (src[:, :20] >= 3).all()
+
+
+# ------------------------------------------------- encoder-side sharing (Tab. 5)
+def test_encoder_side_sharing():
+    cfg = wl.get_config("tiny", n_enc=3)
+    w = wl.make_weights(cfg, seed=14, sharp=4.0)
+    src, lens = ragged_source(cfg)
+    a = so.SanOracle(cfg, w, [2], [2])
+    b = so.SanOracle(cfg, w, [2], [2], enc_pi=[1, 2])
+    ea, eb = a.encode(src, lens), b.encode(src, lens)
+    assert np.array_equal(b.enc_S[1], b.enc_S[2]) and not np.allclose(b.enc_S[0], b.enc_S[1])
+    assert np.array_equal(a.enc_S[1], b.enc_S[1])           # layers up to the first follower are untouched
+    assert not np.allclose(ea, eb)
+    assert np.allclose(b.enc_S[1].sum(-1), 1.0) and (b.enc_S[2][0, :, :, 9:] == 0).all()
+    # the follower's Q/K projections are discarded, its V projection is not
+    w2 = dict(w)
+    w2["enc2.attn.wq"] = w["enc2.attn.wq"] * 3 + 1
+    w2["enc2.attn.bk"] = w["enc2.attn.bk"] + 1
+    assert np.array_equal(so.SanOracle(cfg, w2, [2], [2], enc_pi=[1, 2]).encode(src, lens), eb)
+    w3 = dict(w)
+    w3["enc2.attn.wv"] = w["enc2.attn.wv"] * 1.5
+    assert not np.allclose(so.SanOracle(cfg, w3, [2], [2], enc_pi=[1, 2]).encode(src, lens), eb)
+    # zero queries: all weights uniform over the source, sharing is a no-op
+    w0 = dict(w)
+    for i in range(3):
+        w0[f"enc{i}.attn.wq"] = np.zeros_like(w[f"enc{i}.attn.wq"])
+        w0[f"enc{i}.attn.bq"] = np.zeros_like(w[f"enc{i}.attn.bq"])
+    e0 = so.SanOracle(cfg, w0, [2], [2]).encode(src, lens)
+    e1 = so.SanOracle(cfg, w0, [2], [2], enc_pi=[3]).encode(src, lens)
+    assert np.allclose(e0, e1, atol=1e-12)
+    with pytest.raises(ValueError):
+        so.SanOracle(cfg, w, [2], [2], enc_pi=[2, 2])
