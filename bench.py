@@ -234,6 +234,31 @@ def main():
                              "weight_MB": g.device_bytes(0) / 1e6, "state_MB": g.device_bytes(1) / 1e6}
             g.close()
             del r
+        # the same decode driven by san_decode_n: one host call per 64 steps, pairs of
+        # steps replayed from a captured HIP graph (own stream: the NULL stream cannot be captured)
+        for name, use_graph in (("san_decode_n_eager", False), ("san_decode_n_graph", True)):
+            st = torch.cuda.Stream()
+            with torch.cuda.stream(st):
+                g = make(cfg["self_pi"], cfg["encdec_pi"])
+                r = Runner(torch, g, cfg, src, lens)
+                o_tok = torch.zeros((T, B), dtype=torch.int32, device="cuda")
+                o_par = torch.zeros((T, B), dtype=torch.int32, device="cuda")
+
+                def one_decode():
+                    g.rewind()
+                    cum = r.cum0.clone()
+                    g.decode_n(T, r.bos, cum, o_tok, o_par, r.logits, use_graph)
+
+                one_decode()
+                st.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(4):
+                    one_decode()
+                st.synchronize()
+                w = time.perf_counter() - t0
+                compare[name] = {"tokens_per_s": B * 4 * T / w, "ms_per_step": w / (4 * T) * 1e3, "steps": 4 * T}
+                g.close()
+                del r
         compare["san_cached"] = {"tokens_per_s": tok_per_s, "ms_per_step": ms_per_step}
         compare["speedup_san_vs_unshared_cached"] = tok_per_s / compare["unshared_cached"]["tokens_per_s"]
         if "unshared_no_cache" in compare:

@@ -169,6 +169,25 @@ SAN_API int san_beam_reorder(san_ctx* ctx, const int32_t* parent_idx_dev);
  * Errors: SAN_ESTATE, SAN_EINVAL (layer, what, cap too small). */
 SAN_API int san_debug_get(san_ctx* ctx, int32_t what, int32_t layer, void* dst_dev, size_t cap);
 
+/* n consecutive beam-search steps without returning to the host (Sec. 1: the
+ * decoder produces one word at a time until the end): each step is
+ * san_decode_step + san_topk with k = beam + san_beam_reorder, the chosen tokens
+ * and scores feeding the next step.  With EOS handling on, finished hypotheses
+ * keep extending with EOS at no cost; the call always runs n steps.
+ *   tokens_dev      DEVICE int32 [rows]     input tokens of the first step
+ *   cum_io_dev      DEVICE fp32  [rows]     cumulative scores, in: before, out: after
+ *   out_tokens_dev  DEVICE int32 [n][rows]  token chosen for every row at every step
+ *   out_parents_dev DEVICE int32 [n][rows]  parent row of every row at every step
+ *   logits_work_dev DEVICE fp32  [rows][vocab] scratch
+ * use_graph != 0: pairs of steps are replayed from a captured HIP graph (needs a
+ * stream other than the NULL stream and use_cache = 1; the graph is re-captured
+ * when the output/scratch pointers or the batch change).  Allocates its small
+ * ping-pong buffers on first use.
+ * Errors: SAN_ESTATE, SAN_ECAPACITY (step + n > max_tgt_len), SAN_EINVAL. */
+SAN_API int san_decode_n(san_ctx* ctx, int32_t n, const int32_t* tokens_dev, float* cum_io_dev,
+                         int32_t* out_tokens_dev, int32_t* out_parents_dev, float* logits_work_dev,
+                         int32_t use_graph);
+
 /* ---- Learning a sharing policy (Sec. 3.3) ----
  * san_policy_accumulate: after a decode step of a context with cfg.debug = 1 (every
  * layer's weights are kept), adds the Jensen-Shannon divergence (natural log)

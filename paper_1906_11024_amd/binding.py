@@ -23,7 +23,7 @@ SAN_DBG_S_SELF, SAN_DBG_A_SELF, SAN_DBG_S_CTX, SAN_DBG_A_CTX, SAN_DBG_HIDDEN = r
 EXPORTS = ["san_weight_bytes", "san_init", "san_encode", "san_rewind", "san_decode_step", "san_topk",
            "san_beam_reorder", "san_debug_get", "san_step", "san_device_bytes", "san_last_launch_count",
            "san_last_error", "san_free", "san_profile", "san_profile_read",
-           "san_policy_accumulate", "san_policy_read", "san_policy_search"]
+           "san_policy_accumulate", "san_policy_read", "san_policy_search", "san_decode_n"]
 
 KINDS = ["misc", "proj", "attn_self", "attn_apply", "out", "ln", "attn_ctx", "attn_ctx_apply", "ffn", "logits",
          "topk", "reorder", "aan"]
@@ -87,6 +87,8 @@ def lib():
         l.san_profile.argtypes = [vp, i32]
         l.san_profile_read.restype = C.c_int
         l.san_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]
+        l.san_decode_n.restype = C.c_int
+        l.san_decode_n.argtypes = [vp, i32, i32p, f32p, i32p, i32p, f32p, i32]
         l.san_policy_accumulate.restype = C.c_int
         l.san_policy_accumulate.argtypes = [vp]
         l.san_policy_read.restype = C.c_int
@@ -237,6 +239,16 @@ class San:
         n = (C.c_int64 * len(KINDS))()
         self._check(self._l.san_profile_read(self._h, ms, n, 1 if reset else 0))
         return {k: (ms[i], int(n[i])) for i, k in enumerate(KINDS)}
+
+    def decode_n(self, n, tokens, cum_io, out_tokens, out_parents, logits_work, use_graph=False):
+        torch = self._torch
+        self._want(tokens, torch.int32, self.rows)
+        self._want(cum_io, torch.float32, self.rows)
+        self._want(out_tokens, torch.int32, n * self.rows)
+        self._want(out_parents, torch.int32, n * self.rows)
+        self._want(logits_work, torch.float32, self.rows * self.cfg.vocab)
+        self._check(self._l.san_decode_n(self._h, n, self._p(tokens), self._p(cum_io), self._p(out_tokens),
+                                         self._p(out_parents), self._p(logits_work), 1 if use_graph else 0))
 
     def policy_accumulate(self):
         self._check(self._l.san_policy_accumulate(self._h))

@@ -103,9 +103,15 @@ hipError_t launch_aan_post(int dtype, const float* z, const void* bg, const void
                            hipStream_t stream);
 
 // ---------------------------------------------------------------------- search
+// hist (optional): also append the picks to tok/par[step][batch*k], step =
+// *t_dev - 1 - *t0_dev (the decode step just finished, relative to the call's first)
+struct TopkHistory {
+  int* tok; int* par;
+  const int* t_dev; const int* t0_dev;
+};
 hipError_t launch_topk(const float* logits, const float* cum, const int* last_tok, int eos_id, int batch, int beam,
                        int vocab, int k, float* cand_lp, int* cand_idx, int* out_tok, int* out_parent,
-                       float* out_score, hipStream_t stream);
+                       float* out_score, hipStream_t stream, const TopkHistory* hist = nullptr);
 // per sentence, in place: tab[r][j] = tab[parent[r]][j] for j < *t_dev
 hipError_t launch_reorder_table(int* tab, int ld, const int* parent, const int* t_dev, int batch, int beam,
                                 int max_t, hipStream_t stream);

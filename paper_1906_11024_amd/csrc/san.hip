@@ -75,6 +75,15 @@ struct san_ctx {
   double* js_acc = nullptr;
   float* js_part = nullptr;
   long long js_count[2] = {0, 0};
+  // multi-step decoding (san_decode_n): ping-pong token / score buffers, parents, first-step counter,
+  // and the captured two-step graph with the pointers it was captured for
+  int* pp_tok[2] = {nullptr, nullptr};
+  float* pp_cum[2] = {nullptr, nullptr};
+  int* pp_par = nullptr;
+  int* t0_dev = nullptr;
+  hipGraphExec_t graph2 = nullptr;
+  const void* graph_key[3] = {nullptr, nullptr, nullptr};
+  int graph_rows = 0;
   int *t_dev = nullptr, *anc = nullptr, *hist = nullptr, *last_tok = nullptr, *src_len = nullptr;
   float* cand_lp = nullptr;
   int* cand_idx = nullptr;
@@ -493,6 +502,7 @@ const char* san_last_error(const san_ctx* ctx) { return ctx ? ctx->err.c_str() :
 void san_free(san_ctx* ctx) {
   if (!ctx) return;
   (void)hipStreamSynchronize(ctx->stream);
+  if (ctx->graph2) (void)hipGraphExecDestroy(ctx->graph2);
   for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
   for (void* p : ctx->allocs) (void)hipFree(p);
   delete ctx;
@@ -585,6 +595,7 @@ int san_encode(san_ctx* c, const int32_t* src_ids_dev, const int32_t* src_len_de
   }
   HIP_TRY(c, hipMemsetAsync(c->t_dev, 0, 4, c->stream));
   c->batch = batch; c->max_src = max_src; c->t = 0;
+  c->graph_rows = 0;   // a captured step graph is tied to the batch shape
   return prof_flush(c);
 }
 
@@ -889,6 +900,77 @@ int san_profile_read(san_ctx* c, double* ms_out, int64_t* launches_out, int32_t 
     if (reset) { c->prof_ms[k] = 0; c->prof_n[k] = 0; }
   }
   return rc;
+}
+
+// One beam-search step on the ping-pong buffers: parity p reads set p, writes set p^1.
+static int loop_step(san_ctx* c, int p, int32_t* out_tokens, int32_t* out_parents, float* logits) {
+  int rc = san_decode_step(c, c->pp_tok[p], logits);
+  if (rc) return rc;
+  TopkHistory h{out_tokens, out_parents, c->t_dev, c->t0_dev};
+  HIP_TRY(c, launch_topk(logits, c->pp_cum[p], c->last_tok, c->cfg.eos_id, c->batch, c->cfg.beam, c->V, c->cfg.beam,
+                         c->cand_lp, c->cand_idx, c->pp_tok[p ^ 1], c->pp_par, c->pp_cum[p ^ 1], c->stream, &h));
+  return san_beam_reorder(c, c->pp_par);
+}
+
+int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io_dev, int32_t* out_tokens_dev,
+                 int32_t* out_parents_dev, float* logits_work_dev, int32_t use_graph) {
+  if (!c) return SAN_EINVAL;
+  if (!tokens_dev || !cum_io_dev || !out_tokens_dev || !out_parents_dev || !logits_work_dev || n < 1)
+    return fail(c, SAN_EINVAL, "san_decode_n: bad argument");
+  if (c->t < 0) return fail(c, SAN_ESTATE, "san_decode_n before san_encode");
+  if (c->t + n > c->cfg.max_tgt_len) return fail(c, SAN_ECAPACITY, "san_decode_n: would exceed max_tgt_len");
+  if (c->prof_on) return fail(c, SAN_ESTATE, "san_decode_n: switch san_profile off first");
+  if (use_graph && (!c->stream || !c->cfg.use_cache))
+    return fail(c, SAN_EINVAL, "san_decode_n: graph replay needs a non-default stream and use_cache = 1");
+  const int rows = c->batch * c->cfg.beam;
+  if (!c->pp_par) {
+    int rc;
+    for (int i = 0; i < 2; ++i) {
+      if ((rc = dalloc(c, (void**)&c->pp_tok[i], (size_t)c->rows_max * 4, false))) return rc;
+      if ((rc = dalloc(c, (void**)&c->pp_cum[i], (size_t)c->rows_max * 4, false))) return rc;
+    }
+    if ((rc = dalloc(c, (void**)&c->pp_par, (size_t)c->rows_max * 4, false))) return rc;
+    if ((rc = dalloc(c, (void**)&c->t0_dev, 256, false))) return rc;
+  }
+  HIP_TRY(c, hipMemcpyAsync(c->pp_tok[0], tokens_dev, (size_t)rows * 4, hipMemcpyDeviceToDevice, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(c->pp_cum[0], cum_io_dev, (size_t)rows * 4, hipMemcpyDeviceToDevice, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(c->t0_dev, c->t_dev, 4, hipMemcpyDeviceToDevice, c->stream));
+  int done = 0, rc;
+  if (use_graph && n >= 2) {
+    // the graph holds two steps (parity 0 then 1); it is rebuilt when the caller's
+    // buffers or the batch change
+    const bool stale = !c->graph2 || c->graph_key[0] != out_tokens_dev || c->graph_key[1] != out_parents_dev ||
+                       c->graph_key[2] != logits_work_dev || c->graph_rows != rows;
+    if (stale && n >= 4) {
+      if (c->graph2) { (void)hipGraphExecDestroy(c->graph2); c->graph2 = nullptr; }
+      // two ordinary steps first, so that one-time set-up inside the launchers
+      // (per-kernel attributes) has happened before anything is captured
+      for (; done < 2; ++done)
+        if ((rc = loop_step(c, done & 1, out_tokens_dev, out_parents_dev, logits_work_dev))) return rc;
+      hipGraph_t g = nullptr;
+      const int t_before = c->t;
+      HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+      rc = loop_step(c, 0, out_tokens_dev, out_parents_dev, logits_work_dev);
+      if (!rc) rc = loop_step(c, 1, out_tokens_dev, out_parents_dev, logits_work_dev);
+      const hipError_t e = hipStreamEndCapture(c->stream, &g);
+      c->t = t_before;   // capturing queued nothing
+      if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
+      if (e != hipSuccess) return fail(c, SAN_EHIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+      const hipError_t e2 = hipGraphInstantiate(&c->graph2, g, nullptr, nullptr, 0);
+      (void)hipGraphDestroy(g);
+      if (e2 != hipSuccess) return fail(c, SAN_EHIP, std::string("hipGraphInstantiate: ") + hipGetErrorString(e2));
+      c->graph_key[0] = out_tokens_dev; c->graph_key[1] = out_parents_dev; c->graph_key[2] = logits_work_dev;
+      c->graph_rows = rows;
+    }
+    for (; c->graph2 && done + 2 <= n; done += 2) {
+      HIP_TRY(c, hipGraphLaunch(c->graph2, c->stream));
+      c->t += 2;
+    }
+  }
+  for (; done < n; ++done)
+    if ((rc = loop_step(c, done & 1, out_tokens_dev, out_parents_dev, logits_work_dev))) return rc;
+  HIP_TRY(c, hipMemcpyAsync(cum_io_dev, c->pp_cum[n & 1], (size_t)rows * 4, hipMemcpyDeviceToDevice, c->stream));
+  return SAN_OK;
 }
 
 int san_policy_accumulate(san_ctx* c) {

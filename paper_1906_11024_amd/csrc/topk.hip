@@ -187,8 +187,11 @@ __global__ __launch_bounds__(kTopkThreads) void topk_row_kernel(const float* log
 // One wave per sentence: merge the beam*k candidates, keep the k best.
 __global__ __launch_bounds__(64) void topk_merge_kernel(const float* cand_lp, const int* cand_idx, const float* cum,
                                                         int beam, int vocab, int k, int* out_tok, int* out_parent,
-                                                        float* out_score) {
+                                                        float* out_score, TopkHistory hist) {
   const int b = blockIdx.x, lane = threadIdx.x;
+  // multi-step decoding: this step's picks are also appended to the caller's
+  // [step][rows] arrays; the step index comes from the device-side counters
+  const long long hoff = hist.tok ? (long long)(*hist.t_dev - 1 - *hist.t0_dev) * gridDim.x * k : 0;
   const int nc = beam * k;
   float pv = INFINITY;
   int pi = -1;
@@ -205,9 +208,14 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(const float* cand_lp, co
     best = wave_best(best);
     if (lane == 0) {
       const bool ok = best.i != 0x7fffffff;
-      out_tok[(size_t)b * k + round] = ok ? best.i % vocab : 0;
-      out_parent[(size_t)b * k + round] = b * beam + (ok ? best.i / vocab : 0);
+      const int tk = ok ? best.i % vocab : 0, pr = b * beam + (ok ? best.i / vocab : 0);
+      out_tok[(size_t)b * k + round] = tk;
+      out_parent[(size_t)b * k + round] = pr;
       out_score[(size_t)b * k + round] = ok ? best.v : -INFINITY;
+      if (hist.tok) {
+        hist.tok[hoff + (size_t)b * k + round] = tk;
+        hist.par[hoff + (size_t)b * k + round] = pr;
+      }
     }
     pv = best.v;
     pi = best.i;
@@ -216,7 +224,7 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(const float* cand_lp, co
 
 hipError_t launch_topk(const float* logits, const float* cum, const int* last_tok, int eos_id, int batch, int beam,
                        int vocab, int k, float* cand_lp, int* cand_idx, int* out_tok, int* out_parent,
-                       float* out_score, hipStream_t stream) {
+                       float* out_score, hipStream_t stream, const TopkHistory* hist) {
   const int rows = batch * beam;
   if (rows <= 0) return hipSuccess;
   if (vocab <= kTopkVpt * kTopkThreads)
@@ -227,8 +235,10 @@ hipError_t launch_topk(const float* logits, const float* cum, const int* last_to
                        vocab, k, cand_lp, cand_idx);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  TopkHistory h{};
+  if (hist) h = *hist;
   hipLaunchKernelGGL(topk_merge_kernel, dim3(batch), dim3(64), 0, stream, cand_lp, cand_idx, cum, beam, vocab, k,
-                     out_tok, out_parent, out_score);
+                     out_tok, out_parent, out_score, h);
   return hipGetLastError();
 }
 

@@ -391,3 +391,48 @@ def test_encoder_side_sharing_matches_oracle(dtype, tol):
     assert gpu.device_bytes(0) < g2.device_bytes(0)
     gpu.close()
     g2.close()
+
+
+# ------------------------------------------------ multi-step decoding on the device
+@pytest.mark.parametrize("use_graph", [False, True])
+def test_decode_n_equals_step_by_step(use_graph):
+    cfg = mid_cfg(steps=40)
+    w = wl.make_weights(cfg, seed=16, sharp=4.0)
+    src, lens = ragged(cfg, 16)
+    beam, B, V = cfg["beam"], cfg["batch"] * cfg["beam"], cfg["V"]
+    ref_gpu = hz.make_gpu(cfg, w)
+    ref = hz.gpu_free_run(ref_gpu, src, lens, beam, 23)
+    ref_gpu.close()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        gpu = hz.make_gpu(cfg, w)
+        assert gpu.stream.cuda_stream != 0
+        gpu.encode(torch.from_numpy(src).cuda(), torch.from_numpy(lens).cuda())
+        cum0 = np.full(B, -np.inf, dtype=np.float32)
+        cum0[0::beam] = 0.0
+        logits = torch.empty((B, V), dtype=torch.float32, device="cuda")
+        for rep in range(3):                      # replays of the captured graph, eager work in between
+            n1 = 16 if rep < 2 else 6
+            tokens = torch.full((B,), wl.BOS_ID, dtype=torch.int32, device="cuda")
+            cum = torch.from_numpy(cum0).cuda()
+            out_tok = torch.zeros((23, B), dtype=torch.int32, device="cuda")
+            out_par = torch.zeros((23, B), dtype=torch.int32, device="cuda")
+            gpu.rewind()
+            gpu.decode_n(n1, tokens, cum, out_tok, out_par, logits, use_graph)
+            stream.synchronize()
+            assert gpu.step == n1
+            # continue from where the first call stopped (odd count: graph pairs + one eager step)
+            n2 = 23 - n1
+            gpu.decode_n(n2, out_tok[n1 - 1].clone(), cum, out_tok[n1:], out_par[n1:], logits, use_graph)
+            stream.synchronize()
+            assert gpu.step == 23
+            got_tok, got_par, got_cum = out_tok.cpu().numpy(), out_par.cpu().numpy(), cum.cpu().numpy()
+            for t in range(23):
+                assert np.array_equal(got_tok[t], ref["tokens"][t]), (rep, t)
+                assert np.array_equal(got_par[t], ref["parents"][t]), (rep, t)
+            assert np.array_equal(got_cum, ref["scores"][22])
+        big_t = torch.zeros((30, B), dtype=torch.int32, device="cuda")
+        with pytest.raises(sb.SanError) as e:      # 23 steps done, 30 more would pass max_tgt_len = 40
+            gpu.decode_n(30, tokens, cum, big_t, big_t.clone(), logits, use_graph)
+        assert e.value.code == sb.SAN_ECAPACITY
+        gpu.close()
