@@ -244,9 +244,10 @@ template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p,
     const size_t smem = sizeof(float) * kWavesPerBlock * p.lmax + sizeof(int) * p.lmax;
     dim3 grid((unsigned)(p.rows * nhg));
     hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(256), smem, stream, p);
-  } else if (p.rpg <= 32) {
-    // few queries per stream (the beams of a sentence): one wave per query keeps
-    // enough waves in flight; the queries' re-reads of the stream hit in L2
+  } else if (p.rpg <= 32 && (long)p.groups * p.H * ((p.rpg + 3) / 4) < 1024) {
+    // few queries per stream (the beams of a sentence) and few streams: one wave
+    // per query keeps enough waves in flight (at least ~one per SIMD); the queries'
+    // re-reads of the stream hit in L2.  With >= 1024 streams a wave takes 4 queries.
     const size_t smem = sizeof(float) * kWavesPerBlock * p.lmax;
     dim3 grid((unsigned)(p.groups * p.rpg * nhg));
     hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(256), smem, stream, p);
