@@ -8,10 +8,11 @@
 // D chunks lives in registers (global loads issued D chunks ahead), each chunk is
 // then staged through one of two LDS buffers (rows padded to 144 bytes so that the
 // 16-byte fragment reads of 16 neighbouring lanes hit all 64 banks once), and
-// GEMMs with few output tiles are split along k across blocks: every block writes
-// fp32 partials, the last block to arrive at a tile (an atomic ticket) adds them
-// up in a fixed order -- so results do not depend on arrival order -- and runs the
-// epilogue (bias, ReLU, scatter into the q buffer / key cache / value cache).
+// GEMMs that feed a LayerNorm are split along k across blocks into fp32 partials
+// which the LayerNorm kernel adds up in a fixed order (no atomics, no fences: a
+// device-scope fence per block costs more than the whole GEMM on this multi-XCD
+// part).  The others keep the whole k range in one block and run the epilogue
+// (bias, ReLU, scatter into the q buffer / key cache / value cache) themselves.
 // The weight rows feed the MFMA "A" side and the activation rows the "B" side, so
 // a lane ends up with 4 consecutive output columns of one output row, which makes
 // the epilogue's bias loads and stores 16-byte wide.
@@ -54,7 +55,6 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
   static_assert(BM % RPP == 0 && BN % RPP == 0 && D % 2 == 0, "tile shape");
   static_assert(KW == 1 || (KW - 1) * (WM * WN) * TM * TN * 16 * 64 * 4 <= KW * STAGE, "reduction fits the stages");
   extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ int s_last;
 
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
   const int kg = wid / (WM * WN), w_in = wid % (WM * WN);   // k-group, wave inside the group
@@ -178,9 +178,9 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
 
   // acc[i][j][v]: output row m = tile_m + l32, column n = tile_n + (v/4)*8 + kh*4 + (v%4).
   const bool n_vec = (p.N % 4) == 0;
-  if (p.out_kind == 2 || p.ksplit > 1) {
-    // ---- fp32 partials [ksplit][M][N]
-    float* part = p.out_kind == 2 ? reinterpret_cast<float*>(p.out[0]) : p.part;
+  if (p.out_kind == 2) {
+    // ---- fp32 partials [ksplit][M][N]; the consumer (LayerNorm kernel) adds them up in a fixed order
+    float* part = reinterpret_cast<float*>(p.out[0]);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       const int m = m0 + (wm * TM + i) * 32 + l32;
@@ -200,44 +200,7 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
           }
         }
     }
-    if (p.out_kind == 2) return;
-    // ---- ticket: the last block of this tile reduces and runs the epilogue
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-      int* cnt = p.counters + blockIdx.y * gridDim.x + blockIdx.x;
-      const int old = atomicAdd(cnt, 1);
-      const int last = (old == p.ksplit - 1);
-      if (last) *cnt = 0;   // ready for the next launch
-      s_last = last;
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int m = m0 + (wm * TM + i) * 32 + l32;
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int n = n0 + (wn * TN + j) * 32 + g * 8 + kh * 4;
-          float s4[4] = {0.f, 0.f, 0.f, 0.f};
-          if (m < p.M && n < p.N) {
-            for (int z = 0; z < p.ksplit; ++z) {   // fixed order: deterministic sums
-              const float* src = part + ((size_t)z * p.M + m) * p.N + n;
-              if (n_vec) {
-                const float4 v = *reinterpret_cast<const float4*>(src);
-                s4[0] += v.x; s4[1] += v.y; s4[2] += v.z; s4[3] += v.w;
-              } else {
-                _Pragma("unroll") for (int e = 0; e < 4; ++e) if (n + e < p.N) s4[e] += src[e];
-              }
-            }
-          }
-#pragma unroll
-          for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] = s4[e];
-        }
-    }
+    return;
   }
 
   // ---- epilogue: bias, ReLU, scatter into up to three column segments
@@ -288,7 +251,6 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
       }
     }
   }
-  // exactly one block per tile gets here (the only one, or the last of a split)
   if (p.bump && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *p.bump = *p.bump + 1;
 }
 
@@ -297,7 +259,6 @@ static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
   constexpr int BM = 32 * WM * TM, BN = 32 * WN * TN;
   dim3 grid((p.N + BN - 1) / BN, (p.M + BM - 1) / BM, p.ksplit);
   const size_t smem = (size_t)KW * 2 * (BM + BN) * kRowBytes;
-  if (KW > 1 && p.ksplit > 1 && p.out_kind != 2) return hipErrorInvalidValue;  // ticket path is single-group
   if (smem > 64 * 1024) {
     static bool raised = false;   // the limit is a per-function attribute; set it once
     if (!raised) {
@@ -312,8 +273,9 @@ static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
 }
 
 // Tile choice: 0 = 64x64 or smaller (2x2 waves and the k-group shapes below),
-// 1 = 128x128 (2x2 waves, 2x2 MFMA tiles each) once that still gives ~one block
-// per CU; measured best of {256x64, 128x64, 128x128, 256x128} on the output layer.
+// 1 = 128x128 (4x2 waves, 1x2 MFMA tiles each) once that still gives ~one block
+// per CU; measured best of {256x64, 128x64, 128x128 with 4 or 8 waves, 256x128}
+// on the output layer.
 int gemm_pick_tile(int M, int N) {
   if (M >= 128 && (long)((M + 127) / 128) * ((N + 127) / 128) >= 200) return 1;
   return 0;
@@ -334,11 +296,7 @@ hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
   if (p.M <= 0 || p.N <= 0) return hipSuccess;
   const int epc = dtype == 1 ? 64 : 32;
   if (p.K <= 0 || p.K % epc != 0 || p.ksplit < 1 || p.seg_w % 4 != 0) return hipErrorInvalidValue;
-  const bool ticket = p.ksplit > 1 && p.out_kind != 2;
-  if (ticket) {
-    const long tiles = (long)((p.M + 63) / 64) * ((p.N + 63) / 64);
-    if (!p.part || !p.counters || tiles > kGemmCounters) return hipErrorInvalidValue;
-  }
+  if (p.ksplit > 1 && p.out_kind != 2) return hipErrorInvalidValue;   // only partial outputs may be split across blocks
   const int tile = p.ksplit > 1 ? 0 : gemm_pick_tile(p.M, p.N);
   // A wave's MFMA chain over the whole k range is what bounds a small GEMM, and
   // only waves on different SIMDs run their chains in parallel.  When 64x64 tiles
@@ -349,17 +307,17 @@ hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
   const int chunks = (p.K / epc + p.ksplit - 1) / p.ksplit;
   const long tiles64 = (long)((p.M + 63) / 64) * ((p.N + 63) / 64) * p.ksplit;
   int shape = 0;
-  if (tile == 0 && !ticket) {
+  if (tile == 0) {
     if (tiles64 <= 64 && chunks >= 8) shape = 2;
     else if (tiles64 <= 192 && chunks >= 4) shape = 1;
   }
   if (dtype == 1) {
-    if (tile == 1) return launch_tile<bf16_t, 2, 2, 2, 2, 1, 2>(p, stream);
+    if (tile == 1) return launch_tile<bf16_t, 4, 2, 1, 2, 1, 2>(p, stream);
     if (shape == 2) return launch_tile<bf16_t, 1, 1, 1, 1, 4, 4>(p, stream);
     if (shape == 1) return launch_tile<bf16_t, 2, 1, 1, 1, 2, 4>(p, stream);
     return launch_tile<bf16_t, 2, 2, 1, 1, 1, 4>(p, stream);
   }
-  if (tile == 1) return launch_tile<float, 2, 2, 2, 2, 1, 2>(p, stream);
+  if (tile == 1) return launch_tile<float, 4, 2, 1, 2, 1, 2>(p, stream);
   if (shape == 2) return launch_tile<float, 1, 1, 1, 1, 4, 4>(p, stream);
   if (shape == 1) return launch_tile<float, 2, 1, 1, 1, 2, 4>(p, stream);
   return launch_tile<float, 2, 2, 1, 1, 1, 4>(p, stream);

@@ -13,11 +13,8 @@ namespace san {
 // out[s] + (*t_dev) * tstride[s] + m * ldo[s] + (n - s*seg_w).
 //   out_kind 0: store as T;  1: store fp32;  2: fp32 split-K partials
 //   [ksplit][M][N] at out[0] (no bias, no ReLU; the consumer reduces them).
-//   ksplit > 1 with out_kind 0/1: the blocks of a tile write partials to `part`
-//   ([ksplit][M][N] fp32) and the last one to arrive (ticket in `counters`, one
-//   int per 64x64 tile, all zero between launches) reduces them and stores.
+//   ksplit > 1 is only allowed with out_kind 2.
 //   bump: if not null, *bump is incremented once by the kernel (step counter).
-constexpr int kGemmCounters = 4096;
 struct GemmParams {
   const void* A; int lda;
   const void* W;              // [N][K]
@@ -25,7 +22,7 @@ struct GemmParams {
   void* out[3]; int ldo[3]; long long tstride[3];
   int seg_w;
   const int* t_dev;           // nullptr: no step offset
-  float* part; int* counters; int* bump;
+  int* bump;
   int M, N, K;                // K % (128 / sizeof(T)) == 0
   int relu, out_kind, ksplit;
 };
@@ -89,7 +86,6 @@ hipError_t launch_ln_reduce(int dtype, const float* part, int nsplit, int ldp, c
 // start of a decode step: last_tok[r] = tok[r]; anc[r][t] = r; hist[r][t] = tok[r]
 hipError_t launch_step_begin(const int* tok, int* last_tok, int* anc, int* hist, int ld, const int* t_dev, int rows,
                              hipStream_t stream);
-hipError_t launch_bump(int* t_dev, hipStream_t stream);
 hipError_t launch_to_f32(int dtype, const void* src, int lds, float* dst, int rows, int cols, hipStream_t stream);
 // dst[r][h][0..n) = src[r][h][0..n) with source row stride ldS
 hipError_t launch_compact_S(const float* src, int ldS, float* dst, int rows_h, int n, hipStream_t stream);
@@ -115,9 +111,9 @@ hipError_t launch_topk(const float* logits, const float* cum, const int* last_to
 // per sentence, in place: tab[r][j] = tab[parent[r]][j] for j < *t_dev
 hipError_t launch_reorder_table(int* tab, int ld, const int* parent, const int* t_dev, int batch, int beam,
                                 int max_t, hipStream_t stream);
-// per sentence, in place: st[l][r][c] = st[l][parent[r]][c]
-hipError_t launch_reorder_rows(float* st, const int* parent, int layers, int batch, int beam, int d,
-                               hipStream_t stream);
+// per sentence, in place: st[l][r][c] = st[l][parent[r]][c]; layer l starts at st + l*layer_stride
+hipError_t launch_reorder_rows(float* st, size_t layer_stride, const int* parent, int layers, int batch, int beam,
+                               int d, hipStream_t stream);
 
 // ------------------------------------------------------------- policy learning
 constexpr int kMaxPolicyLayers = 32;

@@ -208,14 +208,6 @@ hipError_t launch_step_begin(const int* tok, int* last_tok, int* anc, int* hist,
   return hipGetLastError();
 }
 
-__global__ void bump_kernel(int* t_dev) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) *t_dev = *t_dev + 1;
-}
-hipError_t launch_bump(int* t_dev, hipStream_t stream) {
-  hipLaunchKernelGGL(bump_kernel, dim3(1), dim3(64), 0, stream, t_dev);
-  return hipGetLastError();
-}
-
 template <typename T> __global__ void to_f32_kernel(const T* src, int lds, float* dst, int rows, int cols) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (size_t)rows * cols) return;
@@ -361,11 +353,11 @@ hipError_t launch_reorder_table(int* tab, int ld, const int* parent, const int* 
   return hipGetLastError();
 }
 
-__global__ void reorder_rows_kernel(float* st, const int* parent, int batch, int beam, int d) {
+__global__ void reorder_rows_kernel(float* st, size_t layer_stride, const int* parent, int batch, int beam, int d) {
   const int b = blockIdx.y, l = blockIdx.z;
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= d) return;
-  float* base = st + ((size_t)l * batch * beam + (size_t)b * beam) * d + c;
+  float* base = st + (size_t)l * layer_stride + (size_t)b * beam * d + c;
   float old[kMaxBeam];
 #pragma unroll
   for (int k = 0; k < kMaxBeam; ++k)
@@ -384,12 +376,12 @@ __global__ void reorder_rows_kernel(float* st, const int* parent, int batch, int
     }
   }
 }
-hipError_t launch_reorder_rows(float* st, const int* parent, int layers, int batch, int beam, int d,
-                               hipStream_t stream) {
+hipError_t launch_reorder_rows(float* st, size_t layer_stride, const int* parent, int layers, int batch, int beam,
+                               int d, hipStream_t stream) {
   if (beam > kMaxBeam) return hipErrorInvalidValue;
   if (layers <= 0) return hipSuccess;
   dim3 grid((d + 127) / 128, batch, layers);
-  hipLaunchKernelGGL(reorder_rows_kernel, grid, dim3(128), 0, stream, st, parent, batch, beam, d);
+  hipLaunchKernelGGL(reorder_rows_kernel, grid, dim3(128), 0, stream, st, layer_stride, parent, batch, beam, d);
   return hipGetLastError();
 }
 

@@ -70,7 +70,7 @@ struct san_ctx {
   void *x = nullptr, *qkv = nullptr, *ab = nullptr, *hb = nullptr, *cat = nullptr;
   float* part = nullptr;
   size_t part_elems = 0;
-  int* counters = nullptr;   // split-K tickets, all zero between launches
+  float* aan_all = nullptr;   // AAN running sums [layer][rows_max][d]
   // policy learning: running JS sums [2][L][L] (self, enc-dec), per-pair scratch, sample counts
   double* js_acc = nullptr;
   float* js_part = nullptr;
@@ -270,7 +270,6 @@ int gemm(san_ctx* c, const void* A, int lda, const void* W, const void* bias, in
   p.M = M; p.N = N; p.K = K; p.relu = relu; p.out_kind = out_kind;
   if (ksplit == 0) ksplit = 1;
   p.ksplit = ksplit;
-  p.part = c->part; p.counters = c->counters;
   LAUNCH(c, launch_gemm(c->dt, p, c->stream));
   return SAN_OK;
 }
@@ -394,7 +393,8 @@ static int build_ctx(san_ctx* c, const Blob& bl, const void* blob, const std::ve
         TRY(wtensor(c, &L.ab2, blob, o.aan.b2, d));
         TRY(wtensor(c, &L.awg, blob, o.wg, 4 * d * d));
         TRY(wtensor(c, &L.abg, blob, o.bg, 2 * d));
-        TRY(dalloc(c, (void**)&L.aan_sum, (size_t)c->rows_max * d * 4, false));
+        if (n == 0) TRY(dalloc(c, (void**)&c->aan_all, (size_t)Ld * c->rows_max * d * 4, false));
+        L.aan_sum = c->aan_all + (size_t)n * c->rows_max * d;   // all layers in one buffer: one reorder launch
       } else {
         if (L.self_head == n) {   // block head: fused [q;k;v] projection, key and value cache, weight scratch
           TRY(dalloc(c, &L.w_self, 3 * d * d * esz, true));
@@ -473,8 +473,6 @@ static int build_ctx(san_ctx* c, const Blob& bl, const void* blob, const std::ve
     c->part_elems = mrows * 2 * d;
     if (c->part_elems < (size_t)4 << 20) c->part_elems = (size_t)4 << 20;
     TRY(dalloc(c, (void**)&c->part, c->part_elems * 4, false));
-    TRY(dalloc(c, (void**)&c->counters, kGemmCounters * 4, false));
-    HIP_TRY(c, hipMemset(c->counters, 0, kGemmCounters * 4));
     TRY(dalloc(c, (void**)&c->t_dev, 256, false));
     TRY(dalloc(c, (void**)&c->anc, (size_t)c->rows_max * T * 4, false));
     if (nocache) TRY(dalloc(c, (void**)&c->hist, (size_t)c->rows_max * T * 4, false));
@@ -838,8 +836,8 @@ int san_beam_reorder(san_ctx* c, const int32_t* parent_idx_dev) {
   if (!c->cfg.use_cache) {
     HIP_TRY(c, launch_reorder_table(c->hist, T, parent_idx_dev, c->t_dev, c->batch, c->cfg.beam, T, c->stream));
   } else if (c->cfg.self_kind == SAN_SELF_AAN) {
-    for (DecLayer& L : c->dec)
-      HIP_TRY(c, launch_reorder_rows(L.aan_sum, parent_idx_dev, 1, c->batch, c->cfg.beam, c->d, c->stream));
+    HIP_TRY(c, launch_reorder_rows(c->aan_all, (size_t)c->rows_max * c->d, parent_idx_dev, (int)c->dec.size(), c->batch,
+                                   c->cfg.beam, c->d, c->stream));
   } else {
     // the caches stay where they are; only the per-row table of which cache row
     // holds each past position is permuted

@@ -17,9 +17,20 @@ struct Cand {
 __device__ __forceinline__ bool better(float av, int ai, float bv, int bi) {
   return av > bv || (av == bv && ai < bi);
 }
+template <int CTRL> __device__ __forceinline__ void best_step_dpp(Cand& c) {
+  const float ov = dpp_mov<CTRL>(c.v);
+  const int oi = dpp_mov_i<CTRL>(c.i);
+  if (better(ov, oi, c.v, c.i)) { c.v = ov; c.i = oi; }
+}
+// best (value, index) pair of the wave, in every lane: DPP moves inside the rows
+// of 16 lanes, two shuffles across rows
 __device__ __forceinline__ Cand wave_best(Cand c) {
+  best_step_dpp<kDppQuadSwap1>(c);
+  best_step_dpp<kDppQuadSwap2>(c);
+  best_step_dpp<kDppRowHalfMirror>(c);
+  best_step_dpp<kDppRowMirror>(c);
 #pragma unroll
-  for (int s = 1; s < kWave; s <<= 1) {
+  for (int s = 16; s < kWave; s <<= 1) {
     const float ov = __shfl_xor(c.v, s, kWave);
     const int oi = __shfl_xor(c.i, s, kWave);
     if (better(ov, oi, c.v, c.i)) { c.v = ov; c.i = oi; }
@@ -37,6 +48,7 @@ __device__ __forceinline__ void lse_merge(float& m, float& s, float om, float os
 }
 
 constexpr int kMaxK = 32;
+constexpr int kListCap = 1024;
 
 template <bool REG>
 __global__ __launch_bounds__(kTopkThreads) void topk_row_kernel(const float* logits, const int* last_tok,
@@ -46,6 +58,11 @@ __global__ __launch_bounds__(kTopkThreads) void topk_row_kernel(const float* log
   __shared__ float red_m[NW], red_s[NW];
   __shared__ float wc_v[NW * kMaxK];   // every wave's k best values ...
   __shared__ int wc_i[NW * kMaxK];     // ... and their word ids
+  __shared__ float list_v[kListCap];   // elements >= threshold
+  __shared__ int list_i[kListCap];
+  __shared__ int list_n;
+  __shared__ float thresh;
+  bool use_list = false;
   const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
   const float* x = logits + (size_t)row * vocab;
   const int nit = (vocab + kTopkThreads - 1) / kTopkThreads;
@@ -85,40 +102,64 @@ __global__ __launch_bounds__(kTopkThreads) void topk_row_kernel(const float* log
   }
   if (lane == 0) { red_m[wid] = m; red_s[wid] = s; }
 
-  // ---- each wave's k best, in order (value down, index up)
   const bool finished = eos_id >= 0 && last_tok[row] == eos_id;
-  if (REG && k <= 4) {
-    // small k: every thread first sorts out its own 4 best (its values arrive in
-    // increasing index order, so a strict '>' keeps ties in index order); the k
-    // wave rounds then only look at the heads of these lists
-    float lv[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-    int li[4] = {0x7fffffff, 0x7fffffff, 0x7fffffff, 0x7fffffff};
+  if (REG) {
+    // ---- threshold pass.  The k-th largest of the per-thread maxima is a lower
+    // bound T on the k-th largest element, so every element of the row's top k is
+    // >= T, and usually only a handful of elements are.  Those go to a short list in
+    // LDS that wave 0 orders; a list overflow (masses of equal values) falls back to
+    // the general rounds below.
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int it = 0; it < kTopkVpt; ++it) tmax = fmaxf(tmax, reg[it]);
+    {
+      // each wave's k largest thread maxima (k rounds of "largest below the previous", by value and lane)
+      float pv = INFINITY;
+      int pl = -1;
+      for (int round = 0; round < k; ++round) {
+        const bool after = (tmax < pv) || (tmax == pv && lane > pl);
+        Cand best = {after ? tmax : -INFINITY, after ? lane : 0x7fffffff};
+        best = wave_best(best);
+        if (lane == 0) wc_v[wid * k + round] = best.v;
+        pv = best.v;
+        pl = best.i;
+      }
+    }
+    if (tid == 0) list_n = 0;
+    __syncthreads();
+    if (wid == 0) {
+      // k-th largest of the NW * k wave values (duplicates count)
+      const int nc = NW * k;
+      float pv = INFINITY;
+      int pc = -1;
+      for (int round = 0; round < k; ++round) {
+        Cand best = {-INFINITY, 0x7fffffff};
+        for (int c = lane; c < nc; c += kWave) {
+          const float v = wc_v[c];
+          const bool after = (v < pv) || (v == pv && c > pc);
+          if (after && better(v, c, best.v, best.i)) { best.v = v; best.i = c; }
+        }
+        best = wave_best(best);
+        pv = best.v;
+        pc = best.i;
+      }
+      if (lane == 0) thresh = pv;
+    }
+    __syncthreads();
+    const float T = thresh;
 #pragma unroll
     for (int it = 0; it < kTopkVpt; ++it) {
       const int idx = it * kTopkThreads + tid;
-      float v = reg[it];
-      int vi = idx < vocab ? idx : 0x7fffffff;
-      if (idx < vocab && v > lv[3]) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {   // insert, pushing the smaller ones down
-          if (v > lv[q]) {
-            const float tv = lv[q]; const int ti = li[q];
-            lv[q] = v; li[q] = vi; v = tv; vi = ti;
-          }
-        }
+      if (idx < vocab && reg[it] >= T) {
+        const int pos = atomicAdd(&list_n, 1);
+        if (pos < kListCap) { list_v[pos] = reg[it]; list_i[pos] = idx; }
       }
     }
-    for (int round = 0; round < k; ++round) {
-      Cand best = {lv[0], li[0]};
-      best = wave_best(best);
-      if (lane == 0) { wc_v[wid * k + round] = best.v; wc_i[wid * k + round] = best.i; }
-      if (li[0] == best.i && best.i != 0x7fffffff) {   // the winner's owner pops its list
-        lv[0] = lv[1]; li[0] = li[1]; lv[1] = lv[2]; li[1] = li[2]; lv[2] = lv[3]; li[2] = li[3];
-        lv[3] = -INFINITY; li[3] = 0x7fffffff;
-      }
-    }
-  } else {
-    // general k: k rounds, each picking the best element after the previous pick
+    __syncthreads();
+    use_list = list_n <= kListCap;
+  }
+  if (!use_list) {
+    // ---- general path: each wave's k best by k rounds over its elements
     float pv = INFINITY;
     int pi = -1;
     for (int round = 0; round < k; ++round) {
@@ -162,15 +203,17 @@ __global__ __launch_bounds__(kTopkThreads) void topk_row_kernel(const float* log
     }
     return;
   }
-  // ---- wave 0 merges the NW * k wave candidates
-  const int nc = NW * k;
+  // ---- wave 0 orders the candidates (the short list, or the NW * k wave candidates)
+  const int nc = use_list ? list_n : NW * k;
+  const float* cv = use_list ? list_v : wc_v;
+  const int* ci = use_list ? list_i : wc_i;
   float pv = INFINITY;
   int pi = -1;
   for (int round = 0; round < k; ++round) {
     Cand best = {-INFINITY, 0x7fffffff};
     for (int c = lane; c < nc; c += kWave) {
-      const float v = wc_v[c];
-      const int idx = wc_i[c];
+      const float v = cv[c];
+      const int idx = ci[c];
       const bool after = (v < pv) || (v == pv && idx > pi);
       if (idx != 0x7fffffff && after && better(v, idx, best.v, best.i)) { best.v = v; best.i = idx; }
     }
