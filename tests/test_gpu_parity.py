@@ -436,3 +436,44 @@ def test_decode_n_equals_step_by_step(use_graph):
             gpu.decode_n(30, tokens, cum, big_t, big_t.clone(), logits, use_graph)
         assert e.value.code == sb.SAN_ECAPACITY
         gpu.close()
+
+
+# ------------------------------------------------------ head widths, extreme shapes
+@pytest.mark.parametrize("d,H,dtype", [(128, 8, "f32"), (128, 4, "f32"), (256, 2, "f32"), (128, 8, "bf16"),
+                                       (256, 8, "bf16"), (256, 2, "bf16")])
+def test_head_widths(d, H, dtype):
+    """Head widths 16, 32 and 128 take other lane mappings of the attention kernel
+    than the 64 of the paper's models."""
+    cfg = mid_cfg(d=d, H=H, F=2 * d, dtype=dtype, steps=37, batch=3, beam=3, self_pi=[2, 2], encdec_pi=[1, 3])
+    w = wl.make_weights(cfg, seed=17, sharp=3.0)
+    src, lens = ragged(cfg, 17)
+    for share in ("A", "S"):
+        gpu = hz.make_gpu(cfg, w, share=share)
+        ls = hz.Lockstep(gpu, hz.make_oracle(cfg, w, share=share), src, lens, cfg["beam"])
+        for t in range(cfg["steps"]):
+            ls.step(tie_tol=5e-4 if dtype == "f32" else 0.2)
+        assert max(ls.log["logit_err"]) <= (F32_TOL if dtype == "f32" else BF16_TOL), (share, max(ls.log["logit_err"]))
+        gpu.close()
+
+
+def test_maximum_beam_and_long_cache():
+    """beam = 32 (the largest the library takes) and a cache of 300 positions
+    (several chunks of the attention pipeline plus a ragged tail)."""
+    cfg = mid_cfg(batch=2, beam=32, steps=6, V=2004)
+    w = wl.make_weights(cfg, seed=18, sharp=4.0)
+    src, lens = ragged(cfg, 18)
+    gpu = hz.make_gpu(cfg, w)
+    ls = hz.Lockstep(gpu, hz.make_oracle(cfg, w), src, lens, 32)
+    for t in range(6):
+        ls.step(tie_tol=5e-4)
+    assert max(ls.log["logit_err"]) <= F32_TOL
+    gpu.close()
+    cfg = mid_cfg(batch=2, beam=2, steps=300, n_dec=2, self_pi=[2], encdec_pi=[2])
+    w = wl.make_weights(cfg, seed=19, sharp=4.0)
+    src, lens = ragged(cfg, 19)
+    gpu = hz.make_gpu(cfg, w)
+    ls = hz.Lockstep(gpu, hz.make_oracle(cfg, w), src, lens, 2)
+    for t in range(300):
+        ls.step(tie_tol=5e-4)
+    assert max(ls.log["logit_err"]) <= F32_TOL
+    gpu.close()
