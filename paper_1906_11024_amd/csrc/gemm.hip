@@ -13,9 +13,11 @@
 // device-scope fence per block costs more than the whole GEMM on this multi-XCD
 // part).  The others keep the whole k range in one block and run the epilogue
 // (bias, ReLU, scatter into the q buffer / key cache / value cache) themselves.
-// The weight rows feed the MFMA "A" side and the activation rows the "B" side, so
-// a lane ends up with 4 consecutive output columns of one output row, which makes
-// the epilogue's bias loads and stores 16-byte wide.
+// The activation rows feed the MFMA "A" side and the weight rows the "B" side, so
+// the 32 lanes of a half-wave hold 32 consecutive output columns of one row and
+// every epilogue store writes whole 128-byte row segments (16-byte stores per lane
+// with the roles swapped measured slower on the wide output layer: each store
+// instruction then touched 64 different cache lines).
 #include "common.h"
 #include "kernels.h"
 
@@ -25,10 +27,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte fragment as a first-class vector
 
-constexpr int kChunkBytes = 128;  // k-extent of one LDS stage, per row
-constexpr int kRowBytes = 144;    // padded LDS row
 
-template <typename T> __device__ __forceinline__ void mma_frag(f32x16& acc, const u32x4& w, const u32x4& x);
+template <typename T> __device__ __forceinline__ void mma_frag(f32x16& acc, const u32x4& w, const u32x4& x);   // acc += w-rows x x-rows^T
 
 // fp32: a 16-byte fragment is 4 k-values -> 4 rank-2 updates (32x32x2).  Lanes
 // 0-31 carry k = 0..3 of the 32-byte sub-step, lanes 32-63 carry k = 4..7; the
@@ -44,12 +44,17 @@ template <> __device__ __forceinline__ void mma_frag<bf16_t>(f32x16& acc, const 
   acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x), acc, 0, 0, 0);
 }
 
-template <typename T, int WM, int WN, int TM, int TN, int KW, int D>
+// CB = bytes of k per row in one LDS stage (128 or 256); rows are padded by 16
+// bytes, which keeps the 16-byte fragment reads of 16 neighbouring lanes on
+// distinct banks for both sizes.
+template <typename T, int WM, int WN, int TM, int TN, int KW, int D, int CB>
 __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
+  constexpr int kRowBytes = CB + 16;
+  constexpr int SEGS = CB / 16;                      // 16-byte segments of a row chunk
   constexpr int NG = WM * WN * 64;                   // threads of one k-group
   constexpr int BM = 32 * WM * TM, BN = 32 * WN * TN;
-  constexpr int EPC = kChunkBytes / (int)sizeof(T);  // elements per chunk
-  constexpr int RPP = NG / 8;                        // rows covered by one pass of 16-byte loads
+  constexpr int EPC = CB / (int)sizeof(T);           // elements per chunk
+  constexpr int RPP = NG / SEGS;                     // rows covered by one pass of 16-byte loads
   constexpr int LA = BM / RPP, LB = BN / RPP;        // 16-byte loads per thread per chunk
   constexpr int STAGE = 2 * (BM + BN) * kRowBytes;   // LDS bytes of one k-group (double buffered)
   static_assert(BM % RPP == 0 && BN % RPP == 0 && D % 2 == 0, "tile shape");
@@ -75,7 +80,7 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
 
   const T* A = reinterpret_cast<const T*>(p.A);
   const T* W = reinterpret_cast<const T*>(p.W);
-  const int lrow = tg >> 3, lseg = tg & 7;  // this thread's row and 16-byte segment of a chunk
+  const int lrow = tg / SEGS, lseg = tg % SEGS;  // this thread's row and 16-byte segment of a chunk
   const T* a_ptr[LA];
   const T* w_ptr[LB];
 #pragma unroll
@@ -131,7 +136,7 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
           const unsigned char* xs = Xs + (buf * BM + wm * 32 * TM + l32) * kRowBytes + kh * 16;
           const unsigned char* ws = Ws + (buf * BN + wn * 32 * TN + l32) * kRowBytes + kh * 16;
 #pragma unroll
-          for (int sub = 0; sub < 4; ++sub) {
+          for (int sub = 0; sub < CB / 32; ++sub) {
             u32x4 xf[TM], wf[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i) xf[i] = *reinterpret_cast<const u32x4*>(xs + i * 32 * kRowBytes + sub * 32);
@@ -140,7 +145,7 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-              for (int j = 0; j < TN; ++j) mma_frag<T>(acc[i][j], wf[j], xf[i]);
+              for (int j = 0; j < TN; ++j) mma_frag<T>(acc[i][j], xf[i], wf[j]);
           }
         }
       }
@@ -176,30 +181,24 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
             acc[i][j][v] += red[((((g - 1) * (WM * WN) + w_in) * (TM * TN) + i * TN + j) * 16 + v) * 64 + lane];
   }
 
-  // acc[i][j][v]: output row m = tile_m + l32, column n = tile_n + (v/4)*8 + kh*4 + (v%4).
-  const bool n_vec = (p.N % 4) == 0;
+  // acc[i][j][v]: output row m = tile_m + (v/4)*8 + kh*4 + (v%4), column n = tile_n + l32.
+  // For a fixed v the 32 lanes of a half-wave hold 32 consecutive columns of one
+  // row, so every store instruction writes two contiguous 128-byte (fp32) row
+  // segments -- whole cache lines, which matters for the wide output layer.
   if (p.out_kind == 2) {
     // ---- fp32 partials [ksplit][M][N]; the consumer (LayerNorm kernel) adds them up in a fixed order
     float* part = reinterpret_cast<float*>(p.out[0]);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int m = m0 + (wm * TM + i) * 32 + l32;
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < TN; ++j) {
+        const int n = n0 + (wn * TN + j) * 32 + l32;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int n = n0 + (wn * TN + j) * 32 + g * 8 + kh * 4;
-          if (m < p.M && n < p.N) {
-            float* dst = part + ((size_t)blockIdx.z * p.M + m) * p.N + n;
-            if (n_vec) {
-              *reinterpret_cast<float4*>(dst) =
-                  make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-            } else {
-              _Pragma("unroll") for (int e = 0; e < 4; ++e) if (n + e < p.N) dst[e] = acc[i][j][4 * g + e];
-            }
-          }
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + (wm * TM + i) * 32 + (v >> 2) * 8 + kh * 4 + (v & 3);
+          if (m < p.M && n < p.N) part[((size_t)blockIdx.z * p.M + m) * p.N + n] = acc[i][j][v];
         }
-    }
+      }
     return;
   }
 
@@ -207,68 +206,49 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
   const int t = p.t_dev ? *p.t_dev : 0;
   const T* bias = reinterpret_cast<const T*>(p.bias);
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int m = m0 + (wm * TM + i) * 32 + l32;
-    if (m >= p.M) continue;
+  for (int j = 0; j < TN; ++j) {
+    const int n = n0 + (wn * TN + j) * 32 + l32;
+    if (n >= p.N) continue;
+    const float bv = bias ? to_f32(bias[n]) : 0.f;
+    const int s = n / p.seg_w;
+    const int nn = n - s * p.seg_w;
+    void* obase = s == 0 ? p.out[0] : (s == 1 ? p.out[1] : p.out[2]);
+    const int ldo = s == 0 ? p.ldo[0] : (s == 1 ? p.ldo[1] : p.ldo[2]);
+    const long long ts = s == 0 ? p.tstride[0] : (s == 1 ? p.tstride[1] : p.tstride[2]);
+    const size_t base = (size_t)t * ts + nn;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n = n0 + (wn * TN + j) * 32 + g * 8 + kh * 4;
-        if (n >= p.N) continue;
-        float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-        const bool full = (n + 3 < p.N);
-        if (bias) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (n + e < p.N) v[e] += to_f32(bias[n + e]);
-        }
-        if (p.relu) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
-        }
-        const int s = n / p.seg_w;   // segments are multiples of 4 columns wide
-        const int nn = n - s * p.seg_w;
-        void* obase = s == 0 ? p.out[0] : (s == 1 ? p.out[1] : p.out[2]);
-        const int ldo = s == 0 ? p.ldo[0] : (s == 1 ? p.ldo[1] : p.ldo[2]);
-        const long long ts = s == 0 ? p.tstride[0] : (s == 1 ? p.tstride[1] : p.tstride[2]);
-        const size_t off = (size_t)t * ts + (size_t)m * ldo + nn;
-        if (p.out_kind == 1) {
-          float* dst = reinterpret_cast<float*>(obase) + off;
-          if (full && n_vec) {
-            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-          } else {
-            _Pragma("unroll") for (int e = 0; e < 4; ++e) if (n + e < p.N) dst[e] = v[e];
-          }
-        } else {
-          T* dst = reinterpret_cast<T*>(obase) + off;
-          if (full && n_vec) {
-            store4(dst, make_float4(v[0], v[1], v[2], v[3]));
-          } else {
-            _Pragma("unroll") for (int e = 0; e < 4; ++e) if (n + e < p.N) dst[e] = from_f32<T>(v[e]);
-          }
-        }
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + (wm * TM + i) * 32 + (v >> 2) * 8 + kh * 4 + (v & 3);
+        if (m >= p.M) continue;
+        float val = acc[i][j][v] + bv;
+        if (p.relu) val = fmaxf(val, 0.f);
+        const size_t off = base + (size_t)m * ldo;
+        if (p.out_kind == 1) reinterpret_cast<float*>(obase)[off] = val;
+        else reinterpret_cast<T*>(obase)[off] = from_f32<T>(val);
       }
     }
   }
   if (p.bump && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *p.bump = *p.bump + 1;
 }
 
-template <typename T, int WM, int WN, int TM, int TN, int KW, int D>
+template <typename T, int WM, int WN, int TM, int TN, int KW, int D, int CB = 128>
 static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
   constexpr int BM = 32 * WM * TM, BN = 32 * WN * TN;
+  constexpr int kRowBytes = CB + 16;
   dim3 grid((p.N + BN - 1) / BN, (p.M + BM - 1) / BM, p.ksplit);
   const size_t smem = (size_t)KW * 2 * (BM + BN) * kRowBytes;
   if (smem > 64 * 1024) {
     static bool raised = false;   // the limit is a per-function attribute; set it once
     if (!raised) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, WM, WN, TM, TN, KW, D>),
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, WM, WN, TM, TN, KW, D, CB>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
       if (e != hipSuccess) return e;
       raised = true;
     }
   }
-  hipLaunchKernelGGL((gemm_kernel<T, WM, WN, TM, TN, KW, D>), grid, dim3(WM * WN * KW * 64), smem, stream, p);
+  hipLaunchKernelGGL((gemm_kernel<T, WM, WN, TM, TN, KW, D, CB>), grid, dim3(WM * WN * KW * 64), smem, stream, p);
   return hipGetLastError();
 }
 
@@ -294,8 +274,11 @@ int gemm_pick_ksplit(int M, int N, int K, int dtype) {
 
 hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
   if (p.M <= 0 || p.N <= 0) return hipSuccess;
+  // bf16 MFMAs retire a 128-byte chunk four times faster than fp32 ones, so bf16
+  // GEMMs walk k in 256-byte chunks (half the barriers) whenever K allows it
+  const bool wide = dtype == 1 && p.K % 128 == 0;
   const int epc = dtype == 1 ? 64 : 32;
-  if (p.K <= 0 || p.K % epc != 0 || p.ksplit < 1 || p.seg_w % 4 != 0) return hipErrorInvalidValue;
+  if (p.K <= 0 || p.K % epc != 0 || p.ksplit < 1) return hipErrorInvalidValue;
   if (p.ksplit > 1 && p.out_kind != 2) return hipErrorInvalidValue;   // only partial outputs may be split across blocks
   const int tile = p.ksplit > 1 ? 0 : gemm_pick_tile(p.M, p.N);
   // A wave's MFMA chain over the whole k range is what bounds a small GEMM, and
@@ -304,7 +287,7 @@ hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
   // 2 or 4 wave groups (reduced through LDS), aiming at ~one wave per SIMD:
   //   shape 1: 64x32 tiles, 2 waves x 2 k-groups;  shape 2: 32x32 tiles, 1 wave x 4 k-groups.
   // (64x32 with 4 k-groups, 32x64 and 64x64 with 2, 32x32 with 8 all measured within 3% of these.)
-  const int chunks = (p.K / epc + p.ksplit - 1) / p.ksplit;
+  const int chunks = (p.K / (dtype == 1 ? 64 : 32) + p.ksplit - 1) / p.ksplit;   // in 128-byte units
   const long tiles64 = (long)((p.M + 63) / 64) * ((p.N + 63) / 64) * p.ksplit;
   int shape = 0;
   if (tile == 0) {
@@ -312,6 +295,11 @@ hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
     else if (tiles64 <= 192 && chunks >= 4) shape = 1;
   }
   if (dtype == 1) {
+    if (wide && tile != 1) {   // (the 128x128 tile with wide chunks would not fit two blocks per CU: slower)
+      if (shape == 2) return launch_tile<bf16_t, 1, 1, 1, 1, 4, 2, 256>(p, stream);
+      if (shape == 1) return launch_tile<bf16_t, 2, 1, 1, 1, 2, 2, 256>(p, stream);
+      return launch_tile<bf16_t, 2, 2, 1, 1, 1, 2, 256>(p, stream);
+    }
     if (tile == 1) return launch_tile<bf16_t, 4, 2, 1, 2, 1, 2>(p, stream);
     if (shape == 2) return launch_tile<bf16_t, 1, 1, 1, 1, 4, 4>(p, stream);
     if (shape == 1) return launch_tile<bf16_t, 2, 1, 1, 1, 2, 4>(p, stream);
