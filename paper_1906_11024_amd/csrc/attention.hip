@@ -48,7 +48,8 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
   const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
   const int c = lane % LPP, g = lane / LPP;
   float* sc = reinterpret_cast<float*>(smem) + (size_t)wid * NQ * p.lmax;                 // [NQ][lmax]
-  int* slots = reinterpret_cast<int*>(smem + sizeof(float) * kWavesPerBlock * NQ * p.lmax);  // [lmax], self mode
+  // self mode: element offset of key j's row inside the cache, [lmax]
+  long long* slot_off = reinterpret_cast<long long*>(smem + sizeof(float) * kWavesPerBlock * NQ * p.lmax);
 
   const int nhg = (p.H + kWavesPerBlock - 1) / kWavesPerBlock;
   const int hg = blockIdx.x % nhg;
@@ -64,8 +65,12 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
     const int r = rest;
     // slot of key j: position-major cache, row taken from the ancestry table.  The
     // whole table row is fetched (entries past the current step are never used),
-    // so these loads do not wait for the step counter.
-    for (int j = threadIdx.x; j < p.lmax; j += blockDim.x) slots[j] = j * p.rows + p.anc[(size_t)r * p.ld_anc + j];
+    // so these loads do not wait for the step counter.  The 64-bit multiply by the
+    // row stride is done here, once per key, not once per load (K and V caches
+    // have the same layout in this mode).
+    const long long ld_cache = p.apply ? p.ldv : p.ldk;
+    for (int j = threadIdx.x; j < p.lmax; j += blockDim.x)
+      slot_off[j] = (long long)(j * p.rows + p.anc[(size_t)r * p.ld_anc + j]) * ld_cache;
     n = *p.t_dev + 1;
     n = min(n, p.lmax);
     qrow[0] = r;
@@ -102,15 +107,24 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
   T* Op = reinterpret_cast<T*>(p.out);
   const int col = h * DH + c * EPL;
   const bool self_mode = p.self_mode != 0;
+  // this lane's column of the stream's first slot; per key only an offset is added
+  Kp += slot_base * p.ldk + col;
+  Vp += slot_base * p.ldv + col;
+  const unsigned ldk = (unsigned)p.ldk, ldv = (unsigned)p.ldv;   // < 2^24 (checked at launch)
 
-  // One chunk = U load instructions = CH positions; positions past n-1 re-read
-  // position n-1 (never out of bounds) and are ignored later.
-  auto load_chunk = [&](const T* base, long long ld, int j0, uint4 (&buf)[U]) {
+  // One chunk = U load instructions = CH positions; inside the last instruction
+  // positions past n-1 re-read position n-1 (never out of bounds) and are ignored
+  // later.
+  auto load_chunk = [&](const T* base, unsigned ld, int j0, uint4 (&buf)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int j = min(j0 + u * PPL + g, n - 1);
-      const long long slot = self_mode ? (long long)slots[j] : slot_base + j;
-      buf[u] = *reinterpret_cast<const uint4*>(base + slot * ld + col);
+      if (j0 + u * PPL < n) {   // wave-uniform: instructions wholly past the end are not issued
+        const int j = min(j0 + u * PPL + g, n - 1);
+        const long long off = self_mode ? slot_off[j] : (long long)__umul24((unsigned)j, ld);   // j < 2^10
+        buf[u] = *reinterpret_cast<const uint4*>(base + off);
+      } else {
+        buf[u] = make_uint4(0u, 0u, 0u, 0u);
+      }
     }
   };
 
@@ -119,8 +133,8 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
   // so a short stream costs a single memory round trip.
   uint4 kb0[U], kb1[U], vb0[U], vb1[U];
   if (n > 0) {
-    if (!p.apply) load_chunk(Kp, p.ldk, 0, kb0);
-    load_chunk(Vp, p.ldv, 0, vb0);
+    if (!p.apply) load_chunk(Kp, ldk, 0, kb0);
+    load_chunk(Vp, ldv, 0, vb0);
   }
 
   if (!p.apply) {
@@ -154,15 +168,15 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
       }
     };
     for (int j0 = 0; j0 < n; j0 += 2 * CH) {
-      if (j0 + CH < n) load_chunk(Kp, p.ldk, j0 + CH, kb1);
+      if (j0 + CH < n) load_chunk(Kp, ldk, j0 + CH, kb1);
       scores(j0, kb0);
       if (j0 + CH < n) {
-        if (j0 + 2 * CH < n) load_chunk(Kp, p.ldk, j0 + 2 * CH, kb0);
+        if (j0 + 2 * CH < n) load_chunk(Kp, ldk, j0 + 2 * CH, kb0);
         scores(j0 + CH, kb1);
       }
     }
     wave_lds_sync();
-    if (CH < n) load_chunk(Vp, p.ldv, CH, vb1);   // second V chunk travels during the softmax
+    if (CH < n) load_chunk(Vp, ldv, CH, vb1);   // second V chunk travels during the softmax
     // ---- softmax over key positions, one query at a time
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
@@ -189,7 +203,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
         for (int j = n + lane; j < p.ldS; j += kWave) Sg[j] = 0.f;
     }
   } else {
-    if (CH < n) load_chunk(Vp, p.ldv, CH, vb1);
+    if (CH < n) load_chunk(Vp, ldv, CH, vb1);
     // ---- shared weights: S^{m+i} = S^m (Eq. 4)
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
@@ -224,10 +238,10 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
   };
   for (int j0 = 0; j0 < n; j0 += 2 * CH) {   // V chunks are requested two chunks ahead
     weighted(j0, vb0);
-    if (j0 + 2 * CH < n) load_chunk(Vp, p.ldv, j0 + 2 * CH, vb0);
+    if (j0 + 2 * CH < n) load_chunk(Vp, ldv, j0 + 2 * CH, vb0);
     if (j0 + CH < n) {
       weighted(j0 + CH, vb1);
-      if (j0 + 3 * CH < n) load_chunk(Vp, p.ldv, j0 + 3 * CH, vb1);
+      if (j0 + 3 * CH < n) load_chunk(Vp, ldv, j0 + 3 * CH, vb1);
     }
   }
 #pragma unroll
@@ -241,7 +255,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
 template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p, hipStream_t stream) {
   const int nhg = (p.H + kWavesPerBlock - 1) / kWavesPerBlock;
   if (p.self_mode) {
-    const size_t smem = sizeof(float) * kWavesPerBlock * p.lmax + sizeof(int) * p.lmax;
+    const size_t smem = sizeof(float) * kWavesPerBlock * p.lmax + sizeof(long long) * p.lmax;
     dim3 grid((unsigned)(p.rows * nhg));
     hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(256), smem, stream, p);
   } else if (p.rpg <= 32 && (long)p.groups * p.H * ((p.rpg + 3) / 4) < 1024) {
@@ -263,6 +277,8 @@ template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p,
 hipError_t launch_attention(int dtype, const AttnParams& p, hipStream_t stream) {
   if (p.rows <= 0 || p.lmax <= 0) return hipSuccess;
   if (p.lmax > 1024) return hipErrorInvalidValue;   // score rows must fit 64 KB of LDS
+  if (p.ldk < 0 || p.ldv < 0 || p.ldk >= (1 << 24) || p.ldv >= (1 << 24)) return hipErrorInvalidValue;
+  if (p.self_mode && p.ldk != p.ldv && !p.apply) return hipErrorInvalidValue;   // one offset table serves both caches
   const int lpp = dtype == 1 ? p.dh / 8 : p.dh / 4;
   if (dtype == 1) {
     switch (lpp) {
