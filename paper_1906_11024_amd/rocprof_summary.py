@@ -70,14 +70,12 @@ def attention(db: str, cfg_name: str) -> None:
     T, B, d = cfg["steps"], cfg["batch"] * cfg["beam"], cfg["d"]
     esz = 2 if cfg["dtype"] == "bf16" else 4
     cur = sqlite3.connect(db).cursor()
-    durs = [r[0] for r in cur.execute(
-        "select duration from kernels where name like '%attention_kernel%' and grid_y = 1 and "
-        "grid_x = (select grid_x from kernels where name like '%attention_kernel%' group by grid_x "
-        "order by count(*) desc limit 1) order by start")]
+    # every attention launch in start order: the encoder's n_enc launches come first (bench.py encodes once
+    # and rewinds), then `per` launches per decode step; the run ends on a decode boundary
+    durs = [r[0] for r in cur.execute("select duration from kernels where name like '%attention_kernel%' order by start")]
     per = len(order)
-    nsteps = len(durs) // per
-    durs = durs[len(durs) - (nsteps // T) * T * per:]            # whole decodes only, from the end
-    ndec = len(durs) // (T * per)
+    ndec = (len(durs) - cfg["n_enc"]) // (T * per)
+    durs = durs[len(durs) - ndec * T * per:]                     # whole decodes only, from the end
     acc = {r: [[0.0, 0] for _ in range(T)] for r in set(order)}
     for i, dur in enumerate(durs):
         t = (i // per) % T
