@@ -130,7 +130,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
-              "decoding shards by sentence with no communication, see DESIGN.md", file=sys.stderr)
+              "decoding shards by sentence (independent replicas, no communication)", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch

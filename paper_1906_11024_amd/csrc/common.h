@@ -113,25 +113,60 @@ template <int N> __device__ __forceinline__ float group_max(float v) {
   return v;
 }
 
-// Reductions over the lanes whose ids differ only in the bits of `mask_bits`
-// (a contiguous run of xor strides from `lo` up to, not including, `hi`).
+// Cross-row exchanges without LDS traffic: v_permlane16_swap / v_permlane32_swap
+// (gfx950) swap the odd 16- (32-) lane rows of one register with the even rows of
+// another.  Fed the same value twice, the two results hold, in every lane, the
+// values of lane and of lane ^ 16 (lane ^ 32).
+__device__ __forceinline__ float sum_xor16(float v) {
+  const unsigned x = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float sum_xor32(float v) {
+  const unsigned x = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float max_xor16(float v) {
+  const unsigned x = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float max_xor32(float v) {
+  const unsigned x = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// The value lane ^ 16 (lane ^ 32) holds.
+__device__ __forceinline__ unsigned other_xor16(unsigned x) {
+  const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+  return (threadIdx.x & 16) ? r[0] : r[1];
+}
+__device__ __forceinline__ unsigned other_xor32(unsigned x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+  return (threadIdx.x & 32) ? r[0] : r[1];
+}
+
+// Sum over the lanes that agree with this one in the low log2(LO) bits of the
+// lane id, inside aligned groups of HI lanes (LO, HI powers of two, HI = 64 here).
+// Inside a 16-lane row the partners are reached by rotating the row by LO, 2*LO,
+// ... 8 lanes (DPP row_ror), across rows by the swaps above.
 template <int LO, int HI> __device__ __forceinline__ float xor_sum(float v) {
-#pragma unroll
-  for (int s = LO; s < HI; s <<= 1) v += __shfl_xor(v, s, kWave);
-  return v;
+  static_assert(HI == kWave, "reduces up to the whole wave");
+  if (LO <= 1) v += dpp_mov<0x121>(v);
+  if (LO <= 2) v += dpp_mov<0x122>(v);
+  if (LO <= 4) v += dpp_mov<0x124>(v);
+  if (LO <= 8) v += dpp_mov<0x128>(v);
+  if (LO <= 16) v = sum_xor16(v);
+  return sum_xor32(v);
 }
-__device__ __forceinline__ float wave_sum(float v) { return xor_sum<16, kWave>(group_sum<16>(v)); }
-__device__ __forceinline__ float wave_max(float v) {
-  v = group_max<16>(v);
-  v = fmaxf(v, __shfl_xor(v, 16, kWave));
-  v = fmaxf(v, __shfl_xor(v, 32, kWave));
-  return v;
-}
+__device__ __forceinline__ float wave_sum(float v) { return sum_xor32(sum_xor16(group_sum<16>(v))); }
+__device__ __forceinline__ float wave_max(float v) { return max_xor32(max_xor16(group_max<16>(v))); }
 // sum over aligned groups of LPP lanes (LPP up to 32)
 template <int LPP> __device__ __forceinline__ float lanes_sum(float v) {
   if (LPP <= 16) return group_sum<(LPP <= 16 ? LPP : 16)>(v);
-  v = group_sum<16>(v);
-  return v + __shfl_xor(v, 16, kWave);
+  return sum_xor16(group_sum<16>(v));
 }
 
 }  // namespace san

@@ -23,16 +23,20 @@ template <int CTRL> __device__ __forceinline__ void best_step_dpp(Cand& c) {
   if (better(ov, oi, c.v, c.i)) { c.v = ov; c.i = oi; }
 }
 // best (value, index) pair of the wave, in every lane: DPP moves inside the rows
-// of 16 lanes, two shuffles across rows
+// of 16 lanes, two row swaps across rows
 __device__ __forceinline__ Cand wave_best(Cand c) {
   best_step_dpp<kDppQuadSwap1>(c);
   best_step_dpp<kDppQuadSwap2>(c);
   best_step_dpp<kDppRowHalfMirror>(c);
   best_step_dpp<kDppRowMirror>(c);
-#pragma unroll
-  for (int s = 16; s < kWave; s <<= 1) {
-    const float ov = __shfl_xor(c.v, s, kWave);
-    const int oi = __shfl_xor(c.i, s, kWave);
+  {
+    const float ov = __uint_as_float(other_xor16(__float_as_uint(c.v)));
+    const int oi = (int)other_xor16((unsigned)c.i);
+    if (better(ov, oi, c.v, c.i)) { c.v = ov; c.i = oi; }
+  }
+  {
+    const float ov = __uint_as_float(other_xor32(__float_as_uint(c.v)));
+    const int oi = (int)other_xor32((unsigned)c.i);
     if (better(ov, oi, c.v, c.i)) { c.v = ov; c.i = oi; }
   }
   return c;
