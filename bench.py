@@ -213,6 +213,44 @@ def main():
                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                     "bytes_per_launch": ab[key] / n, "avg_launch_us": ms / n * 1e3, "launches": n,
                     "event_marker_us_removed_per_launch": marker_us}
+    # ------------------------------------------------ latency, encode time, streaming-read yardstick
+    # (after the timed region; each of these synchronises per call, the headline loop does not)
+    extras = {}
+    if not args.no_profile:
+        lat = []
+        run.pos = 0
+        torch.cuda.synchronize()
+        for _ in range(2 * T):
+            t0 = time.perf_counter()
+            run.steps(1)
+            torch.cuda.synchronize()
+            lat.append((time.perf_counter() - t0) * 1e3)
+        lat = np.sort(np.asarray(lat[T:]))           # second decode: warmed up
+        extras["step_latency_ms_synchronised"] = {"mean": float(lat.mean()), "p50": float(lat[len(lat) // 2]),
+                                                  "p99": float(lat[min(len(lat) - 1, int(0.99 * len(lat)))])}
+        enc = []
+        for _ in range(5):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            gpu.encode(run.src, run.len)
+            torch.cuda.synchronize()
+            enc.append((time.perf_counter() - t0) * 1e3)
+        extras["encode_ms"] = float(np.median(enc))
+        if roofline is not None:
+            # plain read kernel over a buffer of the dominant kernel's average size, and over 1 GiB
+            for label, nbytes in (("launch_sized", int(roofline["bytes_per_launch"])), ("1GiB", 1 << 30)):
+                buf = torch.empty(nbytes // 4, dtype=torch.int32, device="cuda").zero_()
+                for _ in range(3):
+                    gpu.stream_read(buf)
+                torch.cuda.synchronize()
+                reps = 50 if nbytes < (1 << 28) else 5
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    gpu.stream_read(buf)
+                torch.cuda.synchronize()
+                w = (time.perf_counter() - t0) / reps
+                roofline["plain_read_" + label] = {"bytes": buf.numel() * 4, "us": w * 1e6, "GBps": buf.numel() * 4 / w / 1e9}
+                del buf
     gpu.close()
     del run
 
@@ -329,7 +367,7 @@ def main():
                                f"self policy {cfg['self_pi']}, enc-dec policy {cfg['encdec_pi']} (share A)",
                    "rows": B, "kernels_per_step": launches,
                    "sentence_tokens_per_s": cfg["batch"] * K / wall},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "compare": compare,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "compare": compare, **extras,
     }
     if beam_sweep:
         out["beam_sweep"] = beam_sweep

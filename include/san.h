@@ -209,6 +209,13 @@ SAN_API int san_policy_read(san_ctx* ctx, int32_t which, double* js_out, int64_t
 SAN_API int san_policy_search(const double* js, int32_t n_layers, double theta, int32_t* pi_out,
                               int32_t* n_blocks_out);
 
+/* Measurement aid: queue one plain streaming read of `bytes` bytes (rounded
+ * down to a multiple of 16) of DEVICE memory at src_dev on the context's stream
+ * and discard the data.  Timed by the caller, it gives the read bandwidth this
+ * GPU reaches on a working set of that size -- the practical ceiling the
+ * HBM-bound attention kernels are compared with.  Errors: SAN_EINVAL (null). */
+SAN_API int san_stream_read(san_ctx* ctx, const void* src_dev, size_t bytes);
+
 /* Number of decode steps done since the last san_encode / san_rewind (-1 if
  * nothing is encoded). */
 SAN_API int32_t san_step(const san_ctx* ctx);

@@ -129,4 +129,7 @@ hipError_t launch_js_accumulate(const JsParams& p, double* acc, hipStream_t stre
 // host: block sizes of the greedy search with threshold theta on a [L][L] JS matrix
 int policy_search(const double* js, int L, double theta, int32_t* pi, int32_t* n_blocks);
 
+// reads `bytes` (multiple of 16) of device memory once and discards them; sink: 4 writable device bytes
+hipError_t launch_stream_read(const void* src, size_t bytes, unsigned* sink, hipStream_t stream);
+
 }  // namespace san

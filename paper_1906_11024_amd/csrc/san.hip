@@ -1026,6 +1026,14 @@ int san_policy_search(const double* js, int32_t n_layers, double theta, int32_t*
   return policy_search(js, n_layers, theta, pi_out, n_blocks_out);
 }
 
+int san_stream_read(san_ctx* c, const void* src_dev, size_t bytes) {
+  if (!c || !src_dev) return fail(c, SAN_EINVAL, "null argument");
+  c->kind = SAN_K_MISC;
+  // t_dev is a 256-byte allocation of which only the first word is the step counter
+  LAUNCH(c, launch_stream_read(src_dev, bytes, reinterpret_cast<unsigned*>(c->t_dev + 32), c->stream));
+  return SAN_OK;
+}
+
 int32_t san_step(const san_ctx* c) { return c ? c->t : -1; }
 size_t san_device_bytes(const san_ctx* c, int32_t which) { return !c ? 0 : (which == 0 ? c->weight_bytes : c->state_bytes); }
 int32_t san_last_launch_count(const san_ctx* c) { return c ? c->launches : 0; }

@@ -323,6 +323,19 @@ def test_state_and_capacity_errors():
     gpu.close()
 
 
+def test_stream_read_leaves_memory_untouched():
+    """the measurement aid only reads: odd sizes and a tail below 16 bytes included"""
+    cfg = wl.get_config("tiny")
+    gpu = hz.make_gpu(cfg, wl.make_weights(cfg, seed=0))
+    for nbytes in (16, 4096 + 16, (1 << 22) + 48, 1000):
+        buf = torch.arange(nbytes, dtype=torch.int64, device="cuda").to(torch.uint8)
+        ref = buf.clone()
+        gpu.stream_read(buf)
+        torch.cuda.synchronize()
+        assert torch.equal(buf, ref)
+    gpu.close()
+
+
 # ---------------------------------------------------- policy statistics (Sec. 3.3)
 def test_js_divergence_between_layers_matches_oracle():
     from oracle import policy_oracle as po
