@@ -13,7 +13,6 @@
 namespace san {
 
 constexpr int kWavesPerBlock = 4;
-constexpr int kUnroll = 8;
 
 // The LDS score rows are private to a wave: order its lanes' writes before the
 // other lanes' reads without a block-wide barrier.
@@ -38,11 +37,13 @@ __device__ __forceinline__ void widen(const uint4& raw, float (&out)[8]) {
 }
 
 template <typename T, int LPP, int NQ>
-__global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
+__global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnParams p) {
   constexpr int EPL = Frag<T>::N;       // elements per lane per position
   constexpr int PPL = kWave / LPP;      // positions per load instruction
   constexpr int DH = LPP * EPL;
-  constexpr int U = kUnroll;            // load instructions per chunk
+  // load instructions per chunk: a chunk of ~32 positions measured best for both
+  // storage types (deeper chunks cost registers, hence waves; shallower ones loop more)
+  constexpr int U = PPL >= 8 ? 4 : 8;
   constexpr int CH = PPL * U;           // positions per chunk
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
@@ -257,19 +258,19 @@ template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p,
   if (p.self_mode) {
     const size_t smem = sizeof(float) * kWavesPerBlock * p.lmax + sizeof(long long) * p.lmax;
     dim3 grid((unsigned)(p.rows * nhg));
-    hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(256), smem, stream, p);
+    hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
   } else if (p.rpg <= 32 && (long)p.groups * p.H * ((p.rpg + 3) / 4) < 1024) {
     // few queries per stream (the beams of a sentence) and few streams: one wave
     // per query keeps enough waves in flight (at least ~one per SIMD); the queries'
     // re-reads of the stream hit in L2.  With >= 1024 streams a wave takes 4 queries.
     const size_t smem = sizeof(float) * kWavesPerBlock * p.lmax;
     dim3 grid((unsigned)(p.groups * p.rpg * nhg));
-    hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(256), smem, stream, p);
+    hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
   } else {
     const int nqb = (p.rpg + 3) / 4;
     const size_t smem = sizeof(float) * kWavesPerBlock * 4 * p.lmax;
     dim3 grid((unsigned)((size_t)p.groups * nqb * nhg));
-    hipLaunchKernelGGL((attention_kernel<T, LPP, 4>), grid, dim3(256), smem, stream, p);
+    hipLaunchKernelGGL((attention_kernel<T, LPP, 4>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
   }
   return hipGetLastError();
 }
