@@ -48,135 +48,108 @@ hipError_t launch_embed(int dtype, const int* tok, int tok_stride, int rpg, cons
 }
 
 // ------------------------------------------- reduce + bias + residual + LayerNorm
-constexpr int kLnMaxIter = 8;  // n <= 8 * 256 = 2048 columns, one wave per row
+// One block per row, one 4-column group per thread (n / 4 threads, up to 8
+// waves): every load of the row is issued at once, so the kernel costs a single
+// memory round trip whatever the row width.  Row statistics: wave reduction, then
+// the per-wave values are added in wave order through LDS (deterministic).
+constexpr int kLnMaxWaves = 8;  // n <= 8 * 256 = 2048 columns
 
-template <typename T, bool STORE = true>
-__device__ __forceinline__ void layer_norm_row(float (&v)[kLnMaxIter][4], int n, int lane, const T* gamma,
-                                               const T* beta, float eps, T* out, float* out_f32) {
-  // gain and bias are requested first so that they arrive during the reductions
-  float4 gv[kLnMaxIter], bv[kLnMaxIter];
-#pragma unroll
-  for (int it = 0; it < kLnMaxIter; ++it) {
-    const int c = it * 256 + lane * 4;
-    if (c < n) { gv[it] = load4(gamma + c); bv[it] = load4(beta + c); }
-  }
-  float s = 0.f;
-#pragma unroll
-  for (int it = 0; it < kLnMaxIter; ++it) {
-    const int c = it * 256 + lane * 4;
-    if (c < n) s += (v[it][0] + v[it][1]) + (v[it][2] + v[it][3]);
-  }
-  const float mean = wave_sum(s) / (float)n;
+// sum of `x` over the whole block; `slot` is an LDS array of kLnMaxWaves floats used for this reduction only
+__device__ __forceinline__ float block_sum(float x, float* slot, int wid, int lane, int nwaves) {
+  x = wave_sum(x);
+  if (lane == 0) slot[wid] = x;
+  __syncthreads();
+  float total = 0.f;
+  for (int w = 0; w < nwaves; ++w) total += slot[w];
+  return total;
+}
+
+// LayerNorm of a row held as one float4 per thread (threads past the row hold zeros and are inactive)
+__device__ __forceinline__ float4 layer_norm_vec(float4 v, bool active, int n, float4 g, float4 b, float eps,
+                                                 float* slots, int wid, int lane, int nwaves) {
+  const float s = active ? (v.x + v.y) + (v.z + v.w) : 0.f;
+  const float mean = block_sum(s, slots, wid, lane, nwaves) / (float)n;
   float q = 0.f;
-#pragma unroll
-  for (int it = 0; it < kLnMaxIter; ++it) {
-    const int c = it * 256 + lane * 4;
-    if (c < n) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float dlt = v[it][e] - mean;
-        q = fmaf(dlt, dlt, q);
-      }
-    }
+  if (active) {
+    const float d0 = v.x - mean, d1 = v.y - mean, d2 = v.z - mean, d3 = v.w - mean;
+    q = fmaf(d0, d0, fmaf(d1, d1, fmaf(d2, d2, d3 * d3)));
   }
-  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)n + eps);
-#pragma unroll
-  for (int it = 0; it < kLnMaxIter; ++it) {
-    const int c = it * 256 + lane * 4;
-    if (c < n) {
-      const float4 g = gv[it], b = bv[it];
-      const float4 y = make_float4((v[it][0] - mean) * rstd * g.x + b.x, (v[it][1] - mean) * rstd * g.y + b.y,
-                                   (v[it][2] - mean) * rstd * g.z + b.z, (v[it][3] - mean) * rstd * g.w + b.w);
-      if (STORE) {
-        store4(out + c, y);
-        if (out_f32) *reinterpret_cast<float4*>(out_f32 + c) = y;
-      } else {
-        v[it][0] = y.x; v[it][1] = y.y; v[it][2] = y.z; v[it][3] = y.w;
-      }
-    }
+  const float rstd = 1.0f / sqrtf(block_sum(q, slots + kLnMaxWaves, wid, lane, nwaves) / (float)n + eps);
+  return make_float4((v.x - mean) * rstd * g.x + b.x, (v.y - mean) * rstd * g.y + b.y,
+                     (v.z - mean) * rstd * g.z + b.z, (v.w - mean) * rstd * g.w + b.w);
+}
+
+// bias + residual + the nsplit partials of one 4-column group; the partial loads go out four at a time
+template <typename T>
+__device__ __forceinline__ float4 gather_update(const float* part, int nsplit, size_t split_stride, const T* bias,
+                                                const T* res) {
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (bias) a = load4(bias);
+  if (res) {
+    const float4 rv = load4(res);
+    a.x += rv.x; a.y += rv.y; a.z += rv.z; a.w += rv.w;
   }
+  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int s = 0; s < nsplit; s += 4) {
+    float4 pv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      pv[u] = (s + u < nsplit) ? *reinterpret_cast<const float4*>(part + (size_t)(s + u) * split_stride)
+                               : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) { sum.x += pv[u].x; sum.y += pv[u].y; sum.z += pv[u].z; sum.w += pv[u].w; }
+  }
+  return make_float4(sum.x + a.x, sum.y + a.y, sum.z + a.z, sum.w + a.w);
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void ln_reduce_kernel(const float* part, int nsplit, int ldp, const T* bias,
-                                                        const T* res, int ldr, const T* gamma, const T* beta, T* out,
-                                                        int ldo, float* out_f32, int M, int n, float eps,
-                                                        LnStage2 s2) {
-  const int lane = threadIdx.x & 63;
-  const int m = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (m >= M) return;
-  float v[kLnMaxIter][4];
-#pragma unroll
-  for (int it = 0; it < kLnMaxIter; ++it) {
-    const int c = it * 256 + lane * 4;
-    if (c < n) {
-      // bias and residual first, then the partials four at a time: all of these
-      // loads are independent, so they overlap instead of queueing up one by one
-      float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (bias) a = load4(bias + c);
-      if (res) {
-        const float4 rv = load4(res + (size_t)m * ldr + c);
-        a.x += rv.x; a.y += rv.y; a.z += rv.z; a.w += rv.w;
-      }
-      float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-      const float* pp = part + (size_t)m * ldp + c;
-      const size_t ps = (size_t)M * ldp;
-      for (int s = 0; s < nsplit; s += 4) {
-        float4 pv[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-          pv[u] = (s + u < nsplit) ? *reinterpret_cast<const float4*>(pp + (size_t)(s + u) * ps)
-                                   : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) { sum.x += pv[u].x; sum.y += pv[u].y; sum.z += pv[u].z; sum.w += pv[u].w; }
-      }
-      v[it][0] = sum.x + a.x; v[it][1] = sum.y + a.y; v[it][2] = sum.z + a.z; v[it][3] = sum.w + a.w;
-    }
+__global__ __launch_bounds__(kLnMaxWaves * 64) void ln_reduce_kernel(const float* part, int nsplit, int ldp,
+                                                                     const T* bias, const T* res, int ldr,
+                                                                     const T* gamma, const T* beta, T* out, int ldo,
+                                                                     float* out_f32, int M, int n, float eps,
+                                                                     LnStage2 s2) {
+  __shared__ float slots[4 * kLnMaxWaves];
+  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+  const int m = blockIdx.x;
+  const int c = threadIdx.x * 4;
+  const bool active = c < n;
+  const int cc = active ? c : 0;   // inactive threads load column 0 and drop it
+  // everything this thread needs is requested before anything is used
+  const float4 g1 = load4(gamma + cc), b1 = load4(beta + cc);
+  float4 g2 = g1, b2 = b1, u2 = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (s2.part) {
+    g2 = load4(reinterpret_cast<const T*>(s2.gamma) + cc);
+    b2 = load4(reinterpret_cast<const T*>(s2.beta) + cc);
+    u2 = gather_update<T>(s2.part + (size_t)m * s2.ldp + cc, s2.nsplit, (size_t)M * s2.ldp,
+                          reinterpret_cast<const T*>(s2.bias) + cc, (const T*)nullptr);
   }
+  const float4 v = gather_update<T>(part + (size_t)m * ldp + cc, nsplit, (size_t)M * ldp, bias ? bias + cc : nullptr,
+                                    res ? res + (size_t)m * ldr + cc : nullptr);
+  float4 y = layer_norm_vec(v, active, n, g1, b1, eps, slots, wid, lane, nwaves);
   if (s2.part) {
     // second sub-layer without a GEMM of its own in between (an enc-dec follower
-    // whose projected context was computed at the block head): normalise in
-    // registers, add the second update, normalise again
-    layer_norm_row<T, false>(v, n, lane, gamma, beta, eps, nullptr, nullptr);
-#pragma unroll
-    for (int it = 0; it < kLnMaxIter; ++it) {
-      const int c = it * 256 + lane * 4;
-      if (c < n) {
-        float4 a = load4(reinterpret_cast<const T*>(s2.bias) + c);
-        const float* pp = s2.part + (size_t)m * s2.ldp + c;
-        const size_t ps = (size_t)M * s2.ldp;
-        for (int s = 0; s < s2.nsplit; s += 4) {
-          float4 pv[4];
-#pragma unroll
-          for (int u = 0; u < 4; ++u)
-            pv[u] = (s + u < s2.nsplit) ? *reinterpret_cast<const float4*>(pp + (size_t)(s + u) * ps)
-                                        : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-          for (int u = 0; u < 4; ++u) { a.x += pv[u].x; a.y += pv[u].y; a.z += pv[u].z; a.w += pv[u].w; }
-        }
-        // the first LayerNorm's output was rounded to the storage type when it was a
-        // separate launch; keep that rounding so both forms give the same bits
-        v[it][0] = to_f32(from_f32<T>(v[it][0])) + a.x; v[it][1] = to_f32(from_f32<T>(v[it][1])) + a.y;
-        v[it][2] = to_f32(from_f32<T>(v[it][2])) + a.z; v[it][3] = to_f32(from_f32<T>(v[it][3])) + a.w;
-      }
-    }
-    layer_norm_row<T, true>(v, n, lane, reinterpret_cast<const T*>(s2.gamma), reinterpret_cast<const T*>(s2.beta), eps,
-                            out + (size_t)m * ldo, out_f32 ? out_f32 + (size_t)m * n : nullptr);
-    return;
+    // whose projected context was computed at the block head): add the second
+    // update to the first LayerNorm's output and normalise again.  That output was
+    // rounded to the storage type when it was a separate launch; keep the rounding
+    // so both forms give the same bits.
+    const float4 y1 = make_float4(to_f32(from_f32<T>(y.x)) + u2.x, to_f32(from_f32<T>(y.y)) + u2.y,
+                                  to_f32(from_f32<T>(y.z)) + u2.z, to_f32(from_f32<T>(y.w)) + u2.w);
+    y = layer_norm_vec(y1, active, n, g2, b2, eps, slots + 2 * kLnMaxWaves, wid, lane, nwaves);
   }
-  layer_norm_row<T, true>(v, n, lane, gamma, beta, eps, out + (size_t)m * ldo, out_f32 ? out_f32 + (size_t)m * n : nullptr);
+  if (active) {
+    store4(out + (size_t)m * ldo + c, y);
+    if (out_f32) *reinterpret_cast<float4*>(out_f32 + (size_t)m * n + c) = y;
+  }
 }
 
 hipError_t launch_ln_reduce(int dtype, const float* part, int nsplit, int ldp, const void* bias, const void* res, int ldr,
                             const void* gamma, const void* beta, void* out, int ldo, float* out_f32, int M, int n,
                             float eps, hipStream_t stream, const LnStage2* stage2) {
   if (M <= 0) return hipSuccess;
-  if (n > kLnMaxIter * 256 || n % 4) return hipErrorInvalidValue;
+  if (n <= 0 || n > kLnMaxWaves * 256 || n % 4) return hipErrorInvalidValue;
   LnStage2 s2{};
   if (stage2) s2 = *stage2;
-  // one wave per row; with few rows use one-wave blocks so the rows spread over all CUs
-  const int wpb = M <= 1024 ? 1 : 4;
-  dim3 grid((M + wpb - 1) / wpb), block(64 * wpb);
+  dim3 grid(M), block(64 * ((n / 4 + 63) / 64));
   if (dtype == 1)
     hipLaunchKernelGGL(ln_reduce_kernel<bf16_t>, grid, block, 0, stream, part, nsplit, ldp, (const bf16_t*)bias,
                        (const bf16_t*)res, ldr, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)out, ldo,
@@ -271,47 +244,50 @@ hipError_t launch_aan_pre(int dtype, float* sum, const void* x, void* avg, void*
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void aan_post_kernel(const float* z, const T* bg, const T* cat, const T* gamma,
-                                                       const T* beta, T* x, float* out_f32, int rows, int d,
-                                                       float eps) {
-  const int lane = threadIdx.x & 63;
-  const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (m >= rows) return;
-  float v[kLnMaxIter][4];
+__global__ __launch_bounds__(kLnMaxWaves * 64) void aan_post_kernel(const float* z, const T* bg, const T* cat,
+                                                                    const T* gamma, const T* beta, T* x,
+                                                                    float* out_f32, int rows, int d, float eps) {
+  // one block per row, one 4-column group per thread (as the LayerNorm kernel above)
+  __shared__ float slots[2 * kLnMaxWaves];
+  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+  const int m = blockIdx.x;
+  const int c = threadIdx.x * 4;
+  const bool active = c < d;
+  const int cc = active ? c : 0;
+  const float4 g = load4(gamma + cc), b = load4(beta + cc);
+  const float4 zi = *reinterpret_cast<const float4*>(z + (size_t)m * 2 * d + cc);
+  const float4 zf = *reinterpret_cast<const float4*>(z + (size_t)m * 2 * d + d + cc);
+  const float4 bi = load4(bg + cc), bf = load4(bg + d + cc);
+  const float4 xv = load4(cat + (size_t)m * 2 * d + cc);
+  const float4 gv = load4(cat + (size_t)m * 2 * d + d + cc);
+  const float zia[4] = {zi.x + bi.x, zi.y + bi.y, zi.z + bi.z, zi.w + bi.w};
+  const float zfa[4] = {zf.x + bf.x, zf.y + bf.y, zf.z + bf.z, zf.w + bf.w};
+  const float xa[4] = {xv.x, xv.y, xv.z, xv.w}, ga[4] = {gv.x, gv.y, gv.z, gv.w};
+  float v[4];
 #pragma unroll
-  for (int it = 0; it < kLnMaxIter; ++it) {
-    const int c = it * 256 + lane * 4;
-    if (c < d) {
-      const float4 zi = *reinterpret_cast<const float4*>(z + (size_t)m * 2 * d + c);
-      const float4 zf = *reinterpret_cast<const float4*>(z + (size_t)m * 2 * d + d + c);
-      const float4 bi = load4(bg + c), bf = load4(bg + d + c);
-      const float4 xv = load4(cat + (size_t)m * 2 * d + c);
-      const float4 gv = load4(cat + (size_t)m * 2 * d + d + c);
-      const float zia[4] = {zi.x + bi.x, zi.y + bi.y, zi.z + bi.z, zi.w + bi.w};
-      const float zfa[4] = {zf.x + bf.x, zf.y + bf.y, zf.z + bf.z, zf.w + bf.w};
-      const float xa[4] = {xv.x, xv.y, xv.z, xv.w}, ga[4] = {gv.x, gv.y, gv.z, gv.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float ig = 1.0f / (1.0f + expf(-zia[e]));
-        const float fg = 1.0f / (1.0f + expf(-zfa[e]));
-        v[it][e] = xa[e] + ig * xa[e] + fg * ga[e];
-      }
-    }
+  for (int e = 0; e < 4; ++e) {
+    const float ig = 1.0f / (1.0f + expf(-zia[e]));
+    const float fg = 1.0f / (1.0f + expf(-zfa[e]));
+    v[e] = xa[e] + ig * xa[e] + fg * ga[e];
   }
-  layer_norm_row<T>(v, d, lane, gamma, beta, eps, x + (size_t)m * d, out_f32 ? out_f32 + (size_t)m * d : nullptr);
+  const float4 y = layer_norm_vec(make_float4(v[0], v[1], v[2], v[3]), active, d, g, b, eps, slots, wid, lane, nwaves);
+  if (active) {
+    store4(x + (size_t)m * d + c, y);
+    if (out_f32) *reinterpret_cast<float4*>(out_f32 + (size_t)m * d + c) = y;
+  }
 }
 hipError_t launch_aan_post(int dtype, const float* z, const void* bg, const void* cat, const void* gamma,
                            const void* beta, void* x, float* out_f32, int rows, int d, float eps,
                            hipStream_t stream) {
   if (rows <= 0) return hipSuccess;
-  if (d > kLnMaxIter * 256 || d % 4) return hipErrorInvalidValue;
-  dim3 grid((rows + 3) / 4);
+  if (d <= 0 || d > kLnMaxWaves * 256 || d % 4) return hipErrorInvalidValue;
+  dim3 grid(rows), block(64 * ((d / 4 + 63) / 64));
   if (dtype == 1)
-    hipLaunchKernelGGL(aan_post_kernel<bf16_t>, grid, dim3(256), 0, stream, z, (const bf16_t*)bg,
+    hipLaunchKernelGGL(aan_post_kernel<bf16_t>, grid, block, 0, stream, z, (const bf16_t*)bg,
                        (const bf16_t*)cat, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)x, out_f32, rows, d,
                        eps);
   else
-    hipLaunchKernelGGL(aan_post_kernel<float>, grid, dim3(256), 0, stream, z, (const float*)bg, (const float*)cat,
+    hipLaunchKernelGGL(aan_post_kernel<float>, grid, block, 0, stream, z, (const float*)bg, (const float*)cat,
                        (const float*)gamma, (const float*)beta, (float*)x, out_f32, rows, d, eps);
   return hipGetLastError();
 }
