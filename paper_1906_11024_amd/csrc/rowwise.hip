@@ -329,35 +329,48 @@ hipError_t launch_reorder_table(int* tab, int ld, const int* parent, const int* 
   return hipGetLastError();
 }
 
+// V = float4 (4 columns per thread) or float (1 column, for beams whose register copy would not fit otherwise)
+template <int MAXB, typename V>
 __global__ void reorder_rows_kernel(float* st, size_t layer_stride, const int* parent, int batch, int beam, int d) {
+  constexpr int W = sizeof(V) / sizeof(float);
   const int b = blockIdx.y, l = blockIdx.z;
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  const int c = (blockIdx.x * blockDim.x + threadIdx.x) * W;
   if (c >= d) return;
   float* base = st + (size_t)l * layer_stride + (size_t)b * beam * d + c;
-  float old[kMaxBeam];
+  int pl[MAXB];
 #pragma unroll
-  for (int k = 0; k < kMaxBeam; ++k)
-    if (k < beam) old[k] = base[(size_t)k * d];
+  for (int k = 0; k < MAXB; ++k)
+    if (k < beam) pl[k] = parent[b * beam + k] - b * beam;
+  V old[MAXB];
 #pragma unroll
-  for (int k = 0; k < kMaxBeam; ++k) {
+  for (int k = 0; k < MAXB; ++k)
+    if (k < beam) old[k] = *reinterpret_cast<const V*>(base + (size_t)k * d);
+#pragma unroll
+  for (int k = 0; k < MAXB; ++k) {
     if (k < beam) {
-      const int pl = parent[b * beam + k] - b * beam;
-      if (pl >= 0 && pl < beam && pl != k) {
-        float v = old[0];
+      if (pl[k] >= 0 && pl[k] < beam && pl[k] != k) {
+        V v = old[0];
 #pragma unroll
-        for (int q = 1; q < kMaxBeam; ++q)
-          if (q == pl) v = old[q];
-        base[(size_t)k * d] = v;
+        for (int q = 1; q < MAXB; ++q)
+          if (q == pl[k]) v = old[q];
+        *reinterpret_cast<V*>(base + (size_t)k * d) = v;
       }
     }
   }
 }
 hipError_t launch_reorder_rows(float* st, size_t layer_stride, const int* parent, int layers, int batch, int beam,
                                int d, hipStream_t stream) {
-  if (beam > kMaxBeam) return hipErrorInvalidValue;
+  if (beam > kMaxBeam || d % 4) return hipErrorInvalidValue;
   if (layers <= 0) return hipSuccess;
-  dim3 grid((d + 127) / 128, batch, layers);
-  hipLaunchKernelGGL(reorder_rows_kernel, grid, dim3(128), 0, stream, st, layer_stride, parent, batch, beam, d);
+  const dim3 g4((d / 4 + 63) / 64, batch, layers), g1((d + 127) / 128, batch, layers);
+  if (beam <= 4)
+    hipLaunchKernelGGL((reorder_rows_kernel<4, float4>), g4, dim3(64), 0, stream, st, layer_stride, parent, batch, beam, d);
+  else if (beam <= 8)
+    hipLaunchKernelGGL((reorder_rows_kernel<8, float4>), g4, dim3(64), 0, stream, st, layer_stride, parent, batch, beam, d);
+  else if (beam <= 16)
+    hipLaunchKernelGGL((reorder_rows_kernel<16, float4>), g4, dim3(64), 0, stream, st, layer_stride, parent, batch, beam, d);
+  else
+    hipLaunchKernelGGL((reorder_rows_kernel<32, float>), g1, dim3(128), 0, stream, st, layer_stride, parent, batch, beam, d);
   return hipGetLastError();
 }
 

@@ -215,8 +215,9 @@ def test_bf16_lockstep(base, kind):
     gpu.close()
 
 
-def test_aan_fp32_lockstep():
-    cfg = mid_cfg(self_kind="aan", self_pi=[1, 1, 1, 1], steps=30)
+@pytest.mark.parametrize("beam", [4, 6, 12, 20])   # each beam range has its own state-reorder kernel
+def test_aan_fp32_lockstep(beam):
+    cfg = mid_cfg(self_kind="aan", self_pi=[1, 1, 1, 1], steps=30 if beam == 4 else 12, beam=beam)
     w = wl.make_weights(cfg, seed=6)
     src, lens = ragged(cfg, 6)
     gpu = hz.make_gpu(cfg, w)
