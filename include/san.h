@@ -144,8 +144,8 @@ SAN_API int san_decode_step(san_ctx* ctx, const int32_t* tokens_dev, float* logi
  * the beam*vocab candidates are written in order of decreasing score, ties by
  * the lower flat index beam_index*vocab + v.  When eos_id >= 0, a row whose
  * last decoded input token was eos_id can only be extended by eos_id at cost 0.
- *   logits_dev DEVICE fp32 [batch*beam][vocab], cum_score_dev DEVICE fp32
- *   [batch*beam] (-inf marks a dead row), 1 <= k <= min(32, vocab);
+ *   logits_dev DEVICE fp32 [batch*beam][vocab], 16-byte aligned, cum_score_dev
+ *   DEVICE fp32 [batch*beam] (-inf marks a dead row), 1 <= k <= min(32, vocab);
  *   out_token_dev / out_parent_dev DEVICE int32 [batch][k] (parent = global row
  *   index), out_score_dev DEVICE fp32 [batch][k].
  * Errors: SAN_ESTATE, SAN_EINVAL. */
@@ -178,7 +178,7 @@ SAN_API int san_debug_get(san_ctx* ctx, int32_t what, int32_t layer, void* dst_d
  *   cum_io_dev      DEVICE fp32  [rows]     cumulative scores, in: before, out: after
  *   out_tokens_dev  DEVICE int32 [n][rows]  token chosen for every row at every step
  *   out_parents_dev DEVICE int32 [n][rows]  parent row of every row at every step
- *   logits_work_dev DEVICE fp32  [rows][vocab] scratch
+ *   logits_work_dev DEVICE fp32  [rows][vocab] scratch, 16-byte aligned
  * use_graph != 0: pairs of steps are replayed from a captured HIP graph (needs a
  * stream other than the NULL stream and use_cache = 1; the graph is re-captured
  * when the output/scratch pointers or the batch change).  Allocates its small

@@ -148,6 +148,21 @@ __device__ __forceinline__ unsigned other_xor32(unsigned x) {
   return (threadIdx.x & 32) ? r[0] : r[1];
 }
 
+// The value lane ^ J holds (J a power of two): DPP inside a row, row swaps across rows.
+template <int J> __device__ __forceinline__ unsigned lane_xor(unsigned x) {
+  static_assert(J == 1 || J == 2 || J == 4 || J == 8 || J == 16 || J == 32, "stride");
+  if (J == 1) return (unsigned)dpp_mov_i<kDppQuadSwap1>((int)x);
+  if (J == 2) return (unsigned)dpp_mov_i<kDppQuadSwap2>((int)x);
+  if (J == 4) {
+    const int up = dpp_mov_i<0x104>((int)x);    // row_shl:4: from lane + 4
+    const int down = dpp_mov_i<0x114>((int)x);  // row_shr:4: from lane - 4
+    return (unsigned)((threadIdx.x & 4) ? down : up);
+  }
+  if (J == 8) return (unsigned)dpp_mov_i<0x128>((int)x);   // row_ror:8
+  if (J == 16) return other_xor16(x);
+  return other_xor32(x);
+}
+
 // Sum over the lanes that agree with this one in the low log2(LO) bits of the
 // lane id, inside aligned groups of HI lanes (LO, HI powers of two, HI = 64 here).
 // Inside a 16-lane row the partners are reached by rotating the row by LO, 2*LO,

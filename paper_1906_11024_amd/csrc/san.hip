@@ -816,6 +816,7 @@ int san_topk(san_ctx* c, const float* logits_dev, const float* cum_score_dev, in
   if (!logits_dev || !cum_score_dev || !out_token_dev || !out_parent_dev || !out_score_dev)
     return fail(c, SAN_EINVAL, "san_topk: null argument");
   if (k < 1 || k > 32 || k > c->V) return fail(c, SAN_EINVAL, "san_topk: k must be in [1, min(32, vocab)]");
+  if (reinterpret_cast<uintptr_t>(logits_dev) % 16) return fail(c, SAN_EINVAL, "san_topk: logits must be 16-byte aligned");
   if (c->t < 0) return fail(c, SAN_ESTATE, "san_topk before san_encode");
   c->kind = SAN_K_TOPK;
   const long pm = prof_mark(c);
@@ -915,6 +916,8 @@ int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io
   if (!c) return SAN_EINVAL;
   if (!tokens_dev || !cum_io_dev || !out_tokens_dev || !out_parents_dev || !logits_work_dev || n < 1)
     return fail(c, SAN_EINVAL, "san_decode_n: bad argument");
+  if (reinterpret_cast<uintptr_t>(logits_work_dev) % 16)
+    return fail(c, SAN_EINVAL, "san_decode_n: the logits scratch must be 16-byte aligned");
   if (c->t < 0) return fail(c, SAN_ESTATE, "san_decode_n before san_encode");
   if (c->t + n > c->cfg.max_tgt_len) return fail(c, SAN_ECAPACITY, "san_decode_n: would exceed max_tgt_len");
   if (c->prof_on) return fail(c, SAN_ESTATE, "san_decode_n: switch san_profile off first");

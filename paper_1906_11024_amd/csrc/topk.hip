@@ -42,8 +42,68 @@ __device__ __forceinline__ Cand wave_best(Cand c) {
   return c;
 }
 
-// (max, sum of exp(x - max)) pairs combine associatively, so the log-sum-exp needs
-// a single exchange across the block.
+constexpr int kNone = 0x7fffffff;   // index of an empty candidate slot (value -inf)
+
+// One compare-exchange stage of a bitonic network over the 64 lanes: partner is
+// lane ^ J; inside blocks of K lanes that sort "best first" the lower lane of a
+// pair keeps the better element, in the other blocks the worse one.
+template <int K, int J> __device__ __forceinline__ void sort_stage(Cand& c, int lane) {
+  const float ov = __uint_as_float(lane_xor<J>(__float_as_uint(c.v)));
+  const int oi = (int)lane_xor<J>((unsigned)c.i);
+  const bool lower = (lane & J) == 0;
+  const bool best_first = K == kWave || (lane & K) == 0;
+  const bool other_better = better(ov, oi, c.v, c.i);
+  if ((lower == best_first) ? other_better : !other_better) { c.v = ov; c.i = oi; }
+}
+// Sorts the (value, index) pairs of each aligned group of N lanes (N = 16 or 64),
+// best first: lane r of the group ends up with rank r.  Register-only stages (10
+// for N = 16, 21 for N = 64); equal pairs can only be empty slots.
+template <int N> __device__ __forceinline__ void wave_sort(Cand& c, int lane) {
+  static_assert(N == 16 || N == kWave, "group size");
+  sort_stage<2, 1>(c, lane);
+  sort_stage<4, 2>(c, lane); sort_stage<4, 1>(c, lane);
+  sort_stage<8, 4>(c, lane); sort_stage<8, 2>(c, lane); sort_stage<8, 1>(c, lane);
+  if (N == 16) {
+    // last merge of a 16-lane group: every group sorts best first
+    sort_stage<kWave, 8>(c, lane); sort_stage<kWave, 4>(c, lane); sort_stage<kWave, 2>(c, lane);
+    sort_stage<kWave, 1>(c, lane);
+    return;
+  }
+  sort_stage<16, 8>(c, lane); sort_stage<16, 4>(c, lane); sort_stage<16, 2>(c, lane); sort_stage<16, 1>(c, lane);
+  sort_stage<32, 16>(c, lane); sort_stage<32, 8>(c, lane); sort_stage<32, 4>(c, lane); sort_stage<32, 2>(c, lane);
+  sort_stage<32, 1>(c, lane);
+  sort_stage<64, 32>(c, lane); sort_stage<64, 16>(c, lane); sort_stage<64, 8>(c, lane); sort_stage<64, 4>(c, lane);
+  sort_stage<64, 2>(c, lane); sort_stage<64, 1>(c, lane);
+}
+// The k best of the candidates load(0..nc-1), best first in lanes 0..k-1 (k <= 32).
+// Up to 16 candidates: one short sort.  Otherwise 64 candidates per pass; the running
+// k best ride along in lanes k..2k-1 of the next pass.
+template <typename F> __device__ __forceinline__ Cand wave_topk(F load, int nc, int k, int lane) {
+  Cand cur = {-INFINITY, kNone};
+  if (nc <= 16) {
+    if (lane < nc) cur = load(lane);
+    wave_sort<16>(cur, lane);
+    return cur;
+  }
+  for (int base = 0; base < nc; base += kWave) {
+    Cand c = {-INFINITY, kNone};
+    if (base + lane < nc) c = load(base + lane);
+    wave_sort<kWave>(c, lane);
+    if (base > 0) {
+      const float mv = __shfl(cur.v, lane - k, kWave);
+      const int mi = __shfl(cur.i, lane - k, kWave);
+      if (lane >= k) {
+        c.v = lane < 2 * k ? mv : -INFINITY;
+        c.i = lane < 2 * k ? mi : kNone;
+      }
+      wave_sort<kWave>(c, lane);
+    }
+    cur = c;
+  }
+  return cur;
+}
+
+// (max, sum of exp(x - max)) pairs combine associatively
 __device__ __forceinline__ void lse_merge(float& m, float& s, float om, float os) {
   const float M = fmaxf(m, om);
   if (M == -INFINITY) { s = 0.f; return; }
@@ -71,89 +131,76 @@ __global__ __launch_bounds__(kTopkThreads) void topk_row_kernel(const float* log
   const float* x = logits + (size_t)row * vocab;
   const int nit = (vocab + kTopkThreads - 1) / kTopkThreads;
 
+  // register-resident row: 16-byte loads, register `it` holds word
+  // (it / 4) * 4096 + tid * 4 + it % 4 (vocab is a multiple of 4, rows are 16-byte aligned)
   float reg[REG ? kTopkVpt : 1];
   if (REG) {
 #pragma unroll
-    for (int it = 0; it < kTopkVpt; ++it) {
-      const int idx = it * kTopkThreads + tid;
-      reg[it] = (it < nit && idx < vocab) ? x[idx] : -INFINITY;
+    for (int q = 0; q < kTopkVpt / 4; ++q) {
+      const int idx = q * 4 * kTopkThreads + tid * 4;
+      float4 v = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+      if (idx < vocab) v = *reinterpret_cast<const float4*>(x + idx);
+      reg[4 * q] = v.x; reg[4 * q + 1] = v.y; reg[4 * q + 2] = v.z; reg[4 * q + 3] = v.w;
     }
   }
+  auto index_of = [&](int it) -> int {
+    return REG ? (it >> 2) * 4 * kTopkThreads + tid * 4 + (it & 3) : it * kTopkThreads + tid;
+  };
   auto val = [&](int it) -> float {
     if (REG) return reg[it];
-    const int idx = it * kTopkThreads + tid;
+    const int idx = index_of(it);
     return idx < vocab ? x[idx] : -INFINITY;
   };
 
-  // ---- log-sum-exp of the row
-  float m = -INFINITY, s = 0.f;
+  // ---- log-sum-exp of the row: wave maximum first, then one exp per element
+  float tmax = -INFINITY;
   if (REG) {
 #pragma unroll
-    for (int it = 0; it < kTopkVpt; ++it) m = fmaxf(m, reg[it]);
-#pragma unroll
-    for (int it = 0; it < kTopkVpt; ++it) s += (reg[it] == -INFINITY) ? 0.f : __expf(reg[it] - m);
+    for (int it = 0; it < kTopkVpt; ++it) tmax = fmaxf(tmax, reg[it]);
   } else {
-    for (int it = 0; it < nit; ++it) m = fmaxf(m, val(it));
+    for (int it = 0; it < nit; ++it) tmax = fmaxf(tmax, val(it));
+  }
+  const float m_w = wave_max(tmax);
+  float s = 0.f;
+  if (REG) {
+#pragma unroll
+    for (int it = 0; it < kTopkVpt; ++it) s += (reg[it] == -INFINITY) ? 0.f : __expf(reg[it] - m_w);
+  } else {
     for (int it = 0; it < nit; ++it) {
       const float v = val(it);
-      s += (v == -INFINITY) ? 0.f : expf(v - m);
+      s += (v == -INFINITY) ? 0.f : expf(v - m_w);
     }
   }
-#pragma unroll
-  for (int st = 1; st < kWave; st <<= 1) {
-    const float om = __shfl_xor(m, st, kWave), os = __shfl_xor(s, st, kWave);
-    lse_merge(m, s, om, os);
-  }
-  if (lane == 0) { red_m[wid] = m; red_s[wid] = s; }
+  s = wave_sum(s);
+  if (lane == 0) { red_m[wid] = m_w; red_s[wid] = s; }
 
   const bool finished = eos_id >= 0 && last_tok[row] == eos_id;
   if (REG) {
-    // ---- threshold pass.  The k-th largest of the per-thread maxima is a lower
-    // bound T on the k-th largest element, so every element of the row's top k is
+    // ---- threshold pass.  Any value T with at least k elements >= T is a lower
+    // bound on the k-th largest element, so every element of the row's top k is
     // >= T, and usually only a handful of elements are.  Those go to a short list in
     // LDS that wave 0 orders; a list overflow (masses of equal values) falls back to
-    // the general rounds below.
-    float tmax = -INFINITY;
-#pragma unroll
-    for (int it = 0; it < kTopkVpt; ++it) tmax = fmaxf(tmax, reg[it]);
-    {
-      // each wave's k largest thread maxima (k rounds of "largest below the previous", by value and lane)
-      float pv = INFINITY;
-      int pl = -1;
-      for (int round = 0; round < k; ++round) {
-        const bool after = (tmax < pv) || (tmax == pv && lane > pl);
-        Cand best = {after ? tmax : -INFINITY, after ? lane : 0x7fffffff};
-        best = wave_best(best);
-        if (lane == 0) wc_v[wid * k + round] = best.v;
-        pv = best.v;
-        pl = best.i;
-      }
+    // the general rounds below.  T = the k-th largest wave maximum (k <= 16 waves;
+    // already known from the log-sum-exp), else the k-th largest of the waves' k
+    // largest thread maxima.
+    const bool by_wave_max = k <= NW;
+    if (!by_wave_max) {
+      Cand c = {tmax, lane};
+      wave_sort<kWave>(c, lane);
+      if (lane < k) wc_v[wid * k + lane] = c.v;
     }
     if (tid == 0) list_n = 0;
     __syncthreads();
     if (wid == 0) {
-      // k-th largest of the NW * k wave values (duplicates count)
-      const int nc = NW * k;
-      float pv = INFINITY;
-      int pc = -1;
-      for (int round = 0; round < k; ++round) {
-        Cand best = {-INFINITY, 0x7fffffff};
-        for (int c = lane; c < nc; c += kWave) {
-          const float v = wc_v[c];
-          const bool after = (v < pv) || (v == pv && c > pc);
-          if (after && better(v, c, best.v, best.i)) { best.v = v; best.i = c; }
-        }
-        best = wave_best(best);
-        pv = best.v;
-        pc = best.i;
-      }
-      if (lane == 0) thresh = pv;
+      const Cand c = by_wave_max ? wave_topk([&](int q) { return Cand{red_m[q], q}; }, NW, k, lane)
+                                 : wave_topk([&](int q) { return Cand{wc_v[q], q}; }, NW * k, k, lane);
+      if (lane == k - 1) thresh = c.v;
     }
     __syncthreads();
     const float T = thresh;
 #pragma unroll
     for (int it = 0; it < kTopkVpt; ++it) {
-      const int idx = it * kTopkThreads + tid;
+      const int idx = index_of(it);
       if (idx < vocab && reg[it] >= T) {
         const int pos = atomicAdd(&list_n, 1);
         if (pos < kListCap) { list_v[pos] = reg[it]; list_i[pos] = idx; }
@@ -167,18 +214,18 @@ __global__ __launch_bounds__(kTopkThreads) void topk_row_kernel(const float* log
     float pv = INFINITY;
     int pi = -1;
     for (int round = 0; round < k; ++round) {
-      Cand best = {-INFINITY, 0x7fffffff};
+      Cand best = {-INFINITY, kNone};
       if (REG) {
 #pragma unroll
         for (int it = 0; it < kTopkVpt; ++it) {
-          const int idx = it * kTopkThreads + tid;
+          const int idx = index_of(it);
           const float v = reg[it];
           const bool after = (v < pv) || (v == pv && idx > pi);
           if (idx < vocab && after && better(v, idx, best.v, best.i)) { best.v = v; best.i = idx; }
         }
       } else {
         for (int it = 0; it < nit; ++it) {
-          const int idx = it * kTopkThreads + tid;
+          const int idx = index_of(it);
           const float v = val(it);
           const bool after = (v < pv) || (v == pv && idx > pi);
           if (idx < vocab && after && better(v, idx, best.v, best.i)) { best.v = v; best.i = idx; }
@@ -193,7 +240,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_row_kernel(const float* log
   __syncthreads();
   if (wid != 0) return;
 
-  m = red_m[0];
+  float m = red_m[0];
   s = red_s[0];
   for (int w = 1; w < NW; ++w) lse_merge(m, s, red_m[w], red_s[w]);   // same order in every lane
   const float lse = m + logf(s);
@@ -211,23 +258,10 @@ __global__ __launch_bounds__(kTopkThreads) void topk_row_kernel(const float* log
   const int nc = use_list ? list_n : NW * k;
   const float* cv = use_list ? list_v : wc_v;
   const int* ci = use_list ? list_i : wc_i;
-  float pv = INFINITY;
-  int pi = -1;
-  for (int round = 0; round < k; ++round) {
-    Cand best = {-INFINITY, 0x7fffffff};
-    for (int c = lane; c < nc; c += kWave) {
-      const float v = cv[c];
-      const int idx = ci[c];
-      const bool after = (v < pv) || (v == pv && idx > pi);
-      if (idx != 0x7fffffff && after && better(v, idx, best.v, best.i)) { best.v = v; best.i = idx; }
-    }
-    best = wave_best(best);
-    if (lane == 0) {
-      cand_lp[(size_t)row * k + round] = best.v - lse;
-      cand_idx[(size_t)row * k + round] = best.i;
-    }
-    pv = best.v;
-    pi = best.i;
+  const Cand c = wave_topk([&](int q) { return Cand{ci[q] == kNone ? -INFINITY : cv[q], ci[q]}; }, nc, k, lane);
+  if (lane < k) {
+    cand_lp[(size_t)row * k + lane] = c.v - lse;
+    cand_idx[(size_t)row * k + lane] = c.i;
   }
 }
 
@@ -239,33 +273,26 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(const float* cand_lp, co
   // multi-step decoding: this step's picks are also appended to the caller's
   // [step][rows] arrays; the step index comes from the device-side counters
   const long long hoff = hist.tok ? (long long)(*hist.t_dev - 1 - *hist.t0_dev) * gridDim.x * k : 0;
-  const int nc = beam * k;
-  float pv = INFINITY;
-  int pi = -1;
-  for (int round = 0; round < k; ++round) {
-    Cand best = {-INFINITY, 0x7fffffff};
-    for (int cidx = lane; cidx < nc; cidx += kWave) {
-      const int bi = cidx / k;
-      const int r = b * beam + bi;
-      const float sc = cum[r] + cand_lp[(size_t)r * k + (cidx % k)];
-      const int flat = bi * vocab + cand_idx[(size_t)r * k + (cidx % k)];
-      const bool after = (sc < pv) || (sc == pv && flat > pi);
-      if (after && better(sc, flat, best.v, best.i)) { best.v = sc; best.i = flat; }
+  const Cand best = wave_topk(
+      [&](int q) {
+        const int bi = q / k;
+        const int r = b * beam + bi;
+        const int id = cand_idx[(size_t)r * k + (q % k)];
+        const float sc = cum[r] + cand_lp[(size_t)r * k + (q % k)];
+        // an empty row slot, or a score that is not a number, never wins
+        return (id == kNone || !(sc == sc)) ? Cand{-INFINITY, kNone} : Cand{sc, bi * vocab + id};
+      },
+      beam * k, k, lane);
+  if (lane < k) {
+    const bool ok = best.i != kNone;
+    const int tk = ok ? best.i % vocab : 0, pr = b * beam + (ok ? best.i / vocab : 0);
+    out_tok[(size_t)b * k + lane] = tk;
+    out_parent[(size_t)b * k + lane] = pr;
+    out_score[(size_t)b * k + lane] = ok ? best.v : -INFINITY;
+    if (hist.tok) {
+      hist.tok[hoff + (size_t)b * k + lane] = tk;
+      hist.par[hoff + (size_t)b * k + lane] = pr;
     }
-    best = wave_best(best);
-    if (lane == 0) {
-      const bool ok = best.i != 0x7fffffff;
-      const int tk = ok ? best.i % vocab : 0, pr = b * beam + (ok ? best.i / vocab : 0);
-      out_tok[(size_t)b * k + round] = tk;
-      out_parent[(size_t)b * k + round] = pr;
-      out_score[(size_t)b * k + round] = ok ? best.v : -INFINITY;
-      if (hist.tok) {
-        hist.tok[hoff + (size_t)b * k + round] = tk;
-        hist.par[hoff + (size_t)b * k + round] = pr;
-      }
-    }
-    pv = best.v;
-    pi = best.i;
   }
 }
 

@@ -321,6 +321,14 @@ def test_state_and_capacity_errors():
     with pytest.raises(sb.SanError) as e:
         gpu.decode_step(tok, logits)
     assert e.value.code == sb.SAN_ECAPACITY
+    # the beam step reads the logits with 16-byte loads and refuses a misaligned buffer
+    shifted = torch.zeros(20 * cfg["V"] + 4, dtype=torch.float32, device="cuda")[1:1 + 20 * cfg["V"]]
+    cum = torch.zeros(20, dtype=torch.float32, device="cuda")
+    o_i = torch.zeros((5, 4), dtype=torch.int32, device="cuda")
+    o_f = torch.zeros((5, 4), dtype=torch.float32, device="cuda")
+    with pytest.raises(sb.SanError) as e:
+        gpu.topk(shifted, cum, 4, o_i, o_i.clone(), o_f)
+    assert e.value.code == sb.SAN_EINVAL
     gpu.close()
 
 
