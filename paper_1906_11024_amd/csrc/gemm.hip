@@ -252,17 +252,22 @@ static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
   return hipGetLastError();
 }
 
-// Tile choice: 0 = 64x64 or smaller (2x2 waves and the k-group shapes below),
-// 1 = 128x128 (4x2 waves, 1x2 MFMA tiles each) once that still gives ~one block
-// per CU; measured best of {256x64, 128x64, 128x128 with 4 or 8 waves, 256x128}
-// on the output layer.
-int gemm_pick_tile(int M, int N) {
+// Tile choice: 0 = 64x64 or smaller (2x2 waves and the k-group shapes below);
+// 1 = 128x128 once that still gives ~one block per CU (the output layer);
+// 2 = 256x256 (bf16 only) once that does.  The wide output layer is bound by
+// the operand traffic between L2 and the CUs, |X| * N/BN + |W| * M/BM, so the
+// biggest tile that still fills the chip wins: measured on the output layer,
+// fp32 M = 256: 128x128 with 16 waves 69 us (8 waves 81, 256x128 71-76, 256x256
+// 132: half the CUs idle); bf16 M = 512: 256x256 with 16 waves 44-48 us (128x128
+// 63, 256x128 51, 128x256 55).
+int gemm_pick_tile(int M, int N, int dtype) {
+  if (dtype == 1 && M >= 256 && (long)((M + 255) / 256) * ((N + 255) / 256) >= 200) return 2;
   if (M >= 128 && (long)((M + 127) / 128) * ((N + 127) / 128) >= 200) return 1;
   return 0;
 }
 
 int gemm_pick_ksplit(int M, int N, int K, int dtype) {
-  if (gemm_pick_tile(M, N) != 0) return 1;
+  if (gemm_pick_tile(M, N, dtype) != 0) return 1;
   const int epc = dtype == 1 ? 64 : 32;
   const int nchunks = K / epc;
   const long blocks = (long)((M + 63) / 64) * ((N + 63) / 64);
@@ -280,7 +285,7 @@ hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
   const int epc = dtype == 1 ? 64 : 32;
   if (p.K <= 0 || p.K % epc != 0 || p.ksplit < 1) return hipErrorInvalidValue;
   if (p.ksplit > 1 && p.out_kind != 2) return hipErrorInvalidValue;   // only partial outputs may be split across blocks
-  const int tile = p.ksplit > 1 ? 0 : gemm_pick_tile(p.M, p.N);
+  const int tile = p.ksplit > 1 ? 0 : gemm_pick_tile(p.M, p.N, dtype);
   // A wave's MFMA chain over the whole k range is what bounds a small GEMM, and
   // only waves on different SIMDs run their chains in parallel.  When 64x64 tiles
   // would leave most SIMDs idle, use smaller tiles and deal each tile's k range to
@@ -295,6 +300,7 @@ hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
     else if (tiles64 <= 192 && chunks >= 4) shape = 1;
   }
   if (dtype == 1) {
+    if (tile == 2) return launch_tile<bf16_t, 4, 4, 2, 2, 1, 2>(p, stream);
     if (wide && tile != 1) {   // (the 128x128 tile with wide chunks would not fit two blocks per CU: slower)
       if (shape == 2) return launch_tile<bf16_t, 1, 1, 1, 1, 4, 2, 256>(p, stream);
       if (shape == 1) return launch_tile<bf16_t, 2, 1, 1, 1, 2, 2, 256>(p, stream);
@@ -305,7 +311,7 @@ hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
     if (shape == 1) return launch_tile<bf16_t, 2, 1, 1, 1, 2, 4>(p, stream);
     return launch_tile<bf16_t, 2, 2, 1, 1, 1, 4>(p, stream);
   }
-  if (tile == 1) return launch_tile<float, 4, 2, 1, 2, 1, 2>(p, stream);
+  if (tile == 1) return launch_tile<float, 4, 4, 1, 1, 1, 2>(p, stream);
   if (shape == 2) return launch_tile<float, 1, 1, 1, 1, 4, 4>(p, stream);
   if (shape == 1) return launch_tile<float, 2, 1, 1, 1, 2, 4>(p, stream);
   return launch_tile<float, 2, 2, 1, 1, 1, 4>(p, stream);
