@@ -70,6 +70,18 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
   unsigned char* Xs = smem + kg * STAGE;           // [2][BM][144]
   unsigned char* Ws = Xs + 2 * BM * kRowBytes;     // [2][BN][144]
 
+  // The step counter and the bias are requested now.  The bias goes into the
+  // accumulators' start value (of k-group 0), so that no load is pending when the
+  // epilogue runs: a pending load makes the compiler wait for *all* memory traffic
+  // before every conditional store -- the counter it waits on also counts the
+  // stores -- which serialises the 16 stores of a tile (+1.3 us on a 10 us GEMM).
+  const int t_step = p.t_dev ? *p.t_dev : 0;
+  float bias_v[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = n0 + (wn * TN + j) * 32 + l32;
+    bias_v[j] = (p.bias && p.out_kind != 2 && kg == 0 && n < p.N) ? to_f32(reinterpret_cast<const T*>(p.bias)[n]) : 0.f;
+  }
   const int nchunks = p.K / EPC;
   const int cps = (nchunks + p.ksplit - 1) / p.ksplit;
   const int c_begin = blockIdx.z * cps;
@@ -111,46 +123,97 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
   } while (0)
 
   f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-#pragma unroll
-  for (int s = 0; s < D; ++s)
-    if (s < iters && SAN_CHUNK(s) < c_end) SAN_LOAD_GLOBAL(SAN_CHUNK(s), s);
+#define SAN_MMA(buf_)                                                                                      \
+  do {                                                                                                     \
+    const unsigned char* xs_ = Xs + ((buf_) * BM + wm * 32 * TM + l32) * kRowBytes + kh * 16;              \
+    const unsigned char* ws_ = Ws + ((buf_) * BN + wn * 32 * TN + l32) * kRowBytes + kh * 16;              \
+    _Pragma("unroll") for (int sub_ = 0; sub_ < CB / 32; ++sub_) {                                         \
+      u32x4 xf_[TM], wf_[TN];                                                                              \
+      _Pragma("unroll") for (int i_ = 0; i_ < TM; ++i_)                                                    \
+          xf_[i_] = *reinterpret_cast<const u32x4*>(xs_ + i_ * 32 * kRowBytes + sub_ * 32);                \
+      _Pragma("unroll") for (int j_ = 0; j_ < TN; ++j_)                                                    \
+          wf_[j_] = *reinterpret_cast<const u32x4*>(ws_ + j_ * 32 * kRowBytes + sub_ * 32);                \
+      _Pragma("unroll") for (int i_ = 0; i_ < TM; ++i_)                                                    \
+          _Pragma("unroll") for (int j_ = 0; j_ < TN; ++j_) mma_frag<T>(acc[i_][j_], xf_[i_], wf_[j_]);    \
+    }                                                                                                      \
+  } while (0)
 
-  for (int ib = 0; ib < iters; ib += D) {
+  // The loads of the steady state are unconditional on purpose.  The hardware
+  // counts outstanding loads in order, and the compiler must assume the worst
+  // about loads that sit behind a branch: with a conditional refill it waited for
+  // *every* load in flight before each chunk's LDS store, which cut the look-ahead
+  // of the register queue from D chunks to one and made every chunk cost a full
+  // memory latency.  Chunk indices past the end are clamped (the data is loaded
+  // and never used) instead of skipped.
+#define SAN_INIT_ACC()                                                                   \
+  do {                                                                                   \
+    _Pragma("unroll") for (int i_ = 0; i_ < TM; ++i_)                                    \
+        _Pragma("unroll") for (int j_ = 0; j_ < TN; ++j_)                                \
+            _Pragma("unroll") for (int v_ = 0; v_ < 16; ++v_) acc[i_][j_][v_] = bias_v[j_]; \
+  } while (0)   /* column n of every row this lane holds */
+  if (iters <= 0) {   // an empty k-slice of a split GEMM (those carry no bias): contributes zeros
 #pragma unroll
-    for (int s = 0; s < D; ++s) {
-      const int it = ib + s;
-      if (it < iters) {
-        const bool live = SAN_CHUNK(it) < c_end;   // the last round may be short for some groups
-        const int buf = s & 1;                     // D is even, so iteration parity == slot parity
-        if (live) SAN_STORE_LDS(buf, s);           // waits for this chunk's loads only
-        if (it + D < iters && SAN_CHUNK(it + D) < c_end) SAN_LOAD_GLOBAL(SAN_CHUNK(it + D), s);
-        __syncthreads();                           // one barrier per round: the other buffer is still being read
-        if (live) {
-          const unsigned char* xs = Xs + (buf * BM + wm * 32 * TM + l32) * kRowBytes + kh * 16;
-          const unsigned char* ws = Ws + (buf * BN + wn * 32 * TN + l32) * kRowBytes + kh * 16;
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-          for (int sub = 0; sub < CB / 32; ++sub) {
-            u32x4 xf[TM], wf[TN];
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int i = 0; i < TM; ++i) xf[i] = *reinterpret_cast<const u32x4*>(xs + i * 32 * kRowBytes + sub * 32);
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  }
+  if (iters > 0) {
+    const int c_last = c_end - 1;
+#define SAN_CHUNK_C(i_) min(SAN_CHUNK(i_), c_last)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) wf[j] = *reinterpret_cast<const u32x4*>(ws + j * 32 * kRowBytes + sub * 32);
+    for (int s = 0; s < D; ++s) SAN_LOAD_GLOBAL(SAN_CHUNK_C(s), s);
+    // The accumulators start from the bias, which must not stall the loads above:
+    // the asm ties the start values to this point of the program (the loads
+    // cannot sink below a memory clobber, the moves cannot rise above it), where
+    // waiting for the bias means waiting for the oldest load only.
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(bias_v[j]) : : "memory");
+    SAN_INIT_ACC();
+    // steady state: every chunk used here exists, every iteration refills its slot
+    const int iters_main = iters > D ? ((iters - D) / D) * D : 0;
+    int ib = 0;
+    for (; ib < iters_main; ib += D) {
 #pragma unroll
-              for (int j = 0; j < TN; ++j) mma_frag<T>(acc[i][j], xf[i], wf[j]);
-          }
+      for (int s = 0; s < D; ++s) {
+        SAN_STORE_LDS(s & 1, s);                   // D is even, so chunk parity == slot parity
+        SAN_LOAD_GLOBAL(SAN_CHUNK_C(ib + s + D), s);
+        __syncthreads();                           // one barrier per chunk: the other buffer is still being read
+        SAN_MMA(s & 1);
+      }
+    }
+    if (iters % D == 0) {
+      // the last D chunks, nothing left to request: straight-line code, so the
+      // waits stay exact (the last round may be short for some k-groups)
+#pragma unroll
+      for (int s = 0; s < D; ++s) {
+        const bool live = SAN_CHUNK(ib + s) < c_end;
+        if (live) SAN_STORE_LDS(s & 1, s);
+        __syncthreads();
+        if (live) SAN_MMA(s & 1);
+      }
+      ib = iters;
+    }
+    // any other tail: at most 2*D - 1 chunks with conditional refills (conservative waits)
+    for (; ib < iters; ib += D) {
+#pragma unroll
+      for (int s = 0; s < D; ++s) {
+        const int it = ib + s;
+        if (it < iters) {
+          const bool live = SAN_CHUNK(it) < c_end;
+          if (live) SAN_STORE_LDS(s & 1, s);
+          if (it + D < iters) SAN_LOAD_GLOBAL(SAN_CHUNK_C(it + D), s);
+          __syncthreads();
+          if (live) SAN_MMA(s & 1);
         }
       }
     }
+#undef SAN_CHUNK_C
   }
+#undef SAN_MMA
+#undef SAN_INIT_ACC
 #undef SAN_CHUNK
 #undef SAN_LOAD_GLOBAL
 #undef SAN_STORE_LDS
@@ -185,46 +248,50 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
   // For a fixed v the 32 lanes of a half-wave hold 32 consecutive columns of one
   // row, so every store instruction writes two contiguous 128-byte (fp32) row
   // segments -- whole cache lines, which matters for the wide output layer.
+  // Row offsets: one 64-bit product per 32x32 tile (its first row); the other 15
+  // rows are that plus a compile-time multiple of the row stride.
   if (p.out_kind == 2) {
     // ---- fp32 partials [ksplit][M][N]; the consumer (LayerNorm kernel) adds them up in a fixed order
-    float* part = reinterpret_cast<float*>(p.out[0]);
+    float* part = reinterpret_cast<float*>(p.out[0]) + (size_t)blockIdx.z * p.M * p.N;
+    const size_t ld = (size_t)p.N;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int n = n0 + (wn * TN + j) * 32 + l32;
+        const int mrow = m0 + (wm * TM + i) * 32 + kh * 4;
+        float* dst = part + (size_t)mrow * ld + n;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int m = m0 + (wm * TM + i) * 32 + (v >> 2) * 8 + kh * 4 + (v & 3);
-          if (m < p.M && n < p.N) part[((size_t)blockIdx.z * p.M + m) * p.N + n] = acc[i][j][v];
+          const int dm = (v >> 2) * 8 + (v & 3);
+          if (mrow + dm < p.M && n < p.N) dst[dm * ld] = acc[i][j][v];
         }
       }
     return;
   }
 
-  // ---- epilogue: bias, ReLU, scatter into up to three column segments
-  const int t = p.t_dev ? *p.t_dev : 0;
-  const T* bias = reinterpret_cast<const T*>(p.bias);
+  // ---- epilogue: ReLU, scatter into up to three column segments (the bias is already in)
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int n = n0 + (wn * TN + j) * 32 + l32;
     if (n >= p.N) continue;
-    const float bv = bias ? to_f32(bias[n]) : 0.f;
-    const int s = n / p.seg_w;
+    const int s = ((unsigned)n >= (unsigned)p.seg_w) + ((unsigned)n >= 2u * (unsigned)p.seg_w);   // n / seg_w, at most 2
     const int nn = n - s * p.seg_w;
     void* obase = s == 0 ? p.out[0] : (s == 1 ? p.out[1] : p.out[2]);
-    const int ldo = s == 0 ? p.ldo[0] : (s == 1 ? p.ldo[1] : p.ldo[2]);
+    const size_t ld = (size_t)(s == 0 ? p.ldo[0] : (s == 1 ? p.ldo[1] : p.ldo[2]));
     const long long ts = s == 0 ? p.tstride[0] : (s == 1 ? p.tstride[1] : p.tstride[2]);
-    const size_t base = (size_t)t * ts + nn;
+    const size_t base = (size_t)t_step * ts + nn;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+      const int mrow = m0 + (wm * TM + i) * 32 + kh * 4;
+      const size_t row0 = base + (size_t)mrow * ld;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int m = m0 + (wm * TM + i) * 32 + (v >> 2) * 8 + kh * 4 + (v & 3);
-        if (m >= p.M) continue;
-        float val = acc[i][j][v] + bv;
+        const int dm = (v >> 2) * 8 + (v & 3);
+        if (mrow + dm >= p.M) continue;
+        float val = acc[i][j][v];
         if (p.relu) val = fmaxf(val, 0.f);
-        const size_t off = base + (size_t)m * ldo;
+        const size_t off = row0 + dm * ld;
         if (p.out_kind == 1) reinterpret_cast<float*>(obase)[off] = val;
         else reinterpret_cast<T*>(obase)[off] = from_f32<T>(val);
       }
