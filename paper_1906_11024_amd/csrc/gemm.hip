@@ -3,7 +3,7 @@
 // out[m][n] = sum_k A[m][k] * W[n][k]: both operands are contiguous along k, so a
 // lane's MFMA operand fragment is one 16-byte load.  A block of WM x WN waves
 // owns a (32*WM*TM) x (32*WN*TN) tile of the output; k is walked in chunks of 128
-// bytes per row.  Decode-time GEMMs are small (M = batch*beam rows) and therefore
+// (bf16: 256) bytes per row.  Decode-time GEMMs are small (M = batch*beam rows) and therefore
 // latency-bound, so the kernel is built to keep many loads in flight: a queue of
 // D chunks lives in registers (global loads issued D chunks ahead), each chunk is
 // then staged through one of two LDS buffers (rows padded to 144 bytes so that the
@@ -376,12 +376,16 @@ hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
     if (tile == 1) return launch_tile<bf16_t, 4, 2, 1, 2, 1, 2>(p, stream);
     if (shape == 2) return launch_tile<bf16_t, 1, 1, 1, 1, 4, 4>(p, stream);
     if (shape == 1) return launch_tile<bf16_t, 2, 1, 1, 1, 2, 4>(p, stream);
-    return launch_tile<bf16_t, 2, 2, 1, 1, 1, 4>(p, stream);
+    return chunks <= 3 ? launch_tile<bf16_t, 2, 2, 1, 1, 1, 2>(p, stream) : launch_tile<bf16_t, 2, 2, 1, 1, 1, 4>(p, stream);
   }
   if (tile == 1) return launch_tile<float, 4, 4, 1, 1, 1, 2>(p, stream);
-  if (shape == 2) return launch_tile<float, 1, 1, 1, 1, 4, 4>(p, stream);
-  if (shape == 1) return launch_tile<float, 2, 1, 1, 1, 2, 4>(p, stream);
-  return launch_tile<float, 2, 2, 1, 1, 1, 4>(p, stream);
+  // the register queue is always filled D chunks deep (clamped re-reads when the k
+  // range is shorter), so short ranges take the 2-deep variants
+  const int kw = shape == 2 ? 4 : (shape == 1 ? 2 : 1);
+  const bool shallow = (chunks + kw - 1) / kw <= 3;
+  if (shape == 2) return shallow ? launch_tile<float, 1, 1, 1, 1, 4, 2>(p, stream) : launch_tile<float, 1, 1, 1, 1, 4, 4>(p, stream);
+  if (shape == 1) return shallow ? launch_tile<float, 2, 1, 1, 1, 2, 2>(p, stream) : launch_tile<float, 2, 1, 1, 1, 2, 4>(p, stream);
+  return shallow ? launch_tile<float, 2, 2, 1, 1, 1, 2>(p, stream) : launch_tile<float, 2, 2, 1, 1, 1, 4>(p, stream);
 }
 
 }  // namespace san
