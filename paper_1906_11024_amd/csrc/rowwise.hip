@@ -79,10 +79,38 @@ __device__ __forceinline__ float4 layer_norm_vec(float4 v, bool active, int n, f
                      (v.z - mean) * rstd * g.z + b.z, (v.w - mean) * rstd * g.w + b.w);
 }
 
-// bias + residual + the nsplit partials of one 4-column group; the partial loads go out four at a time
+// bias + residual + the NS partials of one 4-column group.  Every load is
+// unconditional and issued before the first use (a load behind a branch is waited
+// for on the spot, and each such wait is a memory round trip): absent operands
+// are read from `safe`, a valid address, and dropped by a select.
+template <typename T, int NS>
+__device__ __forceinline__ float4 gather_fixed(const float* part, size_t split_stride, const T* bias, const T* res,
+                                               const T* safe) {
+  const float4 bv = load4(bias ? bias : safe);
+  const float4 rv = load4(res ? res : safe);
+  float4 pv[NS];
+#pragma unroll
+  for (int u = 0; u < NS; ++u) pv[u] = *reinterpret_cast<const float4*>(part + (size_t)u * split_stride);
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (bias) a = bv;
+  if (res) { a.x += rv.x; a.y += rv.y; a.z += rv.z; a.w += rv.w; }
+  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+  for (int u = 0; u < NS; ++u) { sum.x += pv[u].x; sum.y += pv[u].y; sum.z += pv[u].z; sum.w += pv[u].w; }
+  return make_float4(sum.x + a.x, sum.y + a.y, sum.z + a.z, sum.w + a.w);
+}
+// the split factors the GEMM launcher produces are powers of two up to 16; anything else takes the loop
 template <typename T>
 __device__ __forceinline__ float4 gather_update(const float* part, int nsplit, size_t split_stride, const T* bias,
-                                                const T* res) {
+                                                const T* res, const T* safe) {
+  switch (nsplit) {
+    case 1: return gather_fixed<T, 1>(part, split_stride, bias, res, safe);
+    case 2: return gather_fixed<T, 2>(part, split_stride, bias, res, safe);
+    case 4: return gather_fixed<T, 4>(part, split_stride, bias, res, safe);
+    case 8: return gather_fixed<T, 8>(part, split_stride, bias, res, safe);
+    case 16: return gather_fixed<T, 16>(part, split_stride, bias, res, safe);
+    default: break;
+  }
   float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
   if (bias) a = load4(bias);
   if (res) {
@@ -90,14 +118,9 @@ __device__ __forceinline__ float4 gather_update(const float* part, int nsplit, s
     a.x += rv.x; a.y += rv.y; a.z += rv.z; a.w += rv.w;
   }
   float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int s = 0; s < nsplit; s += 4) {
-    float4 pv[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-      pv[u] = (s + u < nsplit) ? *reinterpret_cast<const float4*>(part + (size_t)(s + u) * split_stride)
-                               : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) { sum.x += pv[u].x; sum.y += pv[u].y; sum.z += pv[u].z; sum.w += pv[u].w; }
+  for (int s = 0; s < nsplit; ++s) {
+    const float4 pv = *reinterpret_cast<const float4*>(part + (size_t)s * split_stride);
+    sum.x += pv.x; sum.y += pv.y; sum.z += pv.z; sum.w += pv.w;
   }
   return make_float4(sum.x + a.x, sum.y + a.y, sum.z + a.z, sum.w + a.w);
 }
@@ -114,17 +137,16 @@ __global__ __launch_bounds__(kLnMaxWaves * 64) void ln_reduce_kernel(const float
   const int c = threadIdx.x * 4;
   const bool active = c < n;
   const int cc = active ? c : 0;   // inactive threads load column 0 and drop it
-  // everything this thread needs is requested before anything is used
   const float4 g1 = load4(gamma + cc), b1 = load4(beta + cc);
   float4 g2 = g1, b2 = b1, u2 = make_float4(0.f, 0.f, 0.f, 0.f);
   if (s2.part) {
     g2 = load4(reinterpret_cast<const T*>(s2.gamma) + cc);
     b2 = load4(reinterpret_cast<const T*>(s2.beta) + cc);
     u2 = gather_update<T>(s2.part + (size_t)m * s2.ldp + cc, s2.nsplit, (size_t)M * s2.ldp,
-                          reinterpret_cast<const T*>(s2.bias) + cc, (const T*)nullptr);
+                          reinterpret_cast<const T*>(s2.bias) + cc, (const T*)nullptr, gamma + cc);
   }
   const float4 v = gather_update<T>(part + (size_t)m * ldp + cc, nsplit, (size_t)M * ldp, bias ? bias + cc : nullptr,
-                                    res ? res + (size_t)m * ldr + cc : nullptr);
+                                    res ? res + (size_t)m * ldr + cc : nullptr, gamma + cc);
   float4 y = layer_norm_vec(v, active, n, g1, b1, eps, slots, wid, lane, nwaves);
   if (s2.part) {
     // second sub-layer without a GEMM of its own in between (an enc-dec follower
