@@ -319,35 +319,45 @@ hipError_t launch_aan_post(int dtype, const float* z, const void* bg, const void
 // of the sentence, then writes the permuted rows, so the update is safe in place.
 constexpr int kMaxBeam = 32;
 
+// MAXB = compile-time cap of the beam.  Every load (step counter, parents, the old
+// entries; rows past the beam re-read the last one) goes out before anything is
+// used, so the kernel costs one memory round trip.
+template <int MAXB>
 __global__ void reorder_table_kernel(int* tab, int ld, const int* parent, const int* t_dev, int batch, int beam,
                                      int max_t) {
   const int b = blockIdx.y;
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  const int n = min(*t_dev, max_t);
-  if (j >= n) return;
-  int old[kMaxBeam];
+  if (j >= max_t) return;
+  const int t = *t_dev;
+  int pl[MAXB], old[MAXB];
 #pragma unroll
-  for (int k = 0; k < kMaxBeam; ++k)
-    if (k < beam) old[k] = tab[(size_t)(b * beam + k) * ld + j];
+  for (int k = 0; k < MAXB; ++k) pl[k] = parent[b * beam + min(k, beam - 1)] - b * beam;
 #pragma unroll
-  for (int k = 0; k < kMaxBeam; ++k) {
-    if (k < beam) {
-      const int pl = parent[b * beam + k] - b * beam;
-      if (pl >= 0 && pl < beam && pl != k) {
-        int v = old[0];
+  for (int k = 0; k < MAXB; ++k) old[k] = tab[(size_t)(b * beam + min(k, beam - 1)) * ld + j];
+  if (j >= min(t, max_t)) return;
 #pragma unroll
-        for (int q = 1; q < kMaxBeam; ++q)
-          if (q == pl) v = old[q];
-        tab[(size_t)(b * beam + k) * ld + j] = v;
-      }
+  for (int k = 0; k < MAXB; ++k) {
+    if (k < beam && pl[k] >= 0 && pl[k] < beam && pl[k] != k) {
+      int v = old[0];
+#pragma unroll
+      for (int q = 1; q < MAXB; ++q)
+        if (q == pl[k]) v = old[q];
+      tab[(size_t)(b * beam + k) * ld + j] = v;
     }
   }
 }
 hipError_t launch_reorder_table(int* tab, int ld, const int* parent, const int* t_dev, int batch, int beam,
                                 int max_t, hipStream_t stream) {
-  if (beam > kMaxBeam) return hipErrorInvalidValue;
+  if (beam > kMaxBeam || beam < 1 || max_t > ld) return hipErrorInvalidValue;
   dim3 grid((max_t + 127) / 128, batch);
-  hipLaunchKernelGGL(reorder_table_kernel, grid, dim3(128), 0, stream, tab, ld, parent, t_dev, batch, beam, max_t);
+  if (beam <= 4)
+    hipLaunchKernelGGL(reorder_table_kernel<4>, grid, dim3(128), 0, stream, tab, ld, parent, t_dev, batch, beam, max_t);
+  else if (beam <= 8)
+    hipLaunchKernelGGL(reorder_table_kernel<8>, grid, dim3(128), 0, stream, tab, ld, parent, t_dev, batch, beam, max_t);
+  else if (beam <= 16)
+    hipLaunchKernelGGL(reorder_table_kernel<16>, grid, dim3(128), 0, stream, tab, ld, parent, t_dev, batch, beam, max_t);
+  else
+    hipLaunchKernelGGL(reorder_table_kernel<32>, grid, dim3(128), 0, stream, tab, ld, parent, t_dev, batch, beam, max_t);
   return hipGetLastError();
 }
 
