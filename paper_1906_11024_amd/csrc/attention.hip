@@ -178,30 +178,63 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnPara
     }
     wave_lds_sync();
     if (CH < n) load_chunk(Vp, ldv, CH, vb1);   // second V chunk travels during the softmax
-    // ---- softmax over key positions, one query at a time
+    if (NQ == 4) {
+      // ---- softmax over key positions, the four queries side by side: lanes
+      // [16 i, 16 i + 16) own query i, so the maxima and sums are 16-lane row
+      // reductions (DPP only) and the four rows cost one pass instead of four
+      const int i = lane >> 4, l16 = lane & 15;
+      int qr = qrow[0];
 #pragma unroll
-    for (int i = 0; i < NQ; ++i) {
-      if (qrow[i] < 0) continue;
+      for (int q = 1; q < NQ; ++q)
+        if (i == q) qr = qrow[q];
       float* row = sc + i * p.lmax;
       float m = -INFINITY;
-      for (int j = lane; j < n; j += kWave) m = fmaxf(m, row[j]);
-      m = wave_max(m);
+      for (int j = l16; j < n; j += 16) m = fmaxf(m, row[j]);
+      m = group_max<16>(m);
       float s = 0.f;
-      for (int j = lane; j < n; j += kWave) {
+      for (int j = l16; j < n; j += 16) {
         const float e = (row[j] == -INFINITY) ? 0.f : expf(row[j] - m);
         row[j] = e;
         s += e;
       }
-      s = wave_sum(s);
+      s = group_sum<16>(s);
       const float inv = s > 0.f ? 1.0f / s : 0.f;
-      float* Sg = p.S_buf ? p.S_buf + ((size_t)qrow[i] * p.H + h) * p.ldS : nullptr;
-      for (int j = lane; j < n; j += kWave) {
-        const float w = row[j] * inv;
-        row[j] = w;
-        if (p.emit) Sg[j] = w;
+      if (qr >= 0) {
+        float* Sg = p.S_buf ? p.S_buf + ((size_t)qr * p.H + h) * p.ldS : nullptr;
+        for (int j = l16; j < n; j += 16) {
+          const float w = row[j] * inv;
+          row[j] = w;
+          if (p.emit) Sg[j] = w;
+        }
+        if (p.emit && p.zero_tail)
+          for (int j = n + l16; j < p.ldS; j += 16) Sg[j] = 0.f;
       }
-      if (p.emit && p.zero_tail)
-        for (int j = n + lane; j < p.ldS; j += kWave) Sg[j] = 0.f;
+    } else {
+      // ---- softmax over key positions, one query at a time
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) {
+        if (qrow[i] < 0) continue;
+        float* row = sc + i * p.lmax;
+        float m = -INFINITY;
+        for (int j = lane; j < n; j += kWave) m = fmaxf(m, row[j]);
+        m = wave_max(m);
+        float s = 0.f;
+        for (int j = lane; j < n; j += kWave) {
+          const float e = (row[j] == -INFINITY) ? 0.f : expf(row[j] - m);
+          row[j] = e;
+          s += e;
+        }
+        s = wave_sum(s);
+        const float inv = s > 0.f ? 1.0f / s : 0.f;
+        float* Sg = p.S_buf ? p.S_buf + ((size_t)qrow[i] * p.H + h) * p.ldS : nullptr;
+        for (int j = lane; j < n; j += kWave) {
+          const float w = row[j] * inv;
+          row[j] = w;
+          if (p.emit) Sg[j] = w;
+        }
+        if (p.emit && p.zero_tail)
+          for (int j = n + lane; j < p.ldS; j += kWave) Sg[j] = 0.f;
+      }
     }
   } else {
     if (CH < n) load_chunk(Vp, ldv, CH, vb1);
