@@ -172,8 +172,13 @@ SAN_API int san_debug_get(san_ctx* ctx, int32_t what, int32_t layer, void* dst_d
 /* n consecutive beam-search steps without returning to the host (Sec. 1: the
  * decoder produces one word at a time until the end): each step is
  * san_decode_step + san_topk with k = beam + san_beam_reorder, the chosen tokens
- * and scores feeding the next step.  With EOS handling on, finished hypotheses
- * keep extending with EOS at no cost; the call always runs n steps.
+ * and scores feeding the next step.  With EOS handling on (eos_id >= 0),
+ * finished hypotheses keep extending with EOS at no cost, and the call returns
+ * early once every sentence of the batch is finished: the count of finished
+ * sentences is read back every 8 steps (one stream synchronisation each), so up
+ * to 7 further all-EOS steps may have run.  san_step tells how many steps were
+ * done; rows of the out_* arrays past that are not written.  With eos_id < 0
+ * the call always runs n steps and never synchronises.
  *   tokens_dev      DEVICE int32 [rows]     input tokens of the first step
  *   cum_io_dev      DEVICE fp32  [rows]     cumulative scores, in: before, out: after
  *   out_tokens_dev  DEVICE int32 [n][rows]  token chosen for every row at every step
@@ -187,6 +192,12 @@ SAN_API int san_debug_get(san_ctx* ctx, int32_t what, int32_t layer, void* dst_d
 SAN_API int san_decode_n(san_ctx* ctx, int32_t n, const int32_t* tokens_dev, float* cum_io_dev,
                          int32_t* out_tokens_dev, int32_t* out_parents_dev, float* logits_work_dev,
                          int32_t use_graph);
+
+/* Number of sentences of the current batch that are finished: every hypothesis
+ * kept by the last beam step (san_topk with k == beam, or a step of
+ * san_decode_n) ends in eos_id.  Always 0 with eos_id < 0.  Synchronises the
+ * context's stream.  count_out HOST.  Errors: SAN_EINVAL, SAN_ESTATE. */
+SAN_API int san_finished(san_ctx* ctx, int32_t* count_out);
 
 /* ---- Learning a sharing policy (Sec. 3.3) ----
  * san_policy_accumulate: after a decode step of a context with cfg.debug = 1 (every

@@ -354,6 +354,13 @@ class SanOracle:
         return logits if return_all else logits[:, -1, :]
 
     # ------------------------------------------------------------------ search
+    def finished(self, tokens, beam):
+        """Sentences whose kept hypotheses all end in EOS after a beam step (Sec. 1:
+        decoding goes on until the end symbol is reached); tokens [batch*beam]."""
+        if self.eos_id < 0:
+            return 0
+        return int((np.asarray(tokens).reshape(-1, beam) == self.eos_id).all(axis=1).sum())
+
     def topk(self, logits, cum_score, k, last_tokens=None):
         """Beam step.  logits [rows, V], cum_score [rows]; rows of sentence b are
         b*beam .. b*beam+beam-1.  Candidate (row r, word v) scores

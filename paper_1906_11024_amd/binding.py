@@ -23,7 +23,7 @@ SAN_DBG_S_SELF, SAN_DBG_A_SELF, SAN_DBG_S_CTX, SAN_DBG_A_CTX, SAN_DBG_HIDDEN = r
 EXPORTS = ["san_weight_bytes", "san_init", "san_encode", "san_rewind", "san_decode_step", "san_topk",
            "san_beam_reorder", "san_debug_get", "san_step", "san_device_bytes", "san_last_launch_count",
            "san_last_error", "san_free", "san_profile", "san_profile_read",
-           "san_policy_accumulate", "san_policy_read", "san_policy_search", "san_decode_n", "san_stream_read"]
+           "san_policy_accumulate", "san_policy_read", "san_policy_search", "san_decode_n", "san_stream_read", "san_finished"]
 
 KINDS = ["misc", "proj", "attn_self", "attn_apply", "out", "ln", "attn_ctx", "attn_ctx_apply", "ffn", "logits",
          "topk", "reorder", "aan"]
@@ -81,6 +81,8 @@ def lib():
         l.san_device_bytes.argtypes = [vp, i32]
         l.san_stream_read.restype = C.c_int
         l.san_stream_read.argtypes = [vp, vp, C.c_size_t]
+        l.san_finished.restype = C.c_int
+        l.san_finished.argtypes = [vp, C.POINTER(C.c_int32)]
         l.san_last_launch_count.restype = i32
         l.san_last_launch_count.argtypes = [vp]
         l.san_last_error.restype = C.c_char_p
@@ -227,6 +229,12 @@ class San:
 
     def device_bytes(self, which):
         return int(self._l.san_device_bytes(self._h, which))
+
+    def finished(self):
+        """sentences of the batch whose kept hypotheses all end in EOS (synchronises the stream)"""
+        n = C.c_int32(0)
+        self._check(self._l.san_finished(self._h, C.byref(n)))
+        return int(n.value)
 
     def stream_read(self, buf):
         """queue one plain streaming read of the whole device tensor `buf` (measurement aid)"""

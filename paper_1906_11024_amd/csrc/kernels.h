@@ -105,9 +105,11 @@ struct TopkHistory {
   int* tok; int* par;
   const int* t_dev; const int* t0_dev;
 };
+// done (optional, eos_id >= 0): int[batch + 1]; done[b] becomes 1 once every pick of sentence b is EOS,
+// done[batch] counts such sentences
 hipError_t launch_topk(const float* logits, const float* cum, const int* last_tok, int eos_id, int batch, int beam,
                        int vocab, int k, float* cand_lp, int* cand_idx, int* out_tok, int* out_parent,
-                       float* out_score, hipStream_t stream, const TopkHistory* hist = nullptr);
+                       float* out_score, hipStream_t stream, const TopkHistory* hist = nullptr, int* done = nullptr);
 // per sentence, in place: tab[r][j] = tab[parent[r]][j] for j < *t_dev
 hipError_t launch_reorder_table(int* tab, int ld, const int* parent, const int* t_dev, int batch, int beam,
                                 int max_t, hipStream_t stream);

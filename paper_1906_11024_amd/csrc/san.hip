@@ -85,6 +85,8 @@ struct san_ctx {
   const void* graph_key[3] = {nullptr, nullptr, nullptr};
   int graph_rows = 0;
   int *t_dev = nullptr, *anc = nullptr, *hist = nullptr, *last_tok = nullptr, *src_len = nullptr;
+  int* done_dev = nullptr;     // [max_batch] finished flags, then the count of finished sentences
+  int* done_host = nullptr;    // pinned, one int
   float* cand_lp = nullptr;
   int* cand_idx = nullptr;
   // state
@@ -478,6 +480,9 @@ static int build_ctx(san_ctx* c, const Blob& bl, const void* blob, const std::ve
     if (nocache) TRY(dalloc(c, (void**)&c->hist, (size_t)c->rows_max * T * 4, false));
     TRY(dalloc(c, (void**)&c->last_tok, (size_t)c->rows_max * 4, false));
     TRY(dalloc(c, (void**)&c->src_len, (size_t)cfg->max_batch * 4, false));
+    TRY(dalloc(c, (void**)&c->done_dev, ((size_t)cfg->max_batch + 1) * 4, false));
+    HIP_TRY(c, hipMemset(c->done_dev, 0, ((size_t)cfg->max_batch + 1) * 4));
+    HIP_TRY(c, hipHostMalloc((void**)&c->done_host, 64, hipHostMallocDefault));
     TRY(dalloc(c, (void**)&c->cand_lp, (size_t)c->rows_max * 32 * 4, false));
     TRY(dalloc(c, (void**)&c->cand_idx, (size_t)c->rows_max * 32 * 4, false));
     HIP_TRY(c, hipMemset(c->t_dev, 0, 256));
@@ -503,6 +508,7 @@ void san_free(san_ctx* ctx) {
   if (ctx->graph2) (void)hipGraphExecDestroy(ctx->graph2);
   for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
   for (void* p : ctx->allocs) (void)hipFree(p);
+  if (ctx->done_host) (void)hipHostFree(ctx->done_host);
   delete ctx;
 }
 
@@ -592,6 +598,7 @@ int san_encode(san_ctx* c, const int32_t* src_ids_dev, const int32_t* src_len_de
     if ((rc = gemm(c, c->x, d, L.wkv_c, L.bkv_c, Ms, N, d, 0, 0, L.mem, N))) return rc;
   }
   HIP_TRY(c, hipMemsetAsync(c->t_dev, 0, 4, c->stream));
+  HIP_TRY(c, hipMemsetAsync(c->done_dev, 0, ((size_t)c->cfg.max_batch + 1) * 4, c->stream));
   c->batch = batch; c->max_src = max_src; c->t = 0;
   c->graph_rows = 0;   // a captured step graph is tied to the batch shape
   return prof_flush(c);
@@ -601,6 +608,7 @@ int san_rewind(san_ctx* c) {
   if (!c) return SAN_EINVAL;
   if (c->t < 0) return fail(c, SAN_ESTATE, "san_rewind before san_encode");
   HIP_TRY(c, hipMemsetAsync(c->t_dev, 0, 4, c->stream));
+  HIP_TRY(c, hipMemsetAsync(c->done_dev, 0, ((size_t)c->cfg.max_batch + 1) * 4, c->stream));
   c->t = 0;
   return SAN_OK;
 }
@@ -821,7 +829,8 @@ int san_topk(san_ctx* c, const float* logits_dev, const float* cum_score_dev, in
   c->kind = SAN_K_TOPK;
   const long pm = prof_mark(c);
   HIP_TRY(c, launch_topk(logits_dev, cum_score_dev, c->last_tok, c->cfg.eos_id, c->batch, c->cfg.beam, c->V, k,
-                         c->cand_lp, c->cand_idx, out_token_dev, out_parent_dev, out_score_dev, c->stream));
+                         c->cand_lp, c->cand_idx, out_token_dev, out_parent_dev, out_score_dev, c->stream, nullptr,
+                         k == c->cfg.beam ? c->done_dev : nullptr));
   prof_close(c, pm);
   return prof_flush(c);
 }
@@ -901,13 +910,23 @@ int san_profile_read(san_ctx* c, double* ms_out, int64_t* launches_out, int32_t 
   return rc;
 }
 
+int san_finished(san_ctx* c, int32_t* count_out) {
+  if (!c || !count_out) return fail(c, SAN_EINVAL, "san_finished: null argument");
+  if (c->t < 0) return fail(c, SAN_ESTATE, "san_finished before san_encode");
+  HIP_TRY(c, hipMemcpyAsync(c->done_host, c->done_dev + c->cfg.max_batch, 4, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  *count_out = *c->done_host;
+  return SAN_OK;
+}
+
 // One beam-search step on the ping-pong buffers: parity p reads set p, writes set p^1.
 static int loop_step(san_ctx* c, int p, int32_t* out_tokens, int32_t* out_parents, float* logits) {
   int rc = san_decode_step(c, c->pp_tok[p], logits);
   if (rc) return rc;
   TopkHistory h{out_tokens, out_parents, c->t_dev, c->t0_dev};
   HIP_TRY(c, launch_topk(logits, c->pp_cum[p], c->last_tok, c->cfg.eos_id, c->batch, c->cfg.beam, c->V, c->cfg.beam,
-                         c->cand_lp, c->cand_idx, c->pp_tok[p ^ 1], c->pp_par, c->pp_cum[p ^ 1], c->stream, &h));
+                         c->cand_lp, c->cand_idx, c->pp_tok[p ^ 1], c->pp_par, c->pp_cum[p ^ 1], c->stream, &h,
+                         c->done_dev));
   return san_beam_reorder(c, c->pp_par);
 }
 
@@ -936,7 +955,20 @@ int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io
   HIP_TRY(c, hipMemcpyAsync(c->pp_tok[0], tokens_dev, (size_t)rows * 4, hipMemcpyDeviceToDevice, c->stream));
   HIP_TRY(c, hipMemcpyAsync(c->pp_cum[0], cum_io_dev, (size_t)rows * 4, hipMemcpyDeviceToDevice, c->stream));
   HIP_TRY(c, hipMemcpyAsync(c->t0_dev, c->t_dev, 4, hipMemcpyDeviceToDevice, c->stream));
-  int done = 0, rc;
+  int done = 0, rc, check_rc = SAN_OK, last_check = 0;
+  // With EOS handling on, the loop stops once every sentence is finished; the
+  // count is read back (one stream synchronisation) every kCheckEvery steps.
+  constexpr int kCheckEvery = 8;
+  bool stop = false;
+  auto all_finished = [&](int steps_done) -> bool {
+    if (stop) return true;
+    if (c->cfg.eos_id < 0 || steps_done - last_check < kCheckEvery) return false;
+    last_check = steps_done;
+    int32_t cnt = 0;
+    check_rc = san_finished(c, &cnt);
+    stop = check_rc != SAN_OK || cnt >= c->batch;
+    return stop;
+  };
   if (use_graph && n >= 2) {
     // the graph holds two steps (parity 0 then 1); it is rebuilt when the caller's
     // buffers or the batch change
@@ -963,14 +995,15 @@ int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io
       c->graph_key[0] = out_tokens_dev; c->graph_key[1] = out_parents_dev; c->graph_key[2] = logits_work_dev;
       c->graph_rows = rows;
     }
-    for (; c->graph2 && done + 2 <= n; done += 2) {
+    for (; c->graph2 && done + 2 <= n && !all_finished(done); done += 2) {
       HIP_TRY(c, hipGraphLaunch(c->graph2, c->stream));
       c->t += 2;
     }
   }
-  for (; done < n; ++done)
+  for (; done < n && !all_finished(done); ++done)
     if ((rc = loop_step(c, done & 1, out_tokens_dev, out_parents_dev, logits_work_dev))) return rc;
-  HIP_TRY(c, hipMemcpyAsync(cum_io_dev, c->pp_cum[n & 1], (size_t)rows * 4, hipMemcpyDeviceToDevice, c->stream));
+  if (check_rc) return check_rc;
+  HIP_TRY(c, hipMemcpyAsync(cum_io_dev, c->pp_cum[done & 1], (size_t)rows * 4, hipMemcpyDeviceToDevice, c->stream));
   return SAN_OK;
 }
 

@@ -268,7 +268,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_row_kernel(const float* log
 // One wave per sentence: merge the beam*k candidates, keep the k best.
 __global__ __launch_bounds__(64) void topk_merge_kernel(const float* cand_lp, const int* cand_idx, const float* cum,
                                                         int beam, int vocab, int k, int* out_tok, int* out_parent,
-                                                        float* out_score, TopkHistory hist) {
+                                                        float* out_score, TopkHistory hist, int eos_id, int* done) {
   const int b = blockIdx.x, lane = threadIdx.x;
   // multi-step decoding: this step's picks are also appended to the caller's
   // [step][rows] arrays; the step index comes from the device-side counters
@@ -294,11 +294,20 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(const float* cand_lp, co
       hist.par[hoff + (size_t)b * k + lane] = pr;
     }
   }
+  if (done && eos_id >= 0) {
+    // the sentence is finished once every hypothesis kept ends in EOS (it stays so: such
+    // a hypothesis can only be extended by EOS); counted once
+    const bool open = lane < k && (best.i == kNone || best.i % vocab != eos_id);
+    if (__ballot(open) == 0 && lane == 0 && done[b] == 0) {
+      done[b] = 1;
+      atomicAdd(&done[gridDim.x], 1);
+    }
+  }
 }
 
 hipError_t launch_topk(const float* logits, const float* cum, const int* last_tok, int eos_id, int batch, int beam,
                        int vocab, int k, float* cand_lp, int* cand_idx, int* out_tok, int* out_parent,
-                       float* out_score, hipStream_t stream, const TopkHistory* hist) {
+                       float* out_score, hipStream_t stream, const TopkHistory* hist, int* done) {
   const int rows = batch * beam;
   if (rows <= 0) return hipSuccess;
   if (vocab <= kTopkVpt * kTopkThreads)
@@ -312,7 +321,7 @@ hipError_t launch_topk(const float* logits, const float* cum, const int* last_to
   TopkHistory h{};
   if (hist) h = *hist;
   hipLaunchKernelGGL(topk_merge_kernel, dim3(batch), dim3(64), 0, stream, cand_lp, cand_idx, cum, beam, vocab, k,
-                     out_tok, out_parent, out_score, h);
+                     out_tok, out_parent, out_score, h, eos_id, done);
   return hipGetLastError();
 }
 

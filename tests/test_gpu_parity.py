@@ -460,6 +460,66 @@ def test_decode_n_equals_step_by_step(use_graph):
         gpu.close()
 
 
+@pytest.mark.parametrize("use_graph", [False, True])
+def test_decode_n_stops_when_every_sentence_is_finished(use_graph):
+    """With EOS handling on, san_decode_n returns at the first 8-step check after every kept
+    hypothesis of every sentence ends in EOS; until then it equals the per-call loop."""
+    cfg = mid_cfg(steps=64, V=8, batch=4, beam=3)          # tiny vocabulary: EOS gets picked often
+    w = wl.make_weights(cfg, seed=4)
+    src, lens = wl.make_source(mid_cfg(batch=4), 4)
+    src = np.minimum(src, 7)
+    beam, B, V, T = 3, 12, 8, 64
+    ref_gpu = hz.make_gpu(cfg, w, eos_id=wl.EOS_ID)
+    # per-call loop, reading the finished count after every step
+    ref_gpu.encode(torch.from_numpy(src).cuda(), torch.from_numpy(lens).cuda())
+    tokens = torch.full((B,), wl.BOS_ID, dtype=torch.int32, device="cuda")
+    cum0 = np.full(B, -np.inf, dtype=np.float32)
+    cum0[0::beam] = 0.0
+    cum = torch.from_numpy(cum0).cuda()
+    logits = torch.empty((B, V), dtype=torch.float32, device="cuda")
+    o_tok = torch.empty((4, beam), dtype=torch.int32, device="cuda")
+    o_par = torch.empty((4, beam), dtype=torch.int32, device="cuda")
+    o_sc = torch.empty((4, beam), dtype=torch.float32, device="cuda")
+    ref_tok, ref_sc, counts = [], [], []
+    for _ in range(T):
+        ref_gpu.decode_step(tokens, logits)
+        ref_gpu.topk(logits, cum, beam, o_tok, o_par, o_sc)
+        ref_gpu.beam_reorder(o_par.reshape(-1))
+        tokens, cum = o_tok.reshape(-1).clone(), o_sc.reshape(-1).clone()
+        ref_tok.append(tokens.cpu().numpy())
+        ref_sc.append(cum.cpu().numpy())
+        counts.append(ref_gpu.finished())
+    ref_gpu.close()
+    # the count is what the oracle's definition says, and a finished sentence stays finished
+    orc = hz.make_oracle(cfg, w, eos_id=wl.EOS_ID)
+    for t in range(T):
+        assert counts[t] == orc.finished(ref_tok[t], beam), t
+        assert t == 0 or counts[t] >= counts[t - 1]
+    assert counts[-1] == 4, "pick another seed: not every sentence finishes within 64 steps"
+    s_star = counts.index(4) + 1                        # steps after which all four are finished
+    expect = min(T, 8 * ((s_star + 7) // 8))
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        gpu = hz.make_gpu(cfg, w, eos_id=wl.EOS_ID)
+        gpu.encode(torch.from_numpy(src).cuda(), torch.from_numpy(lens).cuda())
+        for rep in range(2):
+            gpu.rewind()
+            out_tok = torch.full((T, B), -7, dtype=torch.int32, device="cuda")
+            out_par = torch.full((T, B), -7, dtype=torch.int32, device="cuda")
+            cum = torch.from_numpy(cum0).cuda()
+            gpu.decode_n(T, torch.full((B,), wl.BOS_ID, dtype=torch.int32, device="cuda"), cum, out_tok, out_par,
+                         logits, use_graph)
+            stream.synchronize()
+            assert gpu.step == expect, (gpu.step, s_star, expect)
+            assert gpu.finished() == 4
+            got = out_tok.cpu().numpy()
+            for t in range(expect):
+                assert np.array_equal(got[t], ref_tok[t]), (rep, t)
+            assert (got[expect:] == -7).all()           # rows past the exit are not written
+            assert np.array_equal(cum.cpu().numpy(), ref_sc[expect - 1])
+        gpu.close()
+
+
 # ------------------------------------------------------ head widths, extreme shapes
 @pytest.mark.parametrize("d,H,dtype", [(128, 8, "f32"), (128, 4, "f32"), (256, 2, "f32"), (128, 8, "bf16"),
                                        (256, 8, "bf16"), (256, 2, "bf16")])

@@ -505,3 +505,14 @@ def test_encoder_side_sharing():
     assert np.allclose(e0, e1, atol=1e-12)
     with pytest.raises(ValueError):
         so.SanOracle(cfg, w, [2], [2], enc_pi=[2, 2])
+
+
+def test_finished_count_definition():
+    """a sentence is finished when every kept hypothesis ends in EOS; none is with EOS handling off"""
+    cfg = wl.get_config("tiny")
+    w = wl.make_weights(cfg, seed=0)
+    orc = so.SanOracle(cfg, w, cfg["self_pi"], cfg["encdec_pi"], eos_id=2)
+    toks = np.array([2, 2, 2,   2, 5, 2,   7, 7, 7,   2, 2, 2])
+    assert orc.finished(toks, 3) == 2
+    assert orc.finished(toks, 1) == 8
+    assert so.SanOracle(cfg, w, cfg["self_pi"], cfg["encdec_pi"], eos_id=-1).finished(toks, 3) == 0
