@@ -321,24 +321,37 @@ static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
 
 // Tile choice: 0 = 64x64 or smaller (2x2 waves and the k-group shapes below);
 // 1 = 128x128 once that still gives ~one block per CU (the output layer);
-// 2 = 256x256 (bf16 only) once that does.  The wide output layer is bound by
+// 2 = 256x256 (bf16 only) once that does; 3 = see below.  The wide output layer is bound by
 // the operand traffic between L2 and the CUs, |X| * N/BN + |W| * M/BM, so the
 // biggest tile that still fills the chip wins: measured on the output layer,
 // fp32 M = 256: 128x128 with 16 waves 69 us (8 waves 81, 256x128 71-76, 256x256
 // 132: half the CUs idle); bf16 M = 512: 256x256 with 16 waves 44-48 us (128x128
 // 63, 256x128 51, 128x256 55).
-int gemm_pick_tile(int M, int N, int dtype) {
+// 3 = 64x128 with 8 waves and 256-byte chunks (bf16 only, K % 128 == 0): the bf16
+// decode GEMMs are bound by the same operand traffic (their MFMA time is
+// negligible), and this tile moves 25-30 % fewer bytes than 64x64 at the same
+// block count after splitting k (Big FFN-1 11.9 -> 9.6 us, FFN-2 12.4 -> 10.7).
+// can_split: the GEMM writes partials, so k may be divided over up to 4 blocks to fill the chip
+int gemm_pick_tile(int M, int N, int K, int dtype, bool can_split) {
   if (dtype == 1 && M >= 256 && (long)((M + 255) / 256) * ((N + 255) / 256) >= 200) return 2;
   if (M >= 128 && (long)((M + 127) / 128) * ((N + 127) / 128) >= 200) return 1;
+  if (dtype == 1 && K % 128 == 0 && (long)((M + 63) / 64) * ((N + 127) / 128) >= (can_split ? 64 : 160)) return 3;
   return 0;
 }
 
 int gemm_pick_ksplit(int M, int N, int K, int dtype) {
-  if (gemm_pick_tile(M, N, dtype) != 0) return 1;
+  const int tile = gemm_pick_tile(M, N, K, dtype, true);
+  if (tile == 1 || tile == 2) return 1;
+  int ks = 1;
+  if (tile == 3) {
+    const int nchunks = K / 128;   // 256-byte chunks
+    const long blocks = (long)((M + 63) / 64) * ((N + 127) / 128);
+    while (blocks * ks < 192 && nchunks / (ks * 2) >= 2 && ks < 16) ks *= 2;
+    return ks;
+  }
   const int epc = dtype == 1 ? 64 : 32;
   const int nchunks = K / epc;
   const long blocks = (long)((M + 63) / 64) * ((N + 63) / 64);
-  int ks = 1;
   // aim for >= 256 blocks (one per CU), keep at least 2 chunks of k per block
   while (blocks * ks < 256 && nchunks / (ks * 2) >= 2 && ks < 16) ks *= 2;
   return ks;
@@ -352,7 +365,8 @@ hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
   const int epc = dtype == 1 ? 64 : 32;
   if (p.K <= 0 || p.K % epc != 0 || p.ksplit < 1) return hipErrorInvalidValue;
   if (p.ksplit > 1 && p.out_kind != 2) return hipErrorInvalidValue;   // only partial outputs may be split across blocks
-  const int tile = p.ksplit > 1 ? 0 : gemm_pick_tile(p.M, p.N, dtype);
+  int tile = gemm_pick_tile(p.M, p.N, p.K, dtype, p.out_kind == 2);
+  if (p.ksplit > 1 && tile != 3) tile = 0;   // only the small tiles split k across blocks
   // A wave's MFMA chain over the whole k range is what bounds a small GEMM, and
   // only waves on different SIMDs run their chains in parallel.  When 64x64 tiles
   // would leave most SIMDs idle, use smaller tiles and deal each tile's k range to
@@ -368,6 +382,7 @@ hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
   }
   if (dtype == 1) {
     if (tile == 2) return launch_tile<bf16_t, 4, 4, 2, 2, 1, 2>(p, stream);
+    if (tile == 3) return launch_tile<bf16_t, 2, 4, 1, 1, 1, 2, 256>(p, stream);
     if (wide && tile != 1) {   // (the 128x128 tile with wide chunks would not fit two blocks per CU: slower)
       if (shape == 2) return launch_tile<bf16_t, 1, 1, 1, 1, 4, 2, 256>(p, stream);
       if (shape == 1) return launch_tile<bf16_t, 2, 1, 1, 1, 2, 2, 256>(p, stream);
