@@ -261,6 +261,9 @@ def main():
         variants = [("unshared_cached", [1] * Ld, [1] * Ld, sb.SAN_SHARE_A, 1, 2 * T)]
         if cfg["self_kind"] != "aan":
             variants.append(("san_share_s", cfg["self_pi"], cfg["encdec_pi"], sb.SAN_SHARE_S, 1, 2 * T))
+            if Ld == 6:
+                # the uniform policy of Sec. 4.2: one self-attention block over the stack, enc-dec {3,3}
+                variants.append(("san_uniform_policy", [6], [3, 3], sb.SAN_SHARE_A, 1, 2 * T))
             variants.append(("san_no_cache", cfg["self_pi"], cfg["encdec_pi"], sb.SAN_SHARE_A, 0, T))
             variants.append(("unshared_no_cache", [1] * Ld, [1] * Ld, sb.SAN_SHARE_A, 0, T))
         for name, spi, cpi, share, cache, k in variants:

@@ -66,7 +66,21 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
   const int tg = tid % NG;
   const int wm = w_in % WM, wn = w_in / WM;
   const int l32 = lane & 31, kh = lane >> 5;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  // Tile of this block.  Workgroups go to the 8 XCDs round-robin by their linear
+  // index, and every XCD has its own L2.  With the natural (x = column tile, y =
+  // row tile) order the row tiles that share a weight tile land on one XCD only
+  // when the number of column tiles is a multiple of 8; otherwise (the output
+  // layer: 250 or 125 column tiles) the launcher asks for this mapping: XCD c takes
+  // the column tiles c, c+8, ... and runs the row tiles of one column tile back to
+  // back, so a weight tile leaves HBM once.
+  int tile_x = blockIdx.x, tile_y = blockIdx.y;
+  if (p.xcd_rows > 0) {
+    const int slot = blockIdx.x >> 3;
+    tile_y = slot % p.xcd_rows;
+    tile_x = (slot / p.xcd_rows) * 8 + (blockIdx.x & 7);
+    if (tile_x * BN >= p.N) return;
+  }
+  const int m0 = tile_y * BM, n0 = tile_x * BN;
   unsigned char* Xs = smem + kg * STAGE;           // [2][BM][144]
   unsigned char* Ws = Xs + 2 * BM * kRowBytes;     // [2][BN][144]
 
@@ -297,7 +311,7 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
       }
     }
   }
-  if (p.bump && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *p.bump = *p.bump + 1;
+  if (p.bump && tile_x == 0 && tile_y == 0 && tid == 0) *p.bump = *p.bump + 1;
 }
 
 template <typename T, int WM, int WN, int TM, int TN, int KW, int D, int CB = 128>
@@ -315,7 +329,13 @@ static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
       raised = true;
     }
   }
-  hipLaunchKernelGGL((gemm_kernel<T, WM, WN, TM, TN, KW, D, CB>), grid, dim3(WM * WN * KW * 64), smem, stream, p);
+  GemmParams q = p;
+  q.xcd_rows = 0;
+  if (grid.x % 8 != 0 && grid.y > 1 && grid.z == 1) {
+    q.xcd_rows = (int)grid.y;
+    grid = dim3((grid.x + 7) / 8 * 8 * grid.y, 1, 1);
+  }
+  hipLaunchKernelGGL((gemm_kernel<T, WM, WN, TM, TN, KW, D, CB>), grid, dim3(WM * WN * KW * 64), smem, stream, q);
   return hipGetLastError();
 }
 

@@ -124,6 +124,24 @@ def test_mid_fp32_lockstep(share, sharp):
     gpu.close()
 
 
+@pytest.mark.parametrize("spi,cpi,share", [([4], [4], "A"), ([4], [2, 2], "S"), ([2, 2], [1, 3], "A"),
+                                           ([3, 1], [4], "S"), ([1, 1, 2], [3, 1], "A")])
+def test_mid_fp32_policies(spi, cpi, share):
+    """Other policies than the default one, among them one block over the whole
+    stack (the uniform self-attention policy of Sec. 4.2) and blocks of unequal
+    sizes in either attention (Sec. 3.3's learned policies)."""
+    cfg = mid_cfg(steps=20)
+    w = wl.make_weights(cfg, seed=21, sharp=4.0)
+    src, lens = ragged(cfg, 21)
+    gpu = hz.make_gpu(cfg, w, spi, cpi, share)
+    ls = hz.Lockstep(gpu, hz.make_oracle(cfg, w, spi, cpi, share), src, lens, cfg["beam"])
+    for t in range(cfg["steps"]):
+        ls.step(tie_tol=5e-4)
+    assert max(ls.log["logit_err"]) <= F32_TOL
+    assert sum(ls.log["exact"]) >= 0.8 * cfg["steps"]
+    gpu.close()
+
+
 @pytest.mark.parametrize("beam", [8, 20])
 def test_mid_fp32_large_beams(beam):
     """Beam sizes of the paper's speed-vs-beam study (Fig. 5: 4..20)."""
