@@ -127,7 +127,8 @@ SAN_API int san_encode(san_ctx* ctx, const int32_t* src_ids_dev, const int32_t* 
                int32_t batch, int32_t max_src);
 
 /* Rewind the decoder to step 0 for the batch already encoded (keeps the
- * encoder-decoder keys/values).  Errors: SAN_ESTATE before san_encode. */
+ * encoder-decoder keys/values; sentences dropped by san_compact are back).
+ * Errors: SAN_ESTATE before san_encode. */
 SAN_API int san_rewind(san_ctx* ctx);
 
 /* One auto-regressive decoder step (Sec. 1: one target word at a time) for all
@@ -198,6 +199,30 @@ SAN_API int san_decode_n(san_ctx* ctx, int32_t n, const int32_t* tokens_dev, flo
  * san_decode_n) ends in eos_id.  Always 0 with eos_id < 0.  Synchronises the
  * context's stream.  count_out HOST.  Errors: SAN_EINVAL, SAN_ESTATE. */
 SAN_API int san_finished(san_ctx* ctx, int32_t* count_out);
+
+/* Per-sentence finished flags of the current batch (1 = finished in the sense of
+ * san_finished).  flags_out HOST int32 [current batch].  Synchronises the stream.
+ * Errors: SAN_EINVAL, SAN_ESTATE. */
+SAN_API int san_done_flags(san_ctx* ctx, int32_t* flags_out);
+
+/* Drop sentences from the running batch (decoding stops per sentence at its end
+ * symbol, Sec. 1; a finished sentence otherwise keeps costing a full share of
+ * every step).  keep HOST int32 [n_keep]: strictly increasing indices into the
+ * CURRENT batch of the sentences that stay.  Afterwards the batch has n_keep
+ * sentences; row i*beam + h of every later call is what row keep[i]*beam + h was,
+ * and the caller permutes its own per-row arrays (tokens, cumulative scores) the
+ * same way.  The state of the dropped sentences is discarded; the key/value
+ * caches are not moved (they keep the row stride of the encoded batch).
+ * san_rewind and san_encode restore / replace the full batch.  Synchronises the
+ * stream; allocates a staging buffer on first use.  n_keep == batch is a no-op.
+ * Errors: SAN_EINVAL (null, n_keep outside [1, batch], indices not increasing or
+ * out of range), SAN_ESTATE (before san_encode, use_cache = 0, profiling on). */
+SAN_API int san_compact(san_ctx* ctx, const int32_t* keep, int32_t n_keep);
+
+/* The sentences of the current batch as indices into the batch given to
+ * san_encode.  sentences_out HOST int32 [current batch] (may be null), n_out HOST.
+ * Errors: SAN_EINVAL, SAN_ESTATE. */
+SAN_API int san_active(san_ctx* ctx, int32_t* sentences_out, int32_t* n_out);
 
 /* ---- Learning a sharing policy (Sec. 3.3) ----
  * san_policy_accumulate: after a decode step of a context with cfg.debug = 1 (every

@@ -23,7 +23,8 @@ SAN_DBG_S_SELF, SAN_DBG_A_SELF, SAN_DBG_S_CTX, SAN_DBG_A_CTX, SAN_DBG_HIDDEN = r
 EXPORTS = ["san_weight_bytes", "san_init", "san_encode", "san_rewind", "san_decode_step", "san_topk",
            "san_beam_reorder", "san_debug_get", "san_step", "san_device_bytes", "san_last_launch_count",
            "san_last_error", "san_free", "san_profile", "san_profile_read",
-           "san_policy_accumulate", "san_policy_read", "san_policy_search", "san_decode_n", "san_stream_read", "san_finished"]
+           "san_policy_accumulate", "san_policy_read", "san_policy_search", "san_decode_n", "san_stream_read", "san_finished",
+           "san_done_flags", "san_compact", "san_active"]
 
 KINDS = ["misc", "proj", "attn_self", "attn_apply", "out", "ln", "attn_ctx", "attn_ctx_apply", "ffn", "logits",
          "topk", "reorder", "aan"]
@@ -83,6 +84,12 @@ def lib():
         l.san_stream_read.argtypes = [vp, vp, C.c_size_t]
         l.san_finished.restype = C.c_int
         l.san_finished.argtypes = [vp, C.POINTER(C.c_int32)]
+        l.san_done_flags.restype = C.c_int
+        l.san_done_flags.argtypes = [vp, C.POINTER(C.c_int32)]
+        l.san_compact.restype = C.c_int
+        l.san_compact.argtypes = [vp, C.POINTER(C.c_int32), i32]
+        l.san_active.restype = C.c_int
+        l.san_active.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         l.san_last_launch_count.restype = i32
         l.san_last_launch_count.argtypes = [vp]
         l.san_last_error.restype = C.c_char_p
@@ -189,6 +196,32 @@ class San:
 
     def rewind(self):
         self._check(self._l.san_rewind(self._h))
+        self._sync_batch()
+
+    def _sync_batch(self):
+        n = C.c_int32(0)
+        self._check(self._l.san_active(self._h, None, C.byref(n)))
+        self.batch = int(n.value)
+        self.rows = self.batch * self.cfg.beam
+
+    def done_flags(self):
+        """per-sentence finished flags of the current batch (numpy int32; synchronises the stream)"""
+        out = np.zeros(max(1, self.batch), dtype=np.int32)
+        self._check(self._l.san_done_flags(self._h, out.ctypes.data_as(C.POINTER(C.c_int32))))
+        return out[:self.batch]
+
+    def compact(self, keep):
+        """keep: increasing indices (into the current batch) of the sentences that stay"""
+        keep = np.ascontiguousarray(np.asarray(keep, dtype=np.int32))
+        self._check(self._l.san_compact(self._h, keep.ctypes.data_as(C.POINTER(C.c_int32)), len(keep)))
+        self._sync_batch()
+
+    def active(self):
+        """indices, into the encoded batch, of the sentences of the current batch"""
+        out = np.zeros(max(1, self.cfg.max_batch), dtype=np.int32)
+        n = C.c_int32(0)
+        self._check(self._l.san_active(self._h, out.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(n)))
+        return out[:int(n.value)].copy()
 
     def decode_step(self, tokens, logits):
         torch = self._torch

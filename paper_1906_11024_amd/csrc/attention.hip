@@ -70,8 +70,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnPara
     // row stride is done here, once per key, not once per load (K and V caches
     // have the same layout in this mode).
     const long long ld_cache = p.apply ? p.ldv : p.ldk;
+    const int slot_rows = p.slot_rows > 0 ? p.slot_rows : p.rows;
     for (int j = threadIdx.x; j < p.lmax; j += blockDim.x)
-      slot_off[j] = (long long)(j * p.rows + p.anc[(size_t)r * p.ld_anc + j]) * ld_cache;
+      slot_off[j] = (long long)(j * slot_rows + p.anc[(size_t)r * p.ld_anc + j]) * ld_cache;
     n = *p.t_dev + 1;
     n = min(n, p.lmax);
     qrow[0] = r;
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnPara
     // 8 apart where possible, so that they land on the same XCD and share its L2
     const int qb = rest / p.groups;   // query block inside the group
     const int grp = rest % p.groups;
-    slot_base = (long long)grp * p.slot_stride;
+    slot_base = (long long)(p.group_map ? p.group_map[grp] : grp) * p.slot_stride;
     const int nfull = p.len ? max(0, min(p.len[grp], p.lmax)) : p.n_fixed;
     n = 0;
 #pragma unroll

@@ -56,6 +56,8 @@ struct AttnParams {
   const int* len;                   // grouped, non-causal: keys per group (nullptr: n_fixed)
   int n_fixed;
   int self_mode, rows, groups, rpg, slot_stride, causal;
+  int slot_rows;                    // self mode: rows of one cache position (0: same as rows)
+  const int* group_map;             // grouped: memory of group g is slot group_map[g] (nullptr: g)
   int H, dh;
   int apply, emit, zero_tail;
   int lmax;                         // capacity of one score row (>= any n)
@@ -102,15 +104,19 @@ hipError_t launch_aan_post(int dtype, const float* z, const void* bg, const void
 // ---------------------------------------------------------------------- search
 // hist (optional): also append the picks to tok/par[step][batch*k], step =
 // *t_dev - 1 - *t0_dev (the decode step just finished, relative to the call's first)
+// row_map (optional, needs k == beam): the batch was compacted; row r of the current batch is row
+// row_map[r] of the caller's arrays, whose steps are ld entries apart; parents are translated too
 struct TopkHistory {
   int* tok; int* par;
   const int* t_dev; const int* t0_dev;
+  const int* row_map; int ld;
 };
-// done (optional, eos_id >= 0): int[batch + 1]; done[b] becomes 1 once every pick of sentence b is EOS,
-// done[batch] counts such sentences
+// done (optional, eos_id >= 0): int[batch]; done[b] becomes 1 once every pick of sentence b is EOS,
+// *done_count counts such sentences
 hipError_t launch_topk(const float* logits, const float* cum, const int* last_tok, int eos_id, int batch, int beam,
                        int vocab, int k, float* cand_lp, int* cand_idx, int* out_tok, int* out_parent,
-                       float* out_score, hipStream_t stream, const TopkHistory* hist = nullptr, int* done = nullptr);
+                       float* out_score, hipStream_t stream, const TopkHistory* hist = nullptr, int* done = nullptr,
+                       int* done_count = nullptr);
 // per sentence, in place: tab[r][j] = tab[parent[r]][j] for j < *t_dev
 hipError_t launch_reorder_table(int* tab, int ld, const int* parent, const int* t_dev, int batch, int beam,
                                 int max_t, hipStream_t stream);
@@ -131,6 +137,19 @@ struct JsParams {
 hipError_t launch_js_accumulate(const JsParams& p, double* acc, hipStream_t stream);
 // host: block sizes of the greedy search with threshold theta on a [L][L] JS matrix
 int policy_search(const double* js, int L, double theta, int32_t* pi, int32_t* n_blocks);
+
+// Dropping sentences from a running batch.  dst[(g*rpg + i)*w + c] = src[(keep[g]*rpg + i)*w + c] for
+// g < groups, i < rpg, c < w (4-byte words; dst and src must not overlap)
+hipError_t launch_gather_groups(void* dst, const void* src, const int* keep, int rpg, int groups, int w,
+                                hipStream_t stream);
+// *count = number of non-zero flags[0..n)
+hipError_t launch_count_flags(const int* flags, int n, int* count, hipStream_t stream);
+// tok[s][r] = eos, par[s][r] = r for the rows r of every sentence b with 0 <= from[b] and the steps
+// from[b] <= s < steps ([step][rows] arrays): a dropped sentence keeps extending with EOS in place
+hipError_t launch_fill_finished(int* tok, int* par, const int* from, int batch, int beam, int steps, int eos,
+                                hipStream_t stream);
+// dst[map[r]] = src[r] for r < n (4-byte words)
+hipError_t launch_scatter_words(void* dst, const void* src, const int* map, int n, hipStream_t stream);
 
 // reads `bytes` (multiple of 16) of device memory once and discards them; sink: 4 writable device bytes
 hipError_t launch_stream_read(const void* src, size_t bytes, unsigned* sink, hipStream_t stream);

@@ -2,6 +2,8 @@
 // residual + LayerNorm, the average-attention (AAN) pre/post stages, beam-state
 // reordering and small utilities.  All are bandwidth-trivial; they exist to keep
 // the number of passes over the [rows][d] activations small.
+#include <algorithm>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -403,6 +405,66 @@ hipError_t launch_reorder_rows(float* st, size_t layer_stride, const int* parent
     hipLaunchKernelGGL((reorder_rows_kernel<16, float4>), g4, dim3(64), 0, stream, st, layer_stride, parent, batch, beam, d);
   else
     hipLaunchKernelGGL((reorder_rows_kernel<32, float>), g1, dim3(128), 0, stream, st, layer_stride, parent, batch, beam, d);
+  return hipGetLastError();
+}
+
+// ---- dropping sentences from a running batch (rare, tiny: plain word copies)
+__global__ __launch_bounds__(256) void gather_groups_kernel(int* __restrict__ dst, const int* __restrict__ src,
+                                                            const int* __restrict__ keep, int rpg, int groups, int w) {
+  const size_t per = (size_t)rpg * w, total = (size_t)groups * per;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const size_t g = i / per, rest = i - g * per;
+    dst[i] = src[(size_t)keep[g] * per + rest];
+  }
+}
+hipError_t launch_gather_groups(void* dst, const void* src, const int* keep, int rpg, int groups, int w,
+                                hipStream_t stream) {
+  const size_t total = (size_t)groups * rpg * w;
+  if (total == 0) return hipSuccess;
+  const unsigned blocks = (unsigned)std::min<size_t>((total + 255) / 256, 4096);
+  hipLaunchKernelGGL(gather_groups_kernel, dim3(blocks), dim3(256), 0, stream, reinterpret_cast<int*>(dst),
+                     reinterpret_cast<const int*>(src), keep, rpg, groups, w);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(64) void count_flags_kernel(const int* flags, int n, int* count) {
+  int s = 0;
+  for (int i = threadIdx.x; i < n; i += 64) s += flags[i] != 0;
+  s = (int)wave_sum((float)s);   // exact: n is far below 2^24
+  if (threadIdx.x == 0) *count = s;
+}
+hipError_t launch_count_flags(const int* flags, int n, int* count, hipStream_t stream) {
+  hipLaunchKernelGGL(count_flags_kernel, dim3(1), dim3(64), 0, stream, flags, n, count);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void fill_finished_kernel(int* tok, int* par, const int* from, int batch, int beam,
+                                                            int steps, int eos) {
+  const int rows = batch * beam;
+  const size_t total = (size_t)steps * rows;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int s = (int)(i / rows), r = (int)(i - (size_t)s * rows);
+    const int f = from[r / beam];
+    if (f >= 0 && s >= f) { tok[i] = eos; par[i] = r; }
+  }
+}
+hipError_t launch_fill_finished(int* tok, int* par, const int* from, int batch, int beam, int steps, int eos,
+                                hipStream_t stream) {
+  const size_t total = (size_t)steps * batch * beam;
+  if (total == 0) return hipSuccess;
+  const unsigned blocks = (unsigned)std::min<size_t>((total + 255) / 256, 4096);
+  hipLaunchKernelGGL(fill_finished_kernel, dim3(blocks), dim3(256), 0, stream, tok, par, from, batch, beam, steps, eos);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void scatter_words_kernel(int* dst, const int* src, const int* map, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[map[i]] = src[i];
+}
+hipError_t launch_scatter_words(void* dst, const void* src, const int* map, int n, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(scatter_words_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, reinterpret_cast<int*>(dst),
+                     reinterpret_cast<const int*>(src), map, n);
   return hipGetLastError();
 }
 

@@ -4,6 +4,7 @@
 // the caller's stream.  No arithmetic of the method happens on the host.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -86,7 +87,16 @@ struct san_ctx {
   int graph_rows = 0;
   int *t_dev = nullptr, *anc = nullptr, *hist = nullptr, *last_tok = nullptr, *src_len = nullptr;
   int* done_dev = nullptr;     // [max_batch] finished flags, then the count of finished sentences
-  int* done_host = nullptr;    // pinned, one int
+  int* done_host = nullptr;    // pinned, 2 * max_batch + 16 ints (count or flags read back; keep list going up)
+  // dropping finished sentences (san_compact): the caches keep the row stride of the encoded batch
+  int batch_enc = 0;           // sentences given to san_encode
+  int* src_len0 = nullptr;     // their lengths (src_len holds those of the current batch)
+  int* group_map = nullptr;    // [max_batch] encode-time index of each current sentence
+  int* iota_dev = nullptr;     // 0, 1, 2, ... [max(rows_max, max_batch)]
+  int* keep_dev = nullptr;     // [max_batch]
+  void* cmp_tmp = nullptr;     // gather staging
+  size_t cmp_tmp_bytes = 0;
+  std::vector<int> active;     // host copy of group_map
   float* cand_lp = nullptr;
   int* cand_idx = nullptr;
   // state
@@ -482,7 +492,16 @@ static int build_ctx(san_ctx* c, const Blob& bl, const void* blob, const std::ve
     TRY(dalloc(c, (void**)&c->src_len, (size_t)cfg->max_batch * 4, false));
     TRY(dalloc(c, (void**)&c->done_dev, ((size_t)cfg->max_batch + 1) * 4, false));
     HIP_TRY(c, hipMemset(c->done_dev, 0, ((size_t)cfg->max_batch + 1) * 4));
-    HIP_TRY(c, hipHostMalloc((void**)&c->done_host, 64, hipHostMallocDefault));
+    HIP_TRY(c, hipHostMalloc((void**)&c->done_host, ((size_t)2 * cfg->max_batch + 16) * 4, hipHostMallocDefault));
+    TRY(dalloc(c, (void**)&c->src_len0, (size_t)cfg->max_batch * 4, false));
+    TRY(dalloc(c, (void**)&c->group_map, (size_t)cfg->max_batch * 4, false));
+    TRY(dalloc(c, (void**)&c->keep_dev, (size_t)cfg->max_batch * 4, false));
+    {
+      std::vector<int> iota((size_t)c->rows_max);
+      for (size_t i = 0; i < iota.size(); ++i) iota[i] = (int)i;
+      TRY(dalloc(c, (void**)&c->iota_dev, iota.size() * 4, false));
+      HIP_TRY(c, hipMemcpy(c->iota_dev, iota.data(), iota.size() * 4, hipMemcpyHostToDevice));
+    }
     TRY(dalloc(c, (void**)&c->cand_lp, (size_t)c->rows_max * 32 * 4, false));
     TRY(dalloc(c, (void**)&c->cand_idx, (size_t)c->rows_max * 32 * 4, false));
     HIP_TRY(c, hipMemset(c->t_dev, 0, 256));
@@ -566,6 +585,12 @@ int san_encode(san_ctx* c, const int32_t* src_ids_dev, const int32_t* src_len_de
   int rc;
   c->kind = SAN_K_MISC;
   HIP_TRY(c, hipMemcpyAsync(c->src_len, src_len_dev, (size_t)batch * 4, hipMemcpyDeviceToDevice, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(c->src_len0, src_len_dev, (size_t)batch * 4, hipMemcpyDeviceToDevice, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(c->group_map, c->iota_dev, (size_t)batch * 4, hipMemcpyDeviceToDevice, c->stream));
+  c->batch = batch;   // the encoder below runs on the whole batch
+  c->batch_enc = batch;
+  c->active.resize(batch);
+  for (int i = 0; i < batch; ++i) c->active[i] = i;
   LAUNCH(c, launch_embed(c->dt, src_ids_dev, max_src, max_src, c->src_emb, c->pe, nullptr, c->x, Ms, d, c->V,
                          (float)std::sqrt((double)d), nullptr, nullptr, 0, c->stream));
   for (size_t li = 0; li < c->enc.size(); ++li) {
@@ -609,6 +634,14 @@ int san_rewind(san_ctx* c) {
   if (c->t < 0) return fail(c, SAN_ESTATE, "san_rewind before san_encode");
   HIP_TRY(c, hipMemsetAsync(c->t_dev, 0, 4, c->stream));
   HIP_TRY(c, hipMemsetAsync(c->done_dev, 0, ((size_t)c->cfg.max_batch + 1) * 4, c->stream));
+  if (c->batch != c->batch_enc) {   // sentences dropped by san_compact come back
+    HIP_TRY(c, hipMemcpyAsync(c->src_len, c->src_len0, (size_t)c->batch_enc * 4, hipMemcpyDeviceToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->group_map, c->iota_dev, (size_t)c->batch_enc * 4, hipMemcpyDeviceToDevice, c->stream));
+    c->batch = c->batch_enc;
+    c->active.resize(c->batch);
+    for (int i = 0; i < c->batch; ++i) c->active[i] = i;
+    c->graph_rows = 0;
+  }
   c->t = 0;
   return SAN_OK;
 }
@@ -618,7 +651,9 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
   const float scale = 1.0f / std::sqrt((float)c->dh);
   const bool aan = c->cfg.self_kind == SAN_SELF_AAN, shareS = c->cfg.encdec_share == SAN_SHARE_S;
   const bool dbg = c->cfg.debug != 0;
-  const long long slab = (long long)B * d;   // cache elements per position
+  const int cache_rows = c->batch_enc * c->cfg.beam;   // the caches keep the encoded batch's row stride
+  const long long slab = (long long)cache_rows * d;    // cache elements per position
+  const int* group_map = c->batch != c->batch_enc ? c->group_map : nullptr;
   int rc;
   c->kind = SAN_K_MISC;
   LAUNCH(c, launch_embed(c->dt, tokens, 1, 1, c->tgt_emb, c->pe, c->t_dev, c->x, B, d, c->V,
@@ -658,7 +693,7 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
       a.S_buf = c->dec[L.self_head].S_self; a.ldS = T;
       a.out = c->ab; a.ldo = d;
       a.anc = c->anc; a.ld_anc = T; a.t_dev = c->t_dev;
-      a.self_mode = 1; a.rows = B; a.H = c->H; a.dh = c->dh; a.lmax = T; a.scale = scale;
+      a.self_mode = 1; a.rows = B; a.slot_rows = cache_rows; a.H = c->H; a.dh = c->dh; a.lmax = T; a.scale = scale;
       a.apply = head ? 0 : 1;
       a.emit = head && (has_followers || dbg);
       c->kind = head ? SAN_K_ATTN_SELF : SAN_K_ATTN_APPLY;
@@ -696,6 +731,7 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
       a.S_buf = Hd.S_ctx; a.ldS = c->cfg.max_src_len;
       a.ldo = d;
       a.len = c->src_len; a.rows = B; a.groups = c->batch; a.rpg = c->cfg.beam; a.slot_stride = c->max_src;
+      a.group_map = group_map;
       a.H = c->H; a.dh = c->dh; a.lmax = c->max_src; a.scale = scale;
       c->kind = chead ? SAN_K_ATTN_CTX : SAN_K_ATTN_CTX_APPLY;
       LAUNCH(c, launch_attention(c->dt, a, c->stream));
@@ -830,7 +866,7 @@ int san_topk(san_ctx* c, const float* logits_dev, const float* cum_score_dev, in
   const long pm = prof_mark(c);
   HIP_TRY(c, launch_topk(logits_dev, cum_score_dev, c->last_tok, c->cfg.eos_id, c->batch, c->cfg.beam, c->V, k,
                          c->cand_lp, c->cand_idx, out_token_dev, out_parent_dev, out_score_dev, c->stream, nullptr,
-                         k == c->cfg.beam ? c->done_dev : nullptr));
+                         k == c->cfg.beam ? c->done_dev : nullptr, c->done_dev + c->cfg.max_batch));
   prof_close(c, pm);
   return prof_flush(c);
 }
@@ -919,6 +955,74 @@ int san_finished(san_ctx* c, int32_t* count_out) {
   return SAN_OK;
 }
 
+int san_done_flags(san_ctx* c, int32_t* flags_out) {
+  if (!c || !flags_out) return fail(c, SAN_EINVAL, "san_done_flags: null argument");
+  if (c->t < 0) return fail(c, SAN_ESTATE, "san_done_flags before san_encode");
+  HIP_TRY(c, hipMemcpyAsync(c->done_host, c->done_dev, (size_t)c->batch * 4, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (int i = 0; i < c->batch; ++i) flags_out[i] = c->done_host[i];
+  return SAN_OK;
+}
+
+int san_active(san_ctx* c, int32_t* sentences_out, int32_t* n_out) {
+  if (!c || !n_out) return fail(c, SAN_EINVAL, "san_active: null argument");
+  if (c->t < 0) return fail(c, SAN_ESTATE, "san_active before san_encode");
+  *n_out = c->batch;
+  if (sentences_out)
+    for (int i = 0; i < c->batch; ++i) sentences_out[i] = c->active[i];
+  return SAN_OK;
+}
+
+int san_compact(san_ctx* c, const int32_t* keep, int32_t n_keep) {
+  if (!c || !keep) return fail(c, SAN_EINVAL, "san_compact: null argument");
+  if (c->t < 0) return fail(c, SAN_ESTATE, "san_compact before san_encode");
+  if (!c->cfg.use_cache) return fail(c, SAN_ESTATE, "san_compact needs use_cache = 1");
+  if (c->prof_on) return fail(c, SAN_ESTATE, "san_compact: switch san_profile off first");
+  if (n_keep < 1 || n_keep > c->batch) return fail(c, SAN_EINVAL, "san_compact: n_keep must be in [1, batch]");
+  for (int i = 0; i < n_keep; ++i)
+    if (keep[i] < 0 || keep[i] >= c->batch || (i > 0 && keep[i] <= keep[i - 1]))
+      return fail(c, SAN_EINVAL, "san_compact: keep must be strictly increasing sentence indices of the current batch");
+  if (n_keep == c->batch) return SAN_OK;
+  const int beam = c->cfg.beam, T = c->cfg.max_tgt_len, nrows = n_keep * beam;
+  const bool aan = c->cfg.self_kind == SAN_SELF_AAN;
+  size_t need = (size_t)nrows * T * 4;
+  if (aan && (size_t)nrows * c->d * 4 > need) need = (size_t)nrows * c->d * 4;
+  if (need > c->cmp_tmp_bytes) {
+    // sized once for the largest batch (the old buffer, if any, is released with the context)
+    const size_t full = std::max((size_t)c->rows_max * T * 4, aan ? (size_t)c->rows_max * c->d * 4 : (size_t)0);
+    int rc = dalloc(c, &c->cmp_tmp, full, false);
+    if (rc) return rc;
+    c->cmp_tmp_bytes = full;
+  }
+  // the list goes up through pinned memory; the stream is drained first so that an
+  // earlier list is no longer being read
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  int* pin = c->done_host + c->cfg.max_batch + 8;
+  for (int i = 0; i < n_keep; ++i) pin[i] = keep[i];
+  HIP_TRY(c, hipMemcpyAsync(c->keep_dev, pin, (size_t)n_keep * 4, hipMemcpyHostToDevice, c->stream));
+  // every per-row / per-sentence array: gather into the staging buffer, copy back
+  auto move = [&](void* arr, int rpg, int w) -> int {
+    HIP_TRY(c, launch_gather_groups(c->cmp_tmp, arr, c->keep_dev, rpg, n_keep, w, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(arr, c->cmp_tmp, (size_t)n_keep * rpg * w * 4, hipMemcpyDeviceToDevice, c->stream));
+    return SAN_OK;
+  };
+  int rc;
+  if (!aan && (rc = move(c->anc, beam, T))) return rc;
+  if ((rc = move(c->last_tok, beam, 1))) return rc;
+  if ((rc = move(c->src_len, 1, 1))) return rc;
+  if ((rc = move(c->group_map, 1, 1))) return rc;
+  if ((rc = move(c->done_dev, 1, 1))) return rc;
+  if (aan)
+    for (size_t l = 0; l < c->dec.size(); ++l)
+      if ((rc = move(c->dec[l].aan_sum, beam, c->d))) return rc;
+  HIP_TRY(c, launch_count_flags(c->done_dev, n_keep, c->done_dev + c->cfg.max_batch, c->stream));
+  for (int i = 0; i < n_keep; ++i) c->active[i] = c->active[keep[i]];
+  c->active.resize(n_keep);
+  c->batch = n_keep;
+  c->graph_rows = 0;   // a captured step graph is tied to the batch shape
+  return SAN_OK;
+}
+
 // One beam-search step on the ping-pong buffers: parity p reads set p, writes set p^1.
 static int loop_step(san_ctx* c, int p, int32_t* out_tokens, int32_t* out_parents, float* logits) {
   int rc = san_decode_step(c, c->pp_tok[p], logits);
@@ -926,7 +1030,7 @@ static int loop_step(san_ctx* c, int p, int32_t* out_tokens, int32_t* out_parent
   TopkHistory h{out_tokens, out_parents, c->t_dev, c->t0_dev};
   HIP_TRY(c, launch_topk(logits, c->pp_cum[p], c->last_tok, c->cfg.eos_id, c->batch, c->cfg.beam, c->V, c->cfg.beam,
                          c->cand_lp, c->cand_idx, c->pp_tok[p ^ 1], c->pp_par, c->pp_cum[p ^ 1], c->stream, &h,
-                         c->done_dev));
+                         c->done_dev, c->done_dev + c->cfg.max_batch));
   return san_beam_reorder(c, c->pp_par);
 }
 

@@ -268,11 +268,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_row_kernel(const float* log
 // One wave per sentence: merge the beam*k candidates, keep the k best.
 __global__ __launch_bounds__(64) void topk_merge_kernel(const float* cand_lp, const int* cand_idx, const float* cum,
                                                         int beam, int vocab, int k, int* out_tok, int* out_parent,
-                                                        float* out_score, TopkHistory hist, int eos_id, int* done) {
+                                                        float* out_score, TopkHistory hist, int eos_id, int* done,
+                                                        int* done_count) {
   const int b = blockIdx.x, lane = threadIdx.x;
   // multi-step decoding: this step's picks are also appended to the caller's
   // [step][rows] arrays; the step index comes from the device-side counters
-  const long long hoff = hist.tok ? (long long)(*hist.t_dev - 1 - *hist.t0_dev) * gridDim.x * k : 0;
+  const long long hoff =
+      hist.tok ? (long long)(*hist.t_dev - 1 - *hist.t0_dev) * (hist.row_map ? hist.ld : (int)gridDim.x * k) : 0;
   const Cand best = wave_topk(
       [&](int q) {
         const int bi = q / k;
@@ -290,8 +292,10 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(const float* cand_lp, co
     out_parent[(size_t)b * k + lane] = pr;
     out_score[(size_t)b * k + lane] = ok ? best.v : -INFINITY;
     if (hist.tok) {
-      hist.tok[hoff + (size_t)b * k + lane] = tk;
-      hist.par[hoff + (size_t)b * k + lane] = pr;
+      const int o = b * k + lane;
+      const int oo = hist.row_map ? hist.row_map[o] : o;
+      hist.tok[hoff + oo] = tk;
+      hist.par[hoff + oo] = hist.row_map ? hist.row_map[pr] : pr;
     }
   }
   if (done && eos_id >= 0) {
@@ -300,14 +304,14 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(const float* cand_lp, co
     const bool open = lane < k && (best.i == kNone || best.i % vocab != eos_id);
     if (__ballot(open) == 0 && lane == 0 && done[b] == 0) {
       done[b] = 1;
-      atomicAdd(&done[gridDim.x], 1);
+      atomicAdd(done_count, 1);
     }
   }
 }
 
 hipError_t launch_topk(const float* logits, const float* cum, const int* last_tok, int eos_id, int batch, int beam,
                        int vocab, int k, float* cand_lp, int* cand_idx, int* out_tok, int* out_parent,
-                       float* out_score, hipStream_t stream, const TopkHistory* hist, int* done) {
+                       float* out_score, hipStream_t stream, const TopkHistory* hist, int* done, int* done_count) {
   const int rows = batch * beam;
   if (rows <= 0) return hipSuccess;
   if (vocab <= kTopkVpt * kTopkThreads)
@@ -321,7 +325,7 @@ hipError_t launch_topk(const float* logits, const float* cum, const int* last_to
   TopkHistory h{};
   if (hist) h = *hist;
   hipLaunchKernelGGL(topk_merge_kernel, dim3(batch), dim3(64), 0, stream, cand_lp, cand_idx, cum, beam, vocab, k,
-                     out_tok, out_parent, out_score, h, eos_id, done);
+                     out_tok, out_parent, out_score, h, eos_id, done_count ? done : nullptr, done_count);
   return hipGetLastError();
 }
 

@@ -117,6 +117,29 @@ class Lockstep:
         return lg, lo
 
 
+def lockstep_compact(ls, keep):
+    """Drop sentences from the GPU batch of a Lockstep run: `keep` = increasing indices into
+    the current GPU batch; every sentence the oracle decodes must be among them (the oracle
+    decodes its sentences independently of the others and needs no change)."""
+    torch = ls.torch
+    keep = np.asarray(keep, dtype=np.int64)
+    assert set(ls.subset.tolist()) <= set(keep.tolist())
+    beam = ls.beam
+    rows_keep = (keep[:, None] * beam + np.arange(beam)[None, :]).reshape(-1)
+    idx = torch.from_numpy(rows_keep).to("cuda")
+    ls.gpu.compact(keep)
+    ls.tokens = ls.tokens[idx].contiguous()
+    ls.cum = ls.cum[idx].contiguous()
+    ls.batch = len(keep)
+    ls.B = ls.batch * beam
+    ls.subset = np.searchsorted(keep, ls.subset)
+    ls.rows = (ls.subset[:, None] * beam + np.arange(beam)[None, :]).reshape(-1)
+    ls.logits = ls.logits[:ls.B].contiguous()
+    ls.o_tok = torch.empty((ls.batch, beam), dtype=torch.int32, device="cuda")
+    ls.o_par = torch.empty((ls.batch, beam), dtype=torch.int32, device="cuda")
+    ls.o_sc = torch.empty((ls.batch, beam), dtype=torch.float32, device="cuda")
+
+
 def gpu_free_run(gpu, src, lens, beam, steps, bos_id=wl.BOS_ID, keep_logits=False):
     """GPU-only search; returns per-step tokens / parents / scores (numpy)."""
     import torch

@@ -487,7 +487,7 @@ def test_decode_n_stops_when_every_sentence_is_finished(use_graph):
     src, lens = wl.make_source(mid_cfg(batch=4), 4)
     src = np.minimum(src, 7)
     beam, B, V, T = 3, 12, 8, 64
-    ref_gpu = hz.make_gpu(cfg, w, eos_id=wl.EOS_ID)
+    ref_gpu = hz.make_gpu(cfg, w, eos_id=wl.EOS_ID, max_batch=6)   # a capacity above the batch
     # per-call loop, reading the finished count after every step
     ref_gpu.encode(torch.from_numpy(src).cuda(), torch.from_numpy(lens).cuda())
     tokens = torch.full((B,), wl.BOS_ID, dtype=torch.int32, device="cuda")
@@ -536,6 +536,94 @@ def test_decode_n_stops_when_every_sentence_is_finished(use_graph):
             assert (got[expect:] == -7).all()           # rows past the exit are not written
             assert np.array_equal(cum.cpu().numpy(), ref_sc[expect - 1])
         gpu.close()
+
+
+# ------------------------------------------------------ dropping sentences from a running batch
+@pytest.mark.parametrize("kind,share", [("dot", "A"), ("dot", "S"), ("aan", "A")])
+def test_compact_keeps_the_remaining_sentences_exact(kind, share):
+    """san_compact drops sentences mid-decode; the ones that stay go on exactly as the
+    oracle decodes them (sentences never interact), through two compactions; san_rewind
+    brings the whole batch back."""
+    cfg = mid_cfg(steps=20, self_kind=kind)
+    if kind == "aan":
+        cfg["self_pi"] = [1] * cfg["n_dec"]
+    w = wl.make_weights(cfg, seed=31, sharp=4.0)
+    src, lens = ragged(cfg, 31)
+    gpu = hz.make_gpu(cfg, w, share=share, max_batch=7)
+    orc = hz.make_oracle(cfg, w, share=share)
+    ls = hz.Lockstep(gpu, orc, src, lens, cfg["beam"], subset=[1, 3])
+    first_logits = None
+    for t in range(20):
+        if t == 6:
+            hz.lockstep_compact(ls, [0, 1, 3, 4])
+            assert gpu.active().tolist() == [0, 1, 3, 4] and gpu.batch == 4
+        if t == 11:
+            hz.lockstep_compact(ls, [1, 2])
+            assert gpu.active().tolist() == [1, 3] and gpu.rows == 2 * cfg["beam"]
+        lg, _ = ls.step(tie_tol=5e-4)
+        if t == 0:
+            first_logits = lg.copy()
+    assert max(ls.log["logit_err"]) <= F32_TOL
+    assert sum(ls.log["exact"]) >= 0.8 * 20
+    gpu.rewind()
+    assert gpu.active().tolist() == [0, 1, 2, 3, 4] and gpu.batch == 5
+    B = 5 * cfg["beam"]
+    logits = torch.empty((B, cfg["V"]), dtype=torch.float32, device="cuda")
+    gpu.decode_step(torch.full((B,), wl.BOS_ID, dtype=torch.int32, device="cuda"), logits)
+    rows = torch.from_numpy(np.array([1, 3])[:, None] * cfg["beam"] + np.arange(cfg["beam"])[None, :]).reshape(-1).cuda()
+    assert np.array_equal(logits[rows].cpu().numpy(), first_logits)
+    gpu.close()
+
+
+def test_compact_argument_errors_and_flags():
+    cfg = mid_cfg(steps=64, V=8, batch=4, beam=3)
+    w = wl.make_weights(cfg, seed=4)
+    src, lens = wl.make_source(mid_cfg(batch=4), 4)
+    src = np.minimum(src, 7)
+    gpu = hz.make_gpu(cfg, w, eos_id=wl.EOS_ID, max_batch=6)     # max_batch above the batch on purpose
+    with pytest.raises(sb.SanError) as e:
+        gpu.compact([0])
+    assert e.value.code == sb.SAN_ESTATE
+    gpu.encode(torch.from_numpy(src).cuda(), torch.from_numpy(lens).cuda())
+    for bad in ([], [0, 0], [1, 0], [0, 4], [-1, 2], [0, 1, 2, 3, 3]):
+        with pytest.raises(sb.SanError) as e:
+            gpu.compact(bad)
+        assert e.value.code == sb.SAN_EINVAL, bad
+    gpu.compact([0, 1, 2, 3])                                    # everything stays: nothing happens
+    assert gpu.batch == 4
+    # finished flags against their definition, also after a compaction
+    beam, B, V = 3, 12, 8
+    tokens = torch.full((B,), wl.BOS_ID, dtype=torch.int32, device="cuda")
+    cum0 = np.full(B, -np.inf, dtype=np.float32)
+    cum0[0::beam] = 0.0
+    cum = torch.from_numpy(cum0).cuda()
+    logits = torch.empty((B, V), dtype=torch.float32, device="cuda")
+    keep_all = np.arange(4)
+    seen_done = False
+    for t in range(64):
+        nb = gpu.batch
+        o_tok = torch.empty((nb, beam), dtype=torch.int32, device="cuda")
+        o_par = torch.empty((nb, beam), dtype=torch.int32, device="cuda")
+        o_sc = torch.empty((nb, beam), dtype=torch.float32, device="cuda")
+        gpu.decode_step(tokens, logits)
+        gpu.topk(logits, cum, beam, o_tok, o_par, o_sc)
+        gpu.beam_reorder(o_par.reshape(-1))
+        tokens, cum = o_tok.reshape(-1).clone(), o_sc.reshape(-1).clone()
+        flags = (o_tok.cpu().numpy() == wl.EOS_ID).all(axis=1).astype(np.int32)
+        assert np.array_equal(gpu.done_flags(), flags), t
+        assert gpu.finished() == int(flags.sum())
+        if flags.all():
+            break
+        if flags.any():
+            seen_done = True
+            keep = np.nonzero(flags == 0)[0]
+            keep_all = keep_all[keep]
+            gpu.compact(keep)
+            rows = torch.from_numpy((keep[:, None] * beam + np.arange(beam)[None, :]).reshape(-1)).cuda()
+            tokens, cum = tokens[rows].contiguous(), cum[rows].contiguous()
+            assert gpu.finished() == 0 and gpu.active().tolist() == keep_all.tolist()
+    assert seen_done, "pick another seed: no sentence finished before the others"
+    gpu.close()
 
 
 # ------------------------------------------------------ head widths, extreme shapes
