@@ -103,6 +103,51 @@ class Runner:
         return time.perf_counter() - t0
 
 
+def ragged_finish(torch, gpu, cfg, src, lens, compact, reps=3):
+    """Wall time of one decode in which sentence b is taken to end after
+    T/2 + b*T/(2*batch) steps (a mix of lengths; the synthetic weights never emit the
+    end symbol themselves).  compact: at every 8th step the sentences past their end
+    leave the batch (san_compact); otherwise they ride along to the last step, as in a
+    fixed batch.  Returns (seconds per decode, useful row-steps per decode)."""
+    import numpy as np
+    batch, beam, T, V = cfg["batch"], cfg["beam"], cfg["steps"], cfg["V"]
+    B = batch * beam
+    end = T // 2 + (np.arange(batch) * (T - T // 2)) // batch + 1          # steps sentence b needs
+    src_d, len_d = torch.from_numpy(src).cuda(), torch.from_numpy(lens).cuda()
+    logits = torch.empty((B, V), dtype=torch.float32, device="cuda")
+    bos = torch.full((B,), 1, dtype=torch.int32, device="cuda")
+    cum0 = torch.full((B,), float("-inf"), dtype=torch.float32, device="cuda")
+    cum0[0::beam] = 0.0
+    gpu.encode(src_d, len_d)
+    times = []
+    for rep in range(reps + 1):
+        gpu.rewind()
+        alive = np.arange(batch)
+        tokens, cum = bos, cum0
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(T):
+            if compact and s and s % 8 == 0:
+                keep = np.nonzero(end[alive] > s)[0]
+                if len(keep) < len(alive):
+                    gpu.compact(keep)
+                    rows = torch.from_numpy((keep[:, None] * beam + np.arange(beam)[None, :]).reshape(-1)).cuda()
+                    tokens, cum = tokens[rows].contiguous(), cum[rows].contiguous()
+                    alive = alive[keep]
+            nb = len(alive)
+            o_tok = torch.empty((nb, beam), dtype=torch.int32, device="cuda")
+            o_par = torch.empty((nb, beam), dtype=torch.int32, device="cuda")
+            o_sc = torch.empty((nb, beam), dtype=torch.float32, device="cuda")
+            gpu.decode_step(tokens, logits)
+            gpu.topk(logits, cum, beam, o_tok, o_par, o_sc)
+            gpu.beam_reorder(o_par.view(-1))
+            tokens, cum = o_tok.view(-1), o_sc.view(-1)
+        torch.cuda.synchronize()
+        if rep:
+            times.append(time.perf_counter() - t0)
+    return float(np.median(times)), int(end.sum()) * beam
+
+
 def attention_bytes(cfg, esz, heads_self, followers_self, heads_ctx, s_followers_ctx, mean_src):
     """Algorithmic bytes of the attention kernels, summed over one decode of T
     steps: a block head streams K and V of the n cached positions of every row, a
@@ -300,6 +345,16 @@ def main():
                 compare[name] = {"tokens_per_s": B * 4 * T / w, "ms_per_step": w / (4 * T) * 1e3, "steps": 4 * T}
                 g.close()
                 del r
+        # sentences of different lengths: finished ones leave the batch (san_compact) or ride along
+        rf = {}
+        for name, cmpct in (("fixed_batch", False), ("compacting", True)):
+            g = make(cfg["self_pi"], cfg["encdec_pi"])
+            w, useful = ragged_finish(torch, g, cfg, src, lens, cmpct)
+            rf[name] = {"ms_per_decode": w * 1e3, "useful_tokens_per_s": useful / w}
+            g.close()
+        rf["speedup"] = rf["fixed_batch"]["ms_per_decode"] / rf["compacting"]["ms_per_decode"]
+        rf["schedule"] = "sentence b ends after T/2 + b*T/(2*batch) steps; the batch is compacted every 8 steps"
+        compare["ragged_finish"] = rf
         compare["san_cached"] = {"tokens_per_s": tok_per_s, "ms_per_step": ms_per_step}
         compare["speedup_san_vs_unshared_cached"] = tok_per_s / compare["unshared_cached"]["tokens_per_s"]
         if "unshared_no_cache" in compare:

@@ -185,14 +185,26 @@ SAN_API int san_debug_get(san_ctx* ctx, int32_t what, int32_t layer, void* dst_d
  *   out_tokens_dev  DEVICE int32 [n][rows]  token chosen for every row at every step
  *   out_parents_dev DEVICE int32 [n][rows]  parent row of every row at every step
  *   logits_work_dev DEVICE fp32  [rows][vocab] scratch, 16-byte aligned
- * use_graph != 0: pairs of steps are replayed from a captured HIP graph (needs a
- * stream other than the NULL stream and use_cache = 1; the graph is re-captured
- * when the output/scratch pointers or the batch change).  Allocates its small
- * ping-pong buffers on first use.
+ * flags (SAN_LOOP_*, or-ed):
+ *   SAN_LOOP_GRAPH: pairs of steps are replayed from a captured HIP graph (needs a
+ *     stream other than the NULL stream and use_cache = 1; the graph is
+ *     re-captured when the output/scratch pointers or the batch change).
+ *   SAN_LOOP_COMPACT (needs use_cache = 1; no effect with eos_id < 0): at those
+ *     8-step checks, once at least a quarter of the batch is finished and 16 or
+ *     more steps remain, the finished sentences leave the batch (san_compact) and
+ *     the remaining steps run on the smaller batch.  The caller's arrays keep the
+ *     numbering of the batch at entry: in out_* a sentence that left keeps
+ *     extending with EOS in place (token eos_id, parent = the row itself, as it
+ *     would have), cum_io_dev holds its final scores.  Tokens are the same as
+ *     without the flag except where two candidates' scores are within rounding
+ *     (a smaller batch may run other GEMM tiles).  On return the context's batch
+ *     is the sentences still unfinished (san_active); san_rewind restores it.
+ * Allocates its small ping-pong buffers on first use.
  * Errors: SAN_ESTATE, SAN_ECAPACITY (step + n > max_tgt_len), SAN_EINVAL. */
+enum { SAN_LOOP_GRAPH = 1, SAN_LOOP_COMPACT = 2 };
 SAN_API int san_decode_n(san_ctx* ctx, int32_t n, const int32_t* tokens_dev, float* cum_io_dev,
                          int32_t* out_tokens_dev, int32_t* out_parents_dev, float* logits_work_dev,
-                         int32_t use_graph);
+                         int32_t flags);
 
 /* Number of sentences of the current batch that are finished: every hypothesis
  * kept by the last beam step (san_topk with k == beam, or a step of

@@ -84,7 +84,10 @@ struct san_ctx {
   int* t0_dev = nullptr;
   hipGraphExec_t graph2 = nullptr;
   const void* graph_key[3] = {nullptr, nullptr, nullptr};
-  int graph_rows = 0;
+  int graph_rows = 0, graph_entry_rows = 0;
+  int* row_map = nullptr;      // san_decode_n after a compaction: current row -> row of the caller's arrays
+  float* cum_final = nullptr;  // scores in the caller's numbering
+  int* drop_dev = nullptr;     // [max_batch] step at which each of the caller's sentences left the batch
   int *t_dev = nullptr, *anc = nullptr, *hist = nullptr, *last_tok = nullptr, *src_len = nullptr;
   int* done_dev = nullptr;     // [max_batch] finished flags, then the count of finished sentences
   int* done_host = nullptr;    // pinned, 2 * max_batch + 16 ints (count or flags read back; keep list going up)
@@ -1024,10 +1027,12 @@ int san_compact(san_ctx* c, const int32_t* keep, int32_t n_keep) {
 }
 
 // One beam-search step on the ping-pong buffers: parity p reads set p, writes set p^1.
-static int loop_step(san_ctx* c, int p, int32_t* out_tokens, int32_t* out_parents, float* logits) {
+// entry_rows > 0: the batch was compacted during this call; the history goes to the rows
+// the caller knows (row_map), entry_rows apart per step.
+static int loop_step(san_ctx* c, int p, int32_t* out_tokens, int32_t* out_parents, float* logits, int entry_rows) {
   int rc = san_decode_step(c, c->pp_tok[p], logits);
   if (rc) return rc;
-  TopkHistory h{out_tokens, out_parents, c->t_dev, c->t0_dev};
+  TopkHistory h{out_tokens, out_parents, c->t_dev, c->t0_dev, entry_rows > 0 ? c->row_map : nullptr, entry_rows};
   HIP_TRY(c, launch_topk(logits, c->pp_cum[p], c->last_tok, c->cfg.eos_id, c->batch, c->cfg.beam, c->V, c->cfg.beam,
                          c->cand_lp, c->cand_idx, c->pp_tok[p ^ 1], c->pp_par, c->pp_cum[p ^ 1], c->stream, &h,
                          c->done_dev, c->done_dev + c->cfg.max_batch));
@@ -1035,79 +1040,156 @@ static int loop_step(san_ctx* c, int p, int32_t* out_tokens, int32_t* out_parent
 }
 
 int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io_dev, int32_t* out_tokens_dev,
-                 int32_t* out_parents_dev, float* logits_work_dev, int32_t use_graph) {
+                 int32_t* out_parents_dev, float* logits_work_dev, int32_t flags) {
   if (!c) return SAN_EINVAL;
   if (!tokens_dev || !cum_io_dev || !out_tokens_dev || !out_parents_dev || !logits_work_dev || n < 1)
     return fail(c, SAN_EINVAL, "san_decode_n: bad argument");
+  if (flags & ~(SAN_LOOP_GRAPH | SAN_LOOP_COMPACT)) return fail(c, SAN_EINVAL, "san_decode_n: unknown flag");
   if (reinterpret_cast<uintptr_t>(logits_work_dev) % 16)
     return fail(c, SAN_EINVAL, "san_decode_n: the logits scratch must be 16-byte aligned");
   if (c->t < 0) return fail(c, SAN_ESTATE, "san_decode_n before san_encode");
   if (c->t + n > c->cfg.max_tgt_len) return fail(c, SAN_ECAPACITY, "san_decode_n: would exceed max_tgt_len");
   if (c->prof_on) return fail(c, SAN_ESTATE, "san_decode_n: switch san_profile off first");
+  const bool use_graph = (flags & SAN_LOOP_GRAPH) != 0;
+  const bool compact = (flags & SAN_LOOP_COMPACT) != 0 && c->cfg.eos_id >= 0;
   if (use_graph && (!c->stream || !c->cfg.use_cache))
     return fail(c, SAN_EINVAL, "san_decode_n: graph replay needs a non-default stream and use_cache = 1");
-  const int rows = c->batch * c->cfg.beam;
+  if ((flags & SAN_LOOP_COMPACT) && !c->cfg.use_cache)
+    return fail(c, SAN_EINVAL, "san_decode_n: dropping finished sentences needs use_cache = 1");
+  const int beam = c->cfg.beam;
+  const int batch0 = c->batch, rows0 = batch0 * beam;   // the batch as the caller knows it
+  int rc;
   if (!c->pp_par) {
-    int rc;
     for (int i = 0; i < 2; ++i) {
       if ((rc = dalloc(c, (void**)&c->pp_tok[i], (size_t)c->rows_max * 4, false))) return rc;
       if ((rc = dalloc(c, (void**)&c->pp_cum[i], (size_t)c->rows_max * 4, false))) return rc;
     }
     if ((rc = dalloc(c, (void**)&c->pp_par, (size_t)c->rows_max * 4, false))) return rc;
     if ((rc = dalloc(c, (void**)&c->t0_dev, 256, false))) return rc;
+    if ((rc = dalloc(c, (void**)&c->row_map, (size_t)c->rows_max * 4, false))) return rc;
+    if ((rc = dalloc(c, (void**)&c->cum_final, (size_t)c->rows_max * 4, false))) return rc;
+    if ((rc = dalloc(c, (void**)&c->drop_dev, (size_t)c->cfg.max_batch * 4, false))) return rc;
   }
-  HIP_TRY(c, hipMemcpyAsync(c->pp_tok[0], tokens_dev, (size_t)rows * 4, hipMemcpyDeviceToDevice, c->stream));
-  HIP_TRY(c, hipMemcpyAsync(c->pp_cum[0], cum_io_dev, (size_t)rows * 4, hipMemcpyDeviceToDevice, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(c->pp_tok[0], tokens_dev, (size_t)rows0 * 4, hipMemcpyDeviceToDevice, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(c->pp_cum[0], cum_io_dev, (size_t)rows0 * 4, hipMemcpyDeviceToDevice, c->stream));
   HIP_TRY(c, hipMemcpyAsync(c->t0_dev, c->t_dev, 4, hipMemcpyDeviceToDevice, c->stream));
-  int done = 0, rc, check_rc = SAN_OK, last_check = 0;
-  // With EOS handling on, the loop stops once every sentence is finished; the
-  // count is read back (one stream synchronisation) every kCheckEvery steps.
-  constexpr int kCheckEvery = 8;
+  if (compact)
+    HIP_TRY(c, hipMemcpyAsync(c->row_map, c->iota_dev, (size_t)rows0 * 4, hipMemcpyDeviceToDevice, c->stream));
+  // sentence i of the current batch is sentence ent[i] of the caller's; drop_from[b]: steps done
+  // when the caller's sentence b left the batch (-1: still in)
+  std::vector<int> ent(batch0), drop_from(batch0, -1);
+  for (int i = 0; i < batch0; ++i) ent[i] = i;
+  bool compacted = false;
+
+  // With EOS handling on, the flags of finished sentences and their count are read back
+  // (one stream synchronisation) every kCheckEvery steps: the loop stops once every
+  // sentence is finished, and -- when asked to -- drops the finished ones from the batch
+  // once they are a quarter of it and enough steps remain to pay for the new graph.
+  constexpr int kCheckEvery = 8, kMinStepsLeft = 16;
+  int done = 0, last_check = 0;
   bool stop = false;
-  auto all_finished = [&](int steps_done) -> bool {
-    if (stop) return true;
-    if (c->cfg.eos_id < 0 || steps_done - last_check < kCheckEvery) return false;
-    last_check = steps_done;
-    int32_t cnt = 0;
-    check_rc = san_finished(c, &cnt);
-    stop = check_rc != SAN_OK || cnt >= c->batch;
-    return stop;
-  };
-  if (use_graph && n >= 2) {
-    // the graph holds two steps (parity 0 then 1); it is rebuilt when the caller's
-    // buffers or the batch change
-    const bool stale = !c->graph2 || c->graph_key[0] != out_tokens_dev || c->graph_key[1] != out_parents_dev ||
-                       c->graph_key[2] != logits_work_dev || c->graph_rows != rows;
-    if (stale && n >= 4) {
-      if (c->graph2) { (void)hipGraphExecDestroy(c->graph2); c->graph2 = nullptr; }
-      // two ordinary steps first, so that one-time set-up inside the launchers
-      // (per-kernel attributes) has happened before anything is captured
-      for (; done < 2; ++done)
-        if ((rc = loop_step(c, done & 1, out_tokens_dev, out_parents_dev, logits_work_dev))) return rc;
-      hipGraph_t g = nullptr;
-      const int t_before = c->t;
-      HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
-      rc = loop_step(c, 0, out_tokens_dev, out_parents_dev, logits_work_dev);
-      if (!rc) rc = loop_step(c, 1, out_tokens_dev, out_parents_dev, logits_work_dev);
-      const hipError_t e = hipStreamEndCapture(c->stream, &g);
-      c->t = t_before;   // capturing queued nothing
-      if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
-      if (e != hipSuccess) return fail(c, SAN_EHIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
-      const hipError_t e2 = hipGraphInstantiate(&c->graph2, g, nullptr, nullptr, 0);
-      (void)hipGraphDestroy(g);
-      if (e2 != hipSuccess) return fail(c, SAN_EHIP, std::string("hipGraphInstantiate: ") + hipGetErrorString(e2));
-      c->graph_key[0] = out_tokens_dev; c->graph_key[1] = out_parents_dev; c->graph_key[2] = logits_work_dev;
-      c->graph_rows = rows;
+  enum { kGoOn = 0, kStop = 1, kCompacted = 2 };
+  auto check = [&](int& action) -> int {
+    action = stop ? kStop : kGoOn;
+    if (stop || c->cfg.eos_id < 0 || done - last_check < kCheckEvery) return SAN_OK;
+    last_check = done;
+    const int mb = c->cfg.max_batch;
+    HIP_TRY(c, hipMemcpyAsync(c->done_host, c->done_dev, ((size_t)mb + 1) * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    const int cnt = c->done_host[mb];
+    if (cnt >= c->batch) { stop = true; action = kStop; return SAN_OK; }
+    if (!compact || cnt * 4 < c->batch || n - done < kMinStepsLeft) return SAN_OK;
+    std::vector<int32_t> keep;
+    for (int i = 0; i < c->batch; ++i)
+      if (!c->done_host[i]) keep.push_back(i);
+    if (keep.empty() || (int)keep.size() == c->batch) return SAN_OK;
+    // the leaving sentences' scores are final: every current score goes to the caller's row now
+    const int p = done & 1, rows = c->batch * beam;
+    HIP_TRY(c, launch_scatter_words(c->cum_final, c->pp_cum[p], c->row_map, rows, c->stream));
+    for (int i = 0; i < c->batch; ++i)
+      if (c->done_host[i]) drop_from[ent[i]] = done;
+    int r = san_compact(c, keep.data(), (int32_t)keep.size());
+    if (r) return r;
+    // the loop's own per-row arrays follow (san_compact left the list in keep_dev)
+    const int nk = (int)keep.size();
+    void* arrs[3] = {c->pp_tok[p], c->pp_cum[p], c->row_map};
+    for (void* a : arrs) {
+      HIP_TRY(c, launch_gather_groups(c->cmp_tmp, a, c->keep_dev, beam, nk, 1, c->stream));
+      HIP_TRY(c, hipMemcpyAsync(a, c->cmp_tmp, (size_t)nk * beam * 4, hipMemcpyDeviceToDevice, c->stream));
     }
-    for (; c->graph2 && done + 2 <= n && !all_finished(done); done += 2) {
-      HIP_TRY(c, hipGraphLaunch(c->graph2, c->stream));
-      c->t += 2;
+    for (int i = 0; i < nk; ++i) ent[i] = ent[keep[i]];
+    ent.resize(nk);
+    compacted = true;
+    action = kCompacted;
+    return SAN_OK;
+  };
+
+  while (done < n && !stop) {
+    const int rows = c->batch * beam;
+    const int entry_rows = compacted ? rows0 : 0;
+    int action = kGoOn;
+    if (use_graph && n - done >= 2 && (done & 1) == 0) {
+      // the graph holds two steps (parity 0 then 1); it is rebuilt when the caller's
+      // buffers or the batch change
+      const bool stale = !c->graph2 || c->graph_key[0] != out_tokens_dev || c->graph_key[1] != out_parents_dev ||
+                         c->graph_key[2] != logits_work_dev || c->graph_rows != rows || c->graph_entry_rows != entry_rows;
+      if (stale && n - done >= 4) {
+        if (c->graph2) { (void)hipGraphExecDestroy(c->graph2); c->graph2 = nullptr; }
+        // two ordinary steps first, so that one-time set-up inside the launchers
+        // (per-kernel attributes) has happened before anything is captured
+        for (int i = 0; i < 2; ++i, ++done)
+          if ((rc = loop_step(c, done & 1, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows))) return rc;
+        hipGraph_t g = nullptr;
+        const int t_before = c->t;
+        HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+        rc = loop_step(c, 0, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows);
+        if (!rc) rc = loop_step(c, 1, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows);
+        const hipError_t e = hipStreamEndCapture(c->stream, &g);
+        c->t = t_before;   // capturing queued nothing
+        if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
+        if (e != hipSuccess) return fail(c, SAN_EHIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+        const hipError_t e2 = hipGraphInstantiate(&c->graph2, g, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(g);
+        if (e2 != hipSuccess) return fail(c, SAN_EHIP, std::string("hipGraphInstantiate: ") + hipGetErrorString(e2));
+        c->graph_key[0] = out_tokens_dev; c->graph_key[1] = out_parents_dev; c->graph_key[2] = logits_work_dev;
+        c->graph_rows = rows;
+        c->graph_entry_rows = entry_rows;
+      }
+      const bool fresh = c->graph2 && c->graph_rows == rows && c->graph_entry_rows == entry_rows &&
+                         c->graph_key[0] == out_tokens_dev && c->graph_key[1] == out_parents_dev &&
+                         c->graph_key[2] == logits_work_dev;
+      while (fresh && done + 2 <= n) {
+        if ((rc = check(action))) return rc;
+        if (action != kGoOn) break;
+        HIP_TRY(c, hipGraphLaunch(c->graph2, c->stream));
+        c->t += 2;
+        done += 2;
+      }
+      if (action != kGoOn) continue;   // stopped, or the batch shrank: a new graph
+    }
+    // what the graph did not cover (no graph asked for, an odd tail, too few steps to capture)
+    while (done < n) {
+      if ((rc = check(action))) return rc;
+      if (action != kGoOn) break;
+      if ((rc = loop_step(c, done & 1, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows))) return rc;
+      ++done;
     }
   }
-  for (; done < n && !all_finished(done); ++done)
-    if ((rc = loop_step(c, done & 1, out_tokens_dev, out_parents_dev, logits_work_dev))) return rc;
-  if (check_rc) return check_rc;
-  HIP_TRY(c, hipMemcpyAsync(cum_io_dev, c->pp_cum[done & 1], (size_t)rows * 4, hipMemcpyDeviceToDevice, c->stream));
+  if (!compacted) {
+    HIP_TRY(c, hipMemcpyAsync(cum_io_dev, c->pp_cum[done & 1], (size_t)rows0 * 4, hipMemcpyDeviceToDevice, c->stream));
+    return SAN_OK;
+  }
+  // sentences that left the batch: their rows of the history keep extending with EOS in
+  // place, their scores were saved when they left
+  HIP_TRY(c, launch_scatter_words(c->cum_final, c->pp_cum[done & 1], c->row_map, c->batch * beam, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(cum_io_dev, c->cum_final, (size_t)rows0 * 4, hipMemcpyDeviceToDevice, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));   // the pinned staging area is free again
+  int* pin = c->done_host;
+  for (int b = 0; b < batch0; ++b) pin[b] = drop_from[b];
+  HIP_TRY(c, hipMemcpyAsync(c->drop_dev, pin, (size_t)batch0 * 4, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, launch_fill_finished(out_tokens_dev, out_parents_dev, c->drop_dev, batch0, beam, done, c->cfg.eos_id,
+                                  c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
   return SAN_OK;
 }
 

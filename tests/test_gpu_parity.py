@@ -626,6 +626,61 @@ def test_compact_argument_errors_and_flags():
     gpu.close()
 
 
+@pytest.mark.parametrize("use_graph", [False, True])
+@pytest.mark.parametrize("seed", [3, 5, 7])
+def test_decode_n_drops_finished_sentences(seed, use_graph):
+    """san_decode_n with SAN_LOOP_COMPACT: finished sentences leave the batch at an 8-step
+    check, the rest of the decode runs on the smaller batch, and the caller's arrays are what
+    the per-call loop on the full batch gives (tokens, parents, scores, in the caller's row
+    numbering; sentences that left keep extending with EOS in place)."""
+    batch, beam, V, T = 8, 3, 8, 64
+    B = batch * beam
+    cfg = mid_cfg(steps=T, V=V, batch=batch, beam=beam)
+    w = wl.make_weights(cfg, seed=seed)
+    src, lens = wl.make_source(mid_cfg(batch=batch), seed)
+    src = np.minimum(src, V - 1)
+    cum0 = np.full(B, -np.inf, dtype=np.float32)
+    cum0[0::beam] = 0.0
+    ref_gpu = hz.make_gpu(cfg, w, eos_id=wl.EOS_ID)
+    ref = hz.gpu_free_run(ref_gpu, src, lens, beam, T)
+    ref_gpu.close()
+    done = [(ref["tokens"][t].reshape(batch, beam) == wl.EOS_ID).all(axis=1) for t in range(T)]   # [T][batch]
+    # what the 8-step checks must do, from the reference run
+    active = np.arange(batch)
+    expect_steps = T
+    for s in range(8, T + 1, 8):
+        fin = done[s - 1][active]
+        if fin.all():
+            expect_steps = s
+            break
+        if 4 * fin.sum() >= len(active) and T - s >= 16:
+            active = active[~fin]
+    assert len(active) < batch, "pick another seed: no sentence leaves the batch early"
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        gpu = hz.make_gpu(cfg, w, eos_id=wl.EOS_ID)
+        gpu.encode(torch.from_numpy(src).cuda(), torch.from_numpy(lens).cuda())
+        logits = torch.empty((B, V), dtype=torch.float32, device="cuda")
+        for rep in range(2):
+            gpu.rewind()
+            assert gpu.batch == batch
+            out_tok = torch.full((T, B), -7, dtype=torch.int32, device="cuda")
+            out_par = torch.full((T, B), -7, dtype=torch.int32, device="cuda")
+            cum = torch.from_numpy(cum0).cuda()
+            gpu.decode_n(T, torch.full((B,), wl.BOS_ID, dtype=torch.int32, device="cuda"), cum, out_tok, out_par,
+                         logits, use_graph, compact=True)
+            stream.synchronize()
+            assert gpu.step == expect_steps
+            assert gpu.active().tolist() == active.tolist() and gpu.batch == len(active)
+            got_t, got_p = out_tok.cpu().numpy(), out_par.cpu().numpy()
+            for t in range(expect_steps):
+                assert np.array_equal(got_t[t], ref["tokens"][t].reshape(-1)), (rep, t)
+                assert np.array_equal(got_p[t], ref["parents"][t].reshape(-1)), (rep, t)
+            assert (got_t[expect_steps:] == -7).all() and (got_p[expect_steps:] == -7).all()
+            np.testing.assert_allclose(cum.cpu().numpy(), ref["scores"][expect_steps - 1].reshape(-1), rtol=1e-5, atol=1e-5)
+        gpu.close()
+
+
 # ------------------------------------------------------ head widths, extreme shapes
 @pytest.mark.parametrize("d,H,dtype", [(128, 8, "f32"), (128, 4, "f32"), (256, 2, "f32"), (128, 8, "bf16"),
                                        (256, 8, "bf16"), (256, 2, "bf16")])
