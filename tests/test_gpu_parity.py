@@ -538,6 +538,44 @@ def test_decode_n_stops_when_every_sentence_is_finished(use_graph):
         gpu.close()
 
 
+# ------------------------------------------------------ seeded random small shapes
+def _random_policy(rng, layers):
+    pi, left = [], layers
+    while left:
+        b = int(rng.integers(1, left + 1))
+        pi.append(b)
+        left -= b
+    return pi
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_random_shapes_and_policies(case):
+    """Seeded random model shapes, policies, batch / beam sizes and source lengths: widths
+    that are not powers of two, every head width, ragged tiles in every GEMM, blocks of
+    every size in both attentions, all four cached modes (dot A / dot S / AAN, fp32 / bf16)."""
+    rng = np.random.default_rng(1000 + case)
+    dh = int(rng.choice([16, 32, 64, 128]))
+    H = int(rng.choice([h for h in (1, 2, 3, 4, 5, 6, 8, 12, 16) if 64 <= h * dh <= 512 and (h * dh) % 64 == 0]))
+    n_dec = int(rng.integers(1, 6))
+    kind = "aan" if case % 4 == 3 else "dot"
+    dtype = "bf16" if case % 3 == 2 else "f32"
+    cfg = dict(n_enc=int(rng.integers(1, 3)), n_dec=n_dec, d=H * dh, H=H, F=64 * int(rng.integers(1, 9)),
+               V=4 * int(rng.integers(2, 700)), dtype=dtype, batch=int(rng.integers(1, 7)), beam=int(rng.integers(1, 6)),
+               src_len=(1, int(rng.integers(2, 50))), steps=int(rng.integers(4, 14)), self_kind=kind,
+               self_pi=[1] * n_dec if kind == "aan" else _random_policy(rng, n_dec),
+               encdec_pi=_random_policy(rng, n_dec), name=f"random{case}")
+    share = "S" if case % 2 else "A"
+    w = wl.make_weights(cfg, seed=1000 + case, sharp=3.0)
+    src, lens = ragged(cfg, 1000 + case)
+    gpu = hz.make_gpu(cfg, w, share=share, max_batch=cfg["batch"] + int(rng.integers(0, 3)))
+    ls = hz.Lockstep(gpu, hz.make_oracle(cfg, w, share=share), src, lens, cfg["beam"])
+    tol = BF16_TOL if dtype == "bf16" else F32_TOL
+    for t in range(cfg["steps"]):
+        ls.step(tie_tol=5e-4 if dtype == "f32" else 2 * BF16_TOL * 4.0)
+    assert max(ls.log["logit_err"]) <= tol, (cfg, share)
+    gpu.close()
+
+
 # ------------------------------------------------------ dropping sentences from a running batch
 @pytest.mark.parametrize("kind,share", [("dot", "A"), ("dot", "S"), ("aan", "A")])
 def test_compact_keeps_the_remaining_sentences_exact(kind, share):
