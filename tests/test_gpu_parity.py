@@ -613,6 +613,27 @@ def test_compact_keeps_the_remaining_sentences_exact(kind, share):
     gpu.close()
 
 
+def test_encode_after_compact_starts_clean():
+    """A context that was compacted mid-decode takes a new san_encode like a fresh one."""
+    cfg = mid_cfg(steps=12)
+    w = wl.make_weights(cfg, seed=33, sharp=4.0)
+    src, lens = ragged(cfg, 33)
+    gpu = hz.make_gpu(cfg, w)
+    ls = hz.Lockstep(gpu, hz.make_oracle(cfg, w), src, lens, cfg["beam"], subset=[0, 2])
+    for t in range(5):
+        if t == 3:
+            hz.lockstep_compact(ls, [0, 2])
+        ls.step(tie_tol=5e-4)
+    assert max(ls.log["logit_err"]) <= F32_TOL and gpu.batch == 2
+    src2, lens2 = ragged(cfg, 34)
+    ls2 = hz.Lockstep(gpu, hz.make_oracle(cfg, w), src2, lens2, cfg["beam"])     # encodes the new batch
+    assert gpu.batch == cfg["batch"] and gpu.active().tolist() == list(range(cfg["batch"]))
+    for t in range(6):
+        ls2.step(tie_tol=5e-4)
+    assert max(ls2.log["logit_err"]) <= F32_TOL
+    gpu.close()
+
+
 def test_compact_argument_errors_and_flags():
     cfg = mid_cfg(steps=64, V=8, batch=4, beam=3)
     w = wl.make_weights(cfg, seed=4)
