@@ -758,6 +758,22 @@ def test_head_widths(d, H, dtype):
         gpu.close()
 
 
+@pytest.mark.parametrize("kind,dtype", [("dot", "f32"), ("aan", "bf16")])
+def test_maximum_width(kind, dtype):
+    """d_model = 2048, the widest model the library takes (LayerNorm rows of 8 waves, 64 k-chunks
+    per projection), with 128-wide heads."""
+    cfg = dict(n_enc=1, n_dec=2, d=2048, H=16, F=128, V=64, dtype=dtype, batch=2, beam=2, src_len=(1, 9), steps=4,
+               self_pi=[1, 1] if kind == "aan" else [2], encdec_pi=[2], self_kind=kind, name="wide")
+    w = wl.make_weights(cfg, seed=41, sharp=1.0)
+    src, lens = ragged(cfg, 41)
+    gpu = hz.make_gpu(cfg, w)
+    ls = hz.Lockstep(gpu, hz.make_oracle(cfg, w), src, lens, cfg["beam"])
+    for t in range(cfg["steps"]):
+        ls.step(tie_tol=5e-4 if dtype == "f32" else 0.2)
+    assert max(ls.log["logit_err"]) <= (F32_TOL if dtype == "f32" else BF16_TOL), max(ls.log["logit_err"])
+    gpu.close()
+
+
 def test_maximum_beam_and_long_cache():
     """beam = 32 (the largest the library takes) and a cache of 300 positions
     (several chunks of the attention pipeline plus a ragged tail)."""
