@@ -171,6 +171,37 @@ def gemm_flops_per_step(cfg, heads_self, followers_self, heads_ctx):
     return {"proj": proj, "out": out, "ffn": ffn, "logits": logits}
 
 
+def step_roofline(cfg, esz, self_pi, ctx_pi, mean_src, ms_per_step):
+    """What one decode step has to move and multiply under the sharing policy, each needed
+    weight once, each live cache element once per layer that uses it (average over the T
+    steps), memory K/V once per sentence, logits written and read once: the step-level
+    HBM and MFMA bounds next to the measured step."""
+    B, batch, d, F, V, Ld, T = (cfg["batch"] * cfg["beam"], cfg["batch"], cfg["d"], cfg["F"], cfg["V"], cfg["n_dec"],
+                                cfg["steps"])
+    aan = cfg["self_kind"] == "aan"
+    hs, fs = (0, 0) if aan else (len(self_pi), sum(self_pi) - len(self_pi))
+    hc, fc = len(ctx_pi), sum(ctx_pi) - len(ctx_pi)
+    n_mean = (T + 1) / 2
+    w_elems = (4 * hs + 2 * fs) * d * d + (2 * hc + fc) * d * d + Ld * 2 * d * F + V * d
+    state = (2 * hs + fs) * B * n_mean * d * esz + (2 * hs + fs) * B * d * esz            # cache reads + appends
+    if aan:
+        w_elems += Ld * (2 * d * F + 4 * d * d)
+        state = Ld * 2 * B * d * 4                                                        # running sums, read + write
+    mem = hc * 2 * batch * mean_src * d * esz
+    logits = 2 * B * V * 4
+    total = w_elems * esz + state + mem + logits
+    flops = 2 * B * ((3 * hs + fs + hs + fs) * d * d + (2 * hc + fc) * d * d + Ld * 2 * d * F + V * d)
+    if aan:
+        flops += 2 * B * Ld * (2 * d * F + 4 * d * d)
+    hbm_us = total / (HBM_PEAK_GBS * 1e9) * 1e6
+    mfma_us = flops / (MFMA_PEAK_TFLOPS[cfg["dtype"]] * 1e12) * 1e6
+    bound = max(hbm_us, mfma_us)
+    return {"algorithmic_MB": total / 1e6, "weights_MB": w_elems * esz / 1e6, "state_MB": state / 1e6,
+            "memory_kv_MB": mem / 1e6, "logits_MB": logits / 1e6, "hbm_us_at_peak": hbm_us,
+            "gemm_GFLOP": flops / 1e9, "mfma_us_at_peak": mfma_us, "bound": "hbm" if hbm_us >= mfma_us else "mfma",
+            "bound_us": bound, "measured_us": ms_per_step * 1e3, "frac": bound / (ms_per_step * 1e3)}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -260,7 +291,7 @@ def main():
                     "event_marker_us_removed_per_launch": marker_us}
     # ------------------------------------------------ latency, encode time, streaming-read yardstick
     # (after the timed region; each of these synchronises per call, the headline loop does not)
-    extras = {}
+    extras = {"step_roofline": step_roofline(cfg, esz, cfg["self_pi"], cfg["encdec_pi"], mean_src, ms_per_step)}
     if not args.no_profile:
         lat = []
         run.pos = 0
