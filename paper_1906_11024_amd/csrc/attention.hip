@@ -53,8 +53,20 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnPara
   long long* slot_off = reinterpret_cast<long long*>(smem + sizeof(float) * kWavesPerBlock * NQ * p.lmax);
 
   const int nhg = (p.H + kWavesPerBlock - 1) / kWavesPerBlock;
-  const int hg = blockIdx.x % nhg;
+  int hg = blockIdx.x % nhg;
   int rest = blockIdx.x / nhg;
+  if (p.self_mode && p.rpg > 1) {
+    // The hypotheses of a sentence descend from common ancestors, so their streams
+    // name the same cache rows for most past positions.  Workgroups go to the 8
+    // XCDs round-robin by index and each XCD has its own L2: the rpg rows of a
+    // sentence (same heads) take consecutive slots of ONE XCD, so a shared cache
+    // row leaves HBM once and the other hypotheses hit in L2.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int grp = (slot / p.rpg) * 8 + xcd;            // (sentence, head group)
+    if (grp >= (p.rows / p.rpg) * nhg) return;           // padding of the last round (whole block)
+    hg = grp % nhg;
+    rest = (grp / nhg) * p.rpg + slot % p.rpg;
+  }
   const int h = hg * kWavesPerBlock + wid;
   const bool head_ok = h < p.H;
 
@@ -292,6 +304,11 @@ template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p,
   if (p.self_mode) {
     const size_t smem = sizeof(float) * kWavesPerBlock * p.lmax + sizeof(long long) * p.lmax;
     dim3 grid((unsigned)(p.rows * nhg));
+    if (p.rpg > 1) {   // rows of a sentence on one XCD: groups padded to a multiple of 8
+      if (p.rows % p.rpg) return hipErrorInvalidValue;
+      const int groups = (p.rows / p.rpg) * nhg;
+      grid = dim3((unsigned)((groups + 7) / 8 * 8 * p.rpg));
+    }
     hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
   } else if (p.rpg <= 32 && (long)p.groups * p.H * ((p.rpg + 3) / 4) < 1024) {
     // few queries per stream (the beams of a sentence) and few streams: one wave

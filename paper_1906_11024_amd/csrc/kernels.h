@@ -36,7 +36,9 @@ int gemm_pick_ksplit(int M, int N, int K, int dtype);
 // One kernel for every attention in the model.  A wave owns one head of one
 // key/value stream and NQ queries that share the stream.
 //  self (cached decoding): stream = history of decoder row r, key j lives in
-//     slot j*rows + anc[r*ld_anc + j], n = *t_dev + 1 keys, one query.
+//     slot j*rows + anc[r*ld_anc + j], n = *t_dev + 1 keys, one query.  rpg > 1:
+//     rows come in groups of rpg (the hypotheses of a sentence) that share most
+//     cache rows; a group's workgroups are placed on one XCD.
 //  grouped: stream = group g (a sentence's encoder memory, or the positions of
 //     one hypothesis when nothing is cached), key j in slot g*slot_stride + j;
 //     the group's rpg query rows are g*rpg .. g*rpg+rpg-1; n = len[g] or, when

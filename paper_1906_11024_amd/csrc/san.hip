@@ -696,7 +696,7 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
       a.S_buf = c->dec[L.self_head].S_self; a.ldS = T;
       a.out = c->ab; a.ldo = d;
       a.anc = c->anc; a.ld_anc = T; a.t_dev = c->t_dev;
-      a.self_mode = 1; a.rows = B; a.slot_rows = cache_rows; a.H = c->H; a.dh = c->dh; a.lmax = T; a.scale = scale;
+      a.self_mode = 1; a.rows = B; a.rpg = c->cfg.beam; a.slot_rows = cache_rows; a.H = c->H; a.dh = c->dh; a.lmax = T; a.scale = scale;
       a.apply = head ? 0 : 1;
       a.emit = head && (has_followers || dbg);
       c->kind = head ? SAN_K_ATTN_SELF : SAN_K_ATTN_APPLY;
