@@ -52,20 +52,32 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnPara
   // self mode: element offset of key j's row inside the cache, [lmax]
   long long* slot_off = reinterpret_cast<long long*>(smem + sizeof(float) * kWavesPerBlock * NQ * p.lmax);
 
+  // The launcher spreads the work over a 3-D grid whose linear order (x fastest) is
+  // the order wanted on the XCDs, so that the block index needs no run-time
+  // divisions here (four of them were ~130 scalar instructions at the head of
+  // every wave).  p.grid3 == 0: plain 1-D grid (a dimension would not fit).
   const int nhg = (p.H + kWavesPerBlock - 1) / kWavesPerBlock;
-  int hg = blockIdx.x % nhg;
-  int rest = blockIdx.x / nhg;
+  int hg, rest, qb_grid = 0;
   if (p.self_mode && p.rpg > 1) {
     // The hypotheses of a sentence descend from common ancestors, so their streams
     // name the same cache rows for most past positions.  Workgroups go to the 8
-    // XCDs round-robin by index and each XCD has its own L2: the rpg rows of a
-    // sentence (same heads) take consecutive slots of ONE XCD, so a shared cache
-    // row leaves HBM once and the other hypotheses hit in L2.
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int grp = (slot / p.rpg) * 8 + xcd;            // (sentence, head group)
-    if (grp >= (p.rows / p.rpg) * nhg) return;           // padding of the last round (whole block)
-    hg = grp % nhg;
-    rest = (grp / nhg) * p.rpg + slot % p.rpg;
+    // XCDs round-robin by linear index and each XCD has its own L2: the rpg rows
+    // of a sentence (same heads) take consecutive slots of ONE XCD, so a shared
+    // cache row leaves HBM once and the other hypotheses hit in L2.
+    // grid = (8 XCDs, rpg rows, rounds): linear index = xcd + 8 * (row + rpg * round)
+    const int grp = blockIdx.z * 8 + blockIdx.x;          // (sentence, head group)
+    if (grp >= p.groups * nhg) return;                    // padding of the last round (whole block)
+    const bool pow2 = (nhg & (nhg - 1)) == 0;
+    const int sentence = pow2 ? grp >> __builtin_ctz(nhg) : grp / nhg;
+    hg = grp - sentence * nhg;
+    rest = sentence * p.rpg + blockIdx.y;
+  } else if (p.grid3) {
+    hg = blockIdx.x;            // grid = (head groups, rows) or (head groups, groups, query blocks)
+    rest = blockIdx.y;
+    qb_grid = blockIdx.z;
+  } else {
+    hg = blockIdx.x % nhg;
+    rest = blockIdx.x / nhg;
   }
   const int h = hg * kWavesPerBlock + wid;
   const bool head_ok = h < p.H;
@@ -95,8 +107,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnPara
   } else {
     // blocks of one group (= the beams of a sentence) are numbered a multiple of
     // 8 apart where possible, so that they land on the same XCD and share its L2
-    const int qb = rest / p.groups;   // query block inside the group
-    const int grp = rest % p.groups;
+    const int qb = p.grid3 ? qb_grid : rest / p.groups;   // query block inside the group
+    const int grp = p.grid3 ? rest : rest % p.groups;
     slot_base = (long long)(p.group_map ? p.group_map[grp] : grp) * p.slot_stride;
     const int nfull = p.len ? max(0, min(p.len[grp], p.lmax)) : p.n_fixed;
     n = 0;
@@ -299,15 +311,23 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnPara
   }
 }
 
-template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p, hipStream_t stream) {
+template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p0, hipStream_t stream) {
+  AttnParams p = p0;
   const int nhg = (p.H + kWavesPerBlock - 1) / kWavesPerBlock;
+  constexpr unsigned kMaxDim = 65535;
+  p.grid3 = 0;
   if (p.self_mode) {
     const size_t smem = sizeof(float) * kWavesPerBlock * p.lmax + sizeof(long long) * p.lmax;
     dim3 grid((unsigned)(p.rows * nhg));
-    if (p.rpg > 1) {   // rows of a sentence on one XCD: groups padded to a multiple of 8
+    if (p.rpg > 1) {   // rows of a sentence on one XCD: (sentence, head group) pairs padded to a multiple of 8
       if (p.rows % p.rpg) return hipErrorInvalidValue;
-      const int groups = (p.rows / p.rpg) * nhg;
-      grid = dim3((unsigned)((groups + 7) / 8 * 8 * p.rpg));
+      p.groups = p.rows / p.rpg;
+      const unsigned rounds = (unsigned)((p.groups * nhg + 7) / 8);
+      if (rounds > kMaxDim || (unsigned)p.rpg > kMaxDim) return hipErrorInvalidValue;
+      grid = dim3(8, (unsigned)p.rpg, rounds);
+    } else if ((unsigned)p.rows <= kMaxDim) {
+      p.grid3 = 1;
+      grid = dim3((unsigned)nhg, (unsigned)p.rows, 1);
     }
     hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
   } else if (p.rpg <= 32 && (long)p.groups * p.H * ((p.rpg + 3) / 4) < 1024) {
@@ -316,11 +336,19 @@ template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p,
     // re-reads of the stream hit in L2.  With >= 1024 streams a wave takes 4 queries.
     const size_t smem = sizeof(float) * kWavesPerBlock * p.lmax;
     dim3 grid((unsigned)(p.groups * p.rpg * nhg));
+    if ((unsigned)p.groups <= kMaxDim && (unsigned)p.rpg <= kMaxDim) {
+      p.grid3 = 1;
+      grid = dim3((unsigned)nhg, (unsigned)p.groups, (unsigned)p.rpg);
+    }
     hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
   } else {
     const int nqb = (p.rpg + 3) / 4;
     const size_t smem = sizeof(float) * kWavesPerBlock * 4 * p.lmax;
     dim3 grid((unsigned)((size_t)p.groups * nqb * nhg));
+    if ((unsigned)p.groups <= kMaxDim && (unsigned)nqb <= kMaxDim) {
+      p.grid3 = 1;
+      grid = dim3((unsigned)nhg, (unsigned)p.groups, (unsigned)nqb);
+    }
     hipLaunchKernelGGL((attention_kernel<T, LPP, 4>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
   }
   return hipGetLastError();

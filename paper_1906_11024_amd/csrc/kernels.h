@@ -58,6 +58,7 @@ struct AttnParams {
   const int* len;                   // grouped, non-causal: keys per group (nullptr: n_fixed)
   int n_fixed;
   int self_mode, rows, groups, rpg, slot_stride, causal;
+  int grid3;                        // set by the launcher: the block index is spread over a 3-D grid
   int slot_rows;                    // self mode: rows of one cache position (0: same as rows)
   const int* group_map;             // grouped: memory of group g is slot group_map[g] (nullptr: g)
   int H, dh;
