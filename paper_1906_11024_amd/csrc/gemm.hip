@@ -97,7 +97,7 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
     bias_v[j] = (p.bias && p.out_kind != 2 && kg == 0 && n < p.N) ? to_f32(reinterpret_cast<const T*>(p.bias)[n]) : 0.f;
   }
   const int nchunks = p.K / EPC;
-  const int cps = (nchunks + p.ksplit - 1) / p.ksplit;
+  const int cps = p.cps;   // chunks per k-split, (nchunks + ksplit - 1) / ksplit, divided on the host
   const int c_begin = blockIdx.z * cps;
   const int c_end = min(nchunks, c_begin + cps);
   // inside the block the chunks are dealt round-robin to the KW k-groups; every
@@ -331,6 +331,10 @@ static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
   }
   GemmParams q = p;
   q.xcd_rows = 0;
+  {
+    const int nchunks = p.K / (CB / (int)sizeof(T));
+    q.cps = (nchunks + p.ksplit - 1) / p.ksplit;
+  }
   if (grid.x % 8 != 0 && grid.y > 1 && grid.z == 1) {
     q.xcd_rows = (int)grid.y;
     grid = dim3((grid.x + 7) / 8 * 8 * grid.y, 1, 1);

@@ -25,7 +25,7 @@ struct GemmParams {
   int* bump;
   int M, N, K;                // K % (128 / sizeof(T)) == 0
   int relu, out_kind, ksplit;
-  int xcd_rows;                // set by the launcher (tile-to-XCD mapping), callers leave it alone
+  int xcd_rows, cps;           // set by the launcher (tile-to-XCD mapping, k chunks per split), callers leave them alone
 };
 hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream);
 // split factor that fills the chip for an M x N x K product (1 when the tiles
