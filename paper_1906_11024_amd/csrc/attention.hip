@@ -36,7 +36,12 @@ __device__ __forceinline__ void widen(const uint4& raw, float (&out)[8]) {
   }
 }
 
-template <typename T, int LPP, int NQ>
+// PIPE = 1: the variant for long streams (see stream_pass below): every request after
+// a stream's first chunk is unconditional, so the waits are exact and loading overlaps
+// computing.  It holds three chunks in registers where PIPE = 0 gets by with fewer,
+// and wastes a few instructions on short streams, so the launcher picks it by the
+// capacity of the stream (lmax).
+template <typename T, int LPP, int NQ, int PIPE>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnParams p) {
   constexpr int EPL = Frag<T>::N;       // elements per lane per position
   constexpr int PPL = kWave / LPP;      // positions per load instruction
@@ -154,12 +159,72 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnPara
     }
   };
 
-  // Software pipeline: while chunk i is being consumed the loads of chunk i+1 are
-  // in flight, and the first V chunk is requested before any score is computed,
-  // so a short stream costs a single memory round trip.
+  // The same chunk with every instruction issued (positions past n-1 re-read
+  // position n-1: the same cache line, so only the instruction is wasted).  Used
+  // in the steady state of long streams: a request the compiler sees as
+  // unconditional is one it can count, and only then does the wait for an older
+  // chunk let the younger one stay in flight (behind conditional requests every
+  // wait drains all loads, and loading and computing take turns instead of
+  // overlapping).
+  auto load_all = [&](const T* base, unsigned ld, int j0, uint4 (&buf)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int j = min(j0 + u * PPL + g, n - 1);
+      const long long off = self_mode ? slot_off[j] : (long long)__umul24((unsigned)j, ld);
+      buf[u] = *reinterpret_cast<const uint4*>(base + off);
+    }
+  };
+  // One pass over the stream with two buffers: on entry b0 holds (a request for)
+  // chunk 0 and b1 chunk 1; a buffer is refilled two chunks ahead as soon as it has
+  // been consumed.  PIPE: the steady state has no branches around its requests, and
+  // the last one to three chunks are written out case by case for the same reason.
+  auto stream_pass = [&](auto&& consume, const T* base, unsigned ld, uint4 (&b0)[U], uint4 (&b1)[U]) {
+    int j0 = 0;
+    if constexpr (PIPE) {
+      while (j0 + 3 * CH < n) {
+        consume(j0, b0);
+        load_all(base, ld, j0 + 2 * CH, b0);
+        consume(j0 + CH, b1);
+        load_all(base, ld, j0 + 3 * CH, b1);
+        j0 += 2 * CH;
+      }
+      if (j0 + 2 * CH < n) {
+        consume(j0, b0);
+        load_all(base, ld, j0 + 2 * CH, b0);
+        consume(j0 + CH, b1);
+        consume(j0 + 2 * CH, b0);
+      } else if (j0 + CH < n) {
+        consume(j0, b0);
+        consume(j0 + CH, b1);
+      } else if (j0 < n) {
+        consume(j0, b0);
+      }
+    } else {
+      for (; j0 < n; j0 += 2 * CH) {
+        consume(j0, b0);
+        if (j0 + 2 * CH < n) load_chunk(base, ld, j0 + 2 * CH, b0);
+        if (j0 + CH < n) {
+          consume(j0 + CH, b1);
+          if (j0 + 3 * CH < n) load_chunk(base, ld, j0 + 3 * CH, b1);
+        }
+      }
+    }
+  };
+  auto load_second = [&](const T* base, unsigned ld, uint4 (&buf)[U]) {   // chunk 1, if there is one
+    if (CH < n) {
+      if constexpr (PIPE) load_all(base, ld, CH, buf);
+      else load_chunk(base, ld, CH, buf);
+    }
+  };
+
+  // The first chunks of K and V are requested before any score is computed, so a
+  // short stream costs a single memory round trip.
   uint4 kb0[U], kb1[U], vb0[U], vb1[U];
   if (n > 0) {
-    if (!p.apply) load_chunk(Kp, ldk, 0, kb0);
+    if (!p.apply) {
+      load_chunk(Kp, ldk, 0, kb0);
+      if constexpr (PIPE) load_second(Kp, ldk, kb1);
+    }
     load_chunk(Vp, ldv, 0, vb0);
   }
 
@@ -193,16 +258,20 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnPara
         }
       }
     };
-    for (int j0 = 0; j0 < n; j0 += 2 * CH) {
-      if (j0 + CH < n) load_chunk(Kp, ldk, j0 + CH, kb1);
-      scores(j0, kb0);
-      if (j0 + CH < n) {
-        if (j0 + 2 * CH < n) load_chunk(Kp, ldk, j0 + 2 * CH, kb0);
-        scores(j0 + CH, kb1);
+    if constexpr (PIPE) {
+      stream_pass(scores, Kp, ldk, kb0, kb1);
+    } else {
+      for (int j0 = 0; j0 < n; j0 += 2 * CH) {   // K chunks are requested one chunk ahead
+        if (j0 + CH < n) load_chunk(Kp, ldk, j0 + CH, kb1);
+        scores(j0, kb0);
+        if (j0 + CH < n) {
+          if (j0 + 2 * CH < n) load_chunk(Kp, ldk, j0 + 2 * CH, kb0);
+          scores(j0 + CH, kb1);
+        }
       }
     }
     wave_lds_sync();
-    if (CH < n) load_chunk(Vp, ldv, CH, vb1);   // second V chunk travels during the softmax
+    load_second(Vp, ldv, vb1);   // second V chunk travels during the softmax
     if (NQ == 4) {
       // ---- softmax over key positions, the four queries side by side: lanes
       // [16 i, 16 i + 16) own query i, so the maxima and sums are 16-lane row
@@ -262,7 +331,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnPara
       }
     }
   } else {
-    if (CH < n) load_chunk(Vp, ldv, CH, vb1);
+    load_second(Vp, ldv, vb1);
     // ---- shared weights: S^{m+i} = S^m (Eq. 4)
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
@@ -295,14 +364,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnPara
       }
     }
   };
-  for (int j0 = 0; j0 < n; j0 += 2 * CH) {   // V chunks are requested two chunks ahead
-    weighted(j0, vb0);
-    if (j0 + 2 * CH < n) load_chunk(Vp, ldv, j0 + 2 * CH, vb0);
-    if (j0 + CH < n) {
-      weighted(j0 + CH, vb1);
-      if (j0 + 3 * CH < n) load_chunk(Vp, ldv, j0 + 3 * CH, vb1);
-    }
-  }
+  stream_pass(weighted, Vp, ldv, vb0, vb1);
 #pragma unroll
   for (int i = 0; i < NQ; ++i) {
 #pragma unroll
@@ -316,6 +378,8 @@ template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p0
   const int nhg = (p.H + kWavesPerBlock - 1) / kWavesPerBlock;
   constexpr unsigned kMaxDim = 65535;
   p.grid3 = 0;
+  // streams that can grow past four chunks of 32 positions take the variant whose loads overlap its arithmetic
+  const bool pipe = p.lmax >= 128;
   if (p.self_mode) {
     const size_t smem = sizeof(float) * kWavesPerBlock * p.lmax + sizeof(long long) * p.lmax;
     dim3 grid((unsigned)(p.rows * nhg));
@@ -329,7 +393,8 @@ template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p0
       p.grid3 = 1;
       grid = dim3((unsigned)nhg, (unsigned)p.rows, 1);
     }
-    hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
+    if (pipe) hipLaunchKernelGGL((attention_kernel<T, LPP, 1, 1>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
+    else hipLaunchKernelGGL((attention_kernel<T, LPP, 1, 0>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
   } else if (p.rpg <= 32 && (long)p.groups * p.H * ((p.rpg + 3) / 4) < 1024) {
     // few queries per stream (the beams of a sentence) and few streams: one wave
     // per query keeps enough waves in flight (at least ~one per SIMD); the queries'
@@ -340,7 +405,8 @@ template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p0
       p.grid3 = 1;
       grid = dim3((unsigned)nhg, (unsigned)p.groups, (unsigned)p.rpg);
     }
-    hipLaunchKernelGGL((attention_kernel<T, LPP, 1>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
+    if (pipe) hipLaunchKernelGGL((attention_kernel<T, LPP, 1, 1>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
+    else hipLaunchKernelGGL((attention_kernel<T, LPP, 1, 0>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
   } else {
     const int nqb = (p.rpg + 3) / 4;
     const size_t smem = sizeof(float) * kWavesPerBlock * 4 * p.lmax;
@@ -349,7 +415,8 @@ template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p0
       p.grid3 = 1;
       grid = dim3((unsigned)nhg, (unsigned)p.groups, (unsigned)nqb);
     }
-    hipLaunchKernelGGL((attention_kernel<T, LPP, 4>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
+    if (pipe) hipLaunchKernelGGL((attention_kernel<T, LPP, 4, 1>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
+    else hipLaunchKernelGGL((attention_kernel<T, LPP, 4, 0>), grid, dim3(kWavesPerBlock * 64), smem, stream, p);
   }
   return hipGetLastError();
 }
