@@ -36,7 +36,9 @@ Readings taken where the paper is silent (all listed in the design notes):
 
 Parity pins live in tests/test_oracle_pins.py.  Parity unpinned (no external
 ground truth exists for them, only internal invariants): the choice among the
-readings above, and the AAN definition.
+readings above, and whether the AAN layer as read here is the one the paper's
+"+AAN" systems ran.  The arithmetic of that reading (running mean, gate layout,
+sigmoid) is itself pinned by closed forms.
 """
 from __future__ import annotations
 
@@ -237,6 +239,7 @@ class SanOracle:
             # ---- self-attention sub-layer (or AAN)
             if self.aan:
                 x = self._aan_step(n, x, t)
+                dump["A_self"][n] = x                        # output of the whole AAN sub-layer
             else:
                 p = f"dec{n}.self"
                 m = self.self_head[n]

@@ -246,6 +246,52 @@ def test_aan_fp32_lockstep(beam):
     gpu.close()
 
 
+def test_aan_gate_closed_forms_on_gpu():
+    """The AAN self layer (Tab. 6 rows "+AAN") against closed forms that do not go through the
+    oracle's gate: the layer's FFN made a constant (w2 = 0, so g = b2) and the gate weights 0,
+    a bias of +-40 saturates the gates (i = 1, f = 0: LN(2 x); i = 0, f = 1: LN(x + b2)), a
+    zero bias halves them (LN(1.5 x + 0.5 b2)); x = scaled embedding + position.  These fail
+    if the kernel swaps the gate halves or the [x; g] halves of its input."""
+    import math
+    cfg = mid_cfg(self_kind="aan", self_pi=[1, 1, 1, 1], steps=4)
+    d = cfg["d"]
+    w = {k: v.copy() for k, v in wl.make_weights(cfg, seed=6).items()}
+    w["dec0.aan.w2"][:] = 0.0
+    w["dec0.aan.wg"][:] = 0.0
+    src, lens = ragged(cfg, 6)
+    B = cfg["batch"] * cfg["beam"]
+    rng = np.random.default_rng(3)
+    toks = rng.integers(3, cfg["V"], size=(2, B)).astype(np.int32)
+    pos = np.arange(2, dtype=np.float64)[:, None]
+    ang = pos * np.exp(-np.arange(0, d, 2, dtype=np.float64)[None, :] * math.log(10000.0) / d)
+    pe = np.zeros((2, d))
+    pe[:, 0::2], pe[:, 1::2] = np.sin(ang), np.cos(ang)
+    lng, lnb = w["dec0.ln1.g"].astype(np.float64), w["dec0.ln1.b"].astype(np.float64)
+    b2 = w["dec0.aan.b2"].astype(np.float64)
+
+    def ln(v):
+        return torch.nn.functional.layer_norm(torch.from_numpy(v), (d,), torch.from_numpy(lng), torch.from_numpy(lnb),
+                                              1e-5).numpy()
+
+    cases = ((40.0, lambda x: 2.0 * x), (-40.0, lambda x: x + b2), (0.0, lambda x: 1.5 * x + 0.5 * b2))
+    for bias, want in cases:
+        w["dec0.aan.bg"] = np.concatenate([np.full(d, bias), np.full(d, -bias)]).astype(np.float32)
+        gpu = hz.make_gpu(cfg, w, debug=1)
+        orc = hz.make_oracle(cfg, w)
+        gpu.encode(torch.from_numpy(src).cuda(), torch.from_numpy(lens).cuda())
+        orc.encode(src, lens)
+        logits = torch.empty((B, cfg["V"]), dtype=torch.float32, device="cuda")
+        for t in range(2):
+            gpu.decode_step(torch.from_numpy(toks[t]).cuda(), logits)
+            lo = orc.decode_step(toks[t])
+            x = w["tgt_emb"][toks[t]].astype(np.float64) * math.sqrt(d) + pe[t]
+            got = gpu.debug_get(sb.SAN_DBG_A_SELF, 0).cpu().numpy()
+            assert hz.rel_err_rows(got, ln(want(x))).max() < 2e-5, (bias, t)
+            assert hz.rel_err_rows(got, orc.dump["A_self"][0]).max() < 2e-5, (bias, t)
+            assert hz.rel_err_rows(logits.cpu().numpy(), lo).max() <= F32_TOL
+        gpu.close()
+
+
 # ------------------------------------------------------- stand-alone beam step
 @pytest.mark.parametrize("V,beam,k", [(1000, 1, 1), (2004, 4, 4), (32000, 4, 4), (32000, 5, 20), (40000, 2, 3)])
 def test_topk_kernel_against_oracle_same_inputs(V, beam, k):

@@ -405,6 +405,154 @@ def test_aan_step0_mean_is_input_and_matches_averaging_matrix():
     assert np.allclose(orc.aan_sum[0] / 4.0, avg[:, -1], atol=1e-13)
 
 
+# ---- the AAN gate (Tab. 6 rows "+AAN"): pins that do not repeat the oracle's formula
+def _ln_torch(v, g, b, eps=1e-5):
+    return torch.nn.functional.layer_norm(torch.from_numpy(v), (v.shape[-1],), torch.from_numpy(g),
+                                          torch.from_numpy(b), eps).numpy()
+
+
+def _gate_fixture(d=8, rows=3, seed=11):
+    """An oracle whose only meaningful tensors are the gate and LayerNorm of decoder layer 0."""
+    cfg = wl.get_config("tiny", self_kind="aan", d=d, H=2, F=16)
+    w = {k: v.astype(np.float64) for k, v in wl.make_weights(cfg, seed=seed).items()}
+    rng = np.random.default_rng(seed)
+    w["dec0.ln1.g"] = 1.0 + 0.3 * rng.standard_normal(d)
+    w["dec0.ln1.b"] = 0.2 * rng.standard_normal(d)
+    # magnitudes of at least 1/2, so that a gate fed 100 * value is saturated to rounding
+    x = rng.standard_normal((rows, d))
+    g = rng.standard_normal((rows, d))
+    x, g = x + 0.5 * np.sign(x), g + 0.5 * np.sign(g)
+    return cfg, w, x, g
+
+
+def _gate_pins(oracle_cls):
+    """Every closed form the written-down AAN gate must satisfy; returns the names of those that fail.
+    Block structure of W_g [2d out, 2d in]: out rows 0..d-1 = input gate i, d..2d-1 = forget gate f;
+    in columns 0..d-1 multiply the layer input x, d..2d-1 the averaged-and-transformed state g."""
+    failed = []
+    cfg, w, x, g = _gate_fixture()
+    d = cfg["d"]
+    lng, lnb = w["dec0.ln1.g"], w["dec0.ln1.b"]
+
+    def run(wg, bg):
+        w2 = dict(w)
+        w2["dec0.aan.wg"], w2["dec0.aan.bg"] = wg, bg
+        return oracle_cls(cfg, w2, [1, 1], [2])._aan_gate(0, x, g)
+
+    def check(name, got, want, tol=1e-12):
+        if not np.allclose(got, want, atol=tol, rtol=0):
+            failed.append(name)
+
+    Z, I, z1 = np.zeros((2 * d, 2 * d)), np.eye(d), np.zeros(2 * d)
+    # no gate weights, no bias: both gates are 1/2
+    check("half_gates", run(Z, z1), _ln_torch(1.5 * x + 0.5 * g, lng, lnb))
+    # saturating biases: i = 1, f = 0  ->  LN(2 x);  mirrored: i = 0, f = 1  ->  LN(x + g)
+    b_if = np.concatenate([np.full(d, 40.0), np.full(d, -40.0)])
+    check("i_open_f_closed", run(Z, b_if), _ln_torch(2.0 * x, lng, lnb), 1e-14)
+    check("i_closed_f_open", run(Z, -b_if), _ln_torch(x + g, lng, lnb), 1e-14)
+    # one block of W_g at a time, 100 * identity: that gate becomes a step function of x or of g
+    def blocks(P=0, Q=0, R=0, S=0):
+        wg = Z.copy()
+        wg[:d, :d], wg[:d, d:], wg[d:, :d], wg[d:, d:] = P * I, Q * I, R * I, S * I
+        return wg
+    sx, sg = (x > 0).astype(np.float64), (g > 0).astype(np.float64)
+    check("i_from_x", run(blocks(P=100.0), z1), _ln_torch(x + sx * x + 0.5 * g, lng, lnb))
+    check("i_from_g", run(blocks(Q=100.0), z1), _ln_torch(x + sg * x + 0.5 * g, lng, lnb))
+    check("f_from_x", run(blocks(R=100.0), z1), _ln_torch(1.5 * x + sx * g, lng, lnb))
+    check("f_from_g", run(blocks(S=100.0), z1), _ln_torch(1.5 * x + sg * g, lng, lnb))
+    # a full asymmetric W_g, recomputed with scalar loops and math.exp on a 2 x 4 problem
+    cfg4, w4, x4, g4 = _gate_fixture(d=4, rows=2, seed=12)
+    rng = np.random.default_rng(5)
+    wg, bg = rng.standard_normal((8, 8)), rng.standard_normal(8)
+    w4["dec0.aan.wg"], w4["dec0.aan.bg"] = wg, bg
+    got = oracle_cls(cfg4, w4, [1, 1], [2])._aan_gate(0, x4, g4)
+    pre = np.zeros((2, 4))
+    for r in range(2):
+        for c in range(4):
+            zi, zf = bg[c], bg[4 + c]
+            for k in range(4):
+                zi += wg[c, k] * x4[r, k] + wg[c, 4 + k] * g4[r, k]
+                zf += wg[4 + c, k] * x4[r, k] + wg[4 + c, 4 + k] * g4[r, k]
+            pre[r, c] = x4[r, c] + x4[r, c] / (1.0 + math.exp(-zi)) + g4[r, c] / (1.0 + math.exp(-zf))
+    check("scalar_loops", got, _ln_torch(pre, w4["dec0.ln1.g"], w4["dec0.ln1.b"]))
+    return failed
+
+
+def test_sigmoid_against_math_exp():
+    for z in (0.0, 1.0, -1.0, 30.0, -30.0, 0.25):
+        assert so.sigmoid(np.float64(z)) == pytest.approx(1.0 / (1.0 + math.exp(-z)), rel=1e-15)
+    assert so.sigmoid(np.float64(0.0)) == 0.5
+    assert so.sigmoid(np.float64(30.0)) > 1 - 1e-12 and so.sigmoid(np.float64(-30.0)) < 1e-12
+    v = so.sigmoid(np.array([-2.0, 2.0]))
+    assert v[0] + v[1] == pytest.approx(1.0, abs=1e-15) and v[1] > v[0]
+
+
+def test_aan_gate_closed_forms():
+    assert _gate_pins(so.SanOracle) == []
+
+
+def test_aan_gate_pins_catch_planted_mistakes():
+    """The pins above must turn red for each plausible mistake in the gate (planted here, in
+    copies of the oracle on the CPU): gate halves swapped, [x; g] order swapped, sigmoid of +z
+    in place of -z, W_g applied transposed."""
+    class SwapHalves(so.SanOracle):
+        def _aan_gate(self, n, x, g):
+            z = so.linear(np.concatenate([x, g], -1), self.w[f"dec{n}.aan.wg"], self.w[f"dec{n}.aan.bg"])
+            f_gate, i_gate = so.sigmoid(z[..., : self.d]), so.sigmoid(z[..., self.d:])
+            return self._ln(f"dec{n}.ln1", x + i_gate * x + f_gate * g)
+
+    class SwapConcat(so.SanOracle):
+        def _aan_gate(self, n, x, g):
+            z = so.linear(np.concatenate([g, x], -1), self.w[f"dec{n}.aan.wg"], self.w[f"dec{n}.aan.bg"])
+            i_gate, f_gate = so.sigmoid(z[..., : self.d]), so.sigmoid(z[..., self.d:])
+            return self._ln(f"dec{n}.ln1", x + i_gate * x + f_gate * g)
+
+    class WrongSigmoid(so.SanOracle):
+        def _aan_gate(self, n, x, g):
+            z = so.linear(np.concatenate([x, g], -1), self.w[f"dec{n}.aan.wg"], self.w[f"dec{n}.aan.bg"])
+            i_gate, f_gate = 1 / (1 + np.exp(z[..., : self.d])), 1 / (1 + np.exp(z[..., self.d:]))
+            return self._ln(f"dec{n}.ln1", x + i_gate * x + f_gate * g)
+
+    class Transposed(so.SanOracle):
+        def _aan_gate(self, n, x, g):
+            z = np.concatenate([x, g], -1) @ self.w[f"dec{n}.aan.wg"] + self.w[f"dec{n}.aan.bg"]
+            i_gate, f_gate = so.sigmoid(z[..., : self.d]), so.sigmoid(z[..., self.d:])
+            return self._ln(f"dec{n}.ln1", x + i_gate * x + f_gate * g)
+
+    class NoResidual(so.SanOracle):
+        def _aan_gate(self, n, x, g):
+            z = so.linear(np.concatenate([x, g], -1), self.w[f"dec{n}.aan.wg"], self.w[f"dec{n}.aan.bg"])
+            i_gate, f_gate = so.sigmoid(z[..., : self.d]), so.sigmoid(z[..., self.d:])
+            return self._ln(f"dec{n}.ln1", i_gate * x + f_gate * g)
+
+    for cls in (SwapHalves, SwapConcat, WrongSigmoid, Transposed, NoResidual):
+        assert _gate_pins(cls) != [], cls.__name__
+
+
+def test_aan_layer_through_decode_step_closed_form():
+    """The whole AAN self layer as decode_step runs it, at steps 0 and 1, with the layer's FFN
+    output made a known constant (w2 = 0, so g = b2) and the gates saturated: the layer output
+    (the oracle's A_self dump) is LN(2 x) resp. LN(x + b2), x = the scaled embedding + position."""
+    cfg = wl.get_config("tiny", self_kind="aan")
+    w = {k: v.copy() for k, v in wl.make_weights(cfg, seed=2).items()}
+    d = cfg["d"]
+    w["dec0.aan.w2"][:] = 0.0
+    w["dec0.aan.wg"][:] = 0.0
+    src, lens = wl.make_source(cfg, 0)
+    toks = np.array([[1, 9], [1, 12]])
+    pe = _pe_independent(2, d).numpy()
+    lng, lnb = w["dec0.ln1.g"].astype(np.float64), w["dec0.ln1.b"].astype(np.float64)
+    b2 = w["dec0.aan.b2"].astype(np.float64)
+    for sign, want in ((+1.0, lambda x: 2.0 * x), (-1.0, lambda x: x + b2)):
+        w["dec0.aan.bg"] = np.concatenate([np.full(d, 40.0 * sign), np.full(d, -40.0 * sign)]).astype(np.float32)
+        orc = make_oracle(cfg, w, [1, 1], [2])
+        orc.encode(src, lens)
+        for t in range(2):
+            orc.decode_step(toks[:, t])
+            x = w["tgt_emb"][toks[:, t]].astype(np.float64) * math.sqrt(d) + pe[t]
+            assert np.allclose(orc.dump["A_self"][0], _ln_torch(want(x), lng, lnb), atol=1e-12)
+
+
 # --------------------------------------------------------------------- search
 def test_topk_brute_force_and_tie_break():
     cfg = wl.get_config("tiny", V=7, batch=2, beam=3)
