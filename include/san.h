@@ -58,7 +58,8 @@ enum { SAN_SHARE_A = 0, SAN_SHARE_S = 1 };   /* enc-dec blocks: reuse A = S V (E
                                                 per-layer V (Tab. 4, row "shared V: no")              */
 
 /* which tensor san_debug_get copies out */
-enum { SAN_DBG_S_SELF = 0, SAN_DBG_A_SELF = 1, SAN_DBG_S_CTX = 2, SAN_DBG_A_CTX = 3, SAN_DBG_HIDDEN = 4 };
+enum { SAN_DBG_S_SELF = 0, SAN_DBG_A_SELF = 1, SAN_DBG_S_CTX = 2, SAN_DBG_A_CTX = 3, SAN_DBG_HIDDEN = 4,
+       SAN_DBG_ENC_OUT = 5, SAN_DBG_MEM = 6 };
 
 typedef struct {
   int32_t n_enc_layers, n_dec_layers;
@@ -73,7 +74,8 @@ typedef struct {
   int32_t encdec_share;/* SAN_SHARE_A | SAN_SHARE_S                                   */
   int32_t use_cache;   /* 1: key/value cache (Sec. 4.1 baseline); 0: recompute every
                           target position at every step (Tab. 6 row "-Cache")         */
-  int32_t pad_id, bos_id, eos_id; /* eos_id < 0 switches EOS handling off in san_topk */
+  int32_t pad_id, bos_id, eos_id; /* word ids in [0, vocab); eos_id < 0 switches EOS handling
+                                     off in san_topk                                          */
   int32_t debug;       /* 1: keep per-layer S / A / hidden copies for san_debug_get   */
   float ln_eps;        /* LayerNorm epsilon                                           */
 } san_config;
@@ -166,7 +168,14 @@ SAN_API int san_beam_reorder(san_ctx* ctx, const int32_t* parent_idx_dev);
  * Needs cfg.debug = 1 and use_cache = 1.
  *   SAN_DBG_S_SELF: fp32 [rows][heads][n], n = steps done (weights the layer used)
  *   SAN_DBG_S_CTX : fp32 [rows][heads][max_src] (entries >= src_len are 0)
- *   SAN_DBG_A_SELF / A_CTX / HIDDEN: fp32 [rows][d_model]
+ *   SAN_DBG_A_SELF / A_CTX / HIDDEN: fp32 [rows][d_model] (with SAN_SELF_AAN, A_SELF is
+ *     the output of the whole average-attention sub-layer)
+ * and of the last san_encode (available before the first decode step):
+ *   SAN_DBG_ENC_OUT: fp32 [batch][max_src][d_model], the encoder output (`layer` ignored
+ *     but must be valid)
+ *   SAN_DBG_MEM    : fp32 [batch][max_src][2 d_model] = [K | V], the encoder-decoder
+ *     keys/values of a block head (Sec. 3.2), or [batch][max_src][d_model] = V of a
+ *     follower with SAN_SHARE_S; SAN_EINVAL for a layer that keeps none (Eq. 5 followers)
  * Errors: SAN_ESTATE, SAN_EINVAL (layer, what, cap too small). */
 SAN_API int san_debug_get(san_ctx* ctx, int32_t what, int32_t layer, void* dst_dev, size_t cap);
 

@@ -18,7 +18,7 @@ SAN_OK, SAN_EINVAL, SAN_EPOLICY, SAN_ESTATE, SAN_ECAPACITY, SAN_EHIP, SAN_ENOMEM
 SAN_F32, SAN_BF16 = 0, 1
 SAN_SELF_DOT, SAN_SELF_AAN = 0, 1
 SAN_SHARE_A, SAN_SHARE_S = 0, 1
-SAN_DBG_S_SELF, SAN_DBG_A_SELF, SAN_DBG_S_CTX, SAN_DBG_A_CTX, SAN_DBG_HIDDEN = range(5)
+SAN_DBG_S_SELF, SAN_DBG_A_SELF, SAN_DBG_S_CTX, SAN_DBG_A_CTX, SAN_DBG_HIDDEN, SAN_DBG_ENC_OUT, SAN_DBG_MEM = range(7)
 
 EXPORTS = ["san_weight_bytes", "san_init", "san_encode", "san_rewind", "san_decode_step", "san_topk",
            "san_beam_reorder", "san_debug_get", "san_step", "san_device_bytes", "san_last_launch_count",
@@ -54,6 +54,15 @@ class SanError(RuntimeError):
 _lib = None
 
 
+def lib_state() -> dict:
+    """Which sources the loaded library was built from: the hash recorded by build.py next to
+    libsan.so, the hash of the sources in the tree now, and whether they differ (a library
+    older than csrc/ -- built binaries are not part of the history, so nothing else records it)."""
+    from . import build
+    now, then = build.source_hash(), build.built_from()
+    return {"source_hash": now, "built_from": then, "stale": now != then}
+
+
 def lib():
     """Load libsan.so (built in-tree by build.py).  Fails loudly if it is missing."""
     global _lib
@@ -61,6 +70,11 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is not built; run `python -m paper_1906_11024_amd.build`")
         l = C.CDLL(LIB_PATH)
+        st = lib_state()
+        if st["stale"]:
+            import warnings
+            warnings.warn(f"libsan.so was built from sources {st['built_from'] or '(no record)'} but the tree holds "
+                          f"{st['source_hash']}: run `python -m paper_1906_11024_amd.build`", RuntimeWarning)
         vp, i32, f32p, i32p = C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p
         l.san_weight_bytes.restype = C.c_size_t
         l.san_weight_bytes.argtypes = [C.POINTER(SanConfig)]
@@ -193,6 +207,7 @@ class San:
         batch, max_src = src_ids.shape
         self._check(self._l.san_encode(self._h, self._p(src_ids), self._p(src_len), batch, max_src))
         self.batch = batch
+        self.batch_encoded = batch
         self.max_src_of_batch = max_src
         self.rows = batch * self.cfg.beam
 
@@ -244,7 +259,7 @@ class San:
         self._want(parent, self._torch.int32, self.rows)
         self._check(self._l.san_beam_reorder(self._h, self._p(parent)))
 
-    def debug_get(self, what, layer):
+    def debug_get(self, what, layer, follower=False):
         torch = self._torch
         n = self.step
         H, d = self.cfg.n_heads, self.cfg.d_model
@@ -252,6 +267,11 @@ class San:
             shape = (self.rows, H, n)
         elif what == SAN_DBG_S_CTX:
             shape = (self.rows, H, self.max_src_of_batch)
+        elif what == SAN_DBG_ENC_OUT:
+            shape = (self.batch_encoded, self.max_src_of_batch, d)
+        elif what == SAN_DBG_MEM:
+            # a block head keeps [K | V]; a follower that shares only the weights keeps its own V
+            shape = (self.batch_encoded, self.max_src_of_batch, d if follower else 2 * d)
         else:
             shape = (self.rows, d)
         out = torch.empty(shape, dtype=torch.float32, device="cuda")

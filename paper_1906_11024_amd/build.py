@@ -1,6 +1,7 @@
 """Compile the HIP sources in csrc/ into libsan.so (gfx950), in-tree."""
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 import sys
@@ -13,6 +14,31 @@ SOURCES = ["san.hip", "gemm.hip", "attention.hip", "rowwise.hip", "topk.hip", "p
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]
+
+
+HASH_FILE = LIB + ".srchash"   # hash of the sources the library was built from, written beside it
+
+
+def source_hash() -> str:
+    """sha256 over everything the library is compiled from: csrc/, the public header, the flags."""
+    h = hashlib.sha256()
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h")))
+    files.append(os.path.join(os.path.dirname(HERE), "include", "san.h"))
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    h.update(" ".join(FLAGS + SOURCES).encode())
+    return h.hexdigest()[:16]
+
+
+def built_from() -> str:
+    """Source hash recorded when the library was last built ('' if there is no record)."""
+    try:
+        with open(HASH_FILE) as fh:
+            return fh.read().strip()
+    except OSError:
+        return ""
 
 
 def _compile(src: str, objdir: str) -> str:
@@ -28,6 +54,8 @@ def _compile(src: str, objdir: str) -> str:
 
 
 def build(verbose: bool = True) -> str:
+    if os.path.exists(HASH_FILE):
+        os.remove(HASH_FILE)   # a failed build must not leave a record that matches
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
@@ -36,6 +64,8 @@ def build(verbose: bool = True) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
+    with open(HASH_FILE, "w") as fh:
+        fh.write(source_hash() + "\n")
     if verbose:
         print(f"built {LIB}")
     return LIB

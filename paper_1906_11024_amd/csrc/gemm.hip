@@ -18,6 +18,8 @@
 // every epilogue store writes whole 128-byte row segments (16-byte stores per lane
 // with the roles swapped measured slower on the wide output layer: each store
 // instruction then touched 64 different cache lines).
+#include <atomic>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -321,12 +323,18 @@ static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
   dim3 grid((p.N + BN - 1) / BN, (p.M + BM - 1) / BM, p.ksplit);
   const size_t smem = (size_t)KW * 2 * (BM + BN) * kRowBytes;
   if (smem > 64 * 1024) {
-    static bool raised = false;   // the limit is a per-function attribute; set it once
-    if (!raised) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, WM, WN, TM, TN, KW, D, CB>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    // the limit is an attribute of the function on each device: set it once per device
+    // (bit = device ordinal; a second thread that races here only sets it twice)
+    static std::atomic<unsigned long long> raised{0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (!(raised.load(std::memory_order_acquire) & bit)) {
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, WM, WN, TM, TN, KW, D, CB>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
       if (e != hipSuccess) return e;
-      raised = true;
+      raised.fetch_or(bit, std::memory_order_release);
     }
   }
   GemmParams q = p;

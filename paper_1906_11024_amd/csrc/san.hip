@@ -72,6 +72,7 @@ struct san_ctx {
   float* part = nullptr;
   size_t part_elems = 0;
   float* aan_all = nullptr;   // AAN running sums [layer][rows_max][d]
+  float* dbg_enc = nullptr;   // debug copy of the encoder output [batch*max_src][d]
   // policy learning: running JS sums [2][L][L] (self, enc-dec), per-pair scratch, sample counts
   double* js_acc = nullptr;
   float* js_part = nullptr;
@@ -231,6 +232,9 @@ const char* check_config(const san_config& c) {
   if (!c.use_cache && c.self_kind == SAN_SELF_AAN) return "the un-cached mode supports dot-product self-attention only";
   if (!c.use_cache && c.debug) return "debug copies need use_cache = 1";
   if (!(c.ln_eps > 0.f)) return "ln_eps must be > 0";
+  if (c.pad_id < 0 || c.pad_id >= c.vocab || c.bos_id < 0 || c.bos_id >= c.vocab)
+    return "pad_id and bos_id must be word ids in [0, vocab)";
+  if (c.eos_id >= c.vocab) return "eos_id must be below vocab (negative: EOS handling off)";
   if ((long long)c.max_batch * c.beam * (long long)c.max_tgt_len > (1ll << 30)) return "batch*beam*max_tgt_len too large";
   return nullptr;
 }
@@ -477,6 +481,7 @@ static int build_ctx(san_ctx* c, const Blob& bl, const void* blob, const std::ve
         TRY(dalloc(c, (void**)&L.dbg_hidden, (size_t)c->rows_max * d * 4, false));
       }
     }
+    if (cfg->debug) TRY(dalloc(c, (void**)&c->dbg_enc, (size_t)c->rows_src_max * d * 4, false));
     // workspaces, sized for the largest row count any call uses
     size_t mrows = drows > (size_t)c->rows_src_max ? drows : (size_t)c->rows_src_max;
     const size_t wide = F > 2 * d ? F : 2 * d;
@@ -570,6 +575,7 @@ int san_init(const san_config* cfg, const void* weights_host, size_t weight_byte
   if (rc) {
     g_init_error = c->err;
     for (void* p : c->allocs) (void)hipFree(p);
+    if (c->done_host) (void)hipHostFree(c->done_host);
     delete c;
     return rc;
   }
@@ -619,6 +625,7 @@ int san_encode(san_ctx* c, const int32_t* src_ids_dev, const int32_t* src_len_de
     if ((rc = ffn_block(c, nullptr, &e, Ms, nullptr))) return rc;
     c->kind = SAN_K_MISC;
   }
+  if (c->dbg_enc) LAUNCH(c, launch_to_f32(c->dt, c->x, d, c->dbg_enc, Ms, d, c->stream));
   // encoder-decoder keys/values: block heads get [K;V]; in mode S every follower gets its own V
   for (DecLayer& L : c->dec) {
     if (!L.mem) continue;
@@ -899,10 +906,22 @@ int san_beam_reorder(san_ctx* c, const int32_t* parent_idx_dev) {
 int san_debug_get(san_ctx* c, int32_t what, int32_t layer, void* dst_dev, size_t cap) {
   if (!c) return SAN_EINVAL;
   if (!c->cfg.debug) return fail(c, SAN_ESTATE, "san_debug_get needs cfg.debug = 1");
-  if (c->t < 1) return fail(c, SAN_ESTATE, "san_debug_get before the first decode step");
   if (!dst_dev || layer < 0 || layer >= (int)c->dec.size()) return fail(c, SAN_EINVAL, "san_debug_get: bad argument");
-  const int B = c->batch * c->cfg.beam;
   DecLayer& L = c->dec[layer];
+  if (what == SAN_DBG_ENC_OUT || what == SAN_DBG_MEM) {   // written by san_encode
+    if (c->t < 0) return fail(c, SAN_ESTATE, "san_debug_get before san_encode");
+    const int Ms = c->batch_enc * c->max_src;
+    const int cols = what == SAN_DBG_ENC_OUT ? c->d : (L.wq_c ? 2 * c->d : c->d);
+    if (what == SAN_DBG_MEM && !L.mem) return fail(c, SAN_EINVAL, "san_debug_get: this layer keeps no encoder memory");
+    if (cap < (size_t)Ms * cols * 4) return fail(c, SAN_EINVAL, "san_debug_get: destination too small");
+    if (what == SAN_DBG_ENC_OUT)
+      HIP_TRY(c, hipMemcpyAsync(dst_dev, c->dbg_enc, (size_t)Ms * cols * 4, hipMemcpyDeviceToDevice, c->stream));
+    else
+      HIP_TRY(c, launch_to_f32(c->dt, L.mem, cols, (float*)dst_dev, Ms, cols, c->stream));
+    return SAN_OK;
+  }
+  if (c->t < 1) return fail(c, SAN_ESTATE, "san_debug_get before the first decode step");
+  const int B = c->batch * c->cfg.beam;
   const float* src = nullptr;
   switch (what) {
     case SAN_DBG_S_SELF: {

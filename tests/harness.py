@@ -37,7 +37,10 @@ class Lockstep:
     never interact) and is forced onto the GPU's beam choices after each step, so
     that one near-tie cannot cascade.  Each step records the logits error on the
     subset's rows and checks that the GPU's beam choice is a valid top-k of the
-    oracle's scores within `tie_tol`."""
+    oracle's scores within a tolerance: either the absolute `tie_tol`, or the one that follows
+    from the logits bound `logit_tol` asserted on the same step -- a log-probability moves by
+    at most twice the largest logit error of its row (once directly, once through the
+    log-sum-exp), i.e. 2 * logit_tol * max|o|, plus the fp32 rounding of the running score."""
 
     def __init__(self, gpu, orc, src, lens, beam, subset=None, bos_id=wl.BOS_ID):
         import torch
@@ -67,7 +70,8 @@ class Lockstep:
         self.rows = (self.subset[:, None] * beam + np.arange(beam)[None, :]).reshape(-1)
         self.log = {"logit_err": [], "exact": [], "margin": [], "tokens": [], "parents": [], "scores": []}
 
-    def step(self, tie_tol, forced_tokens=None):
+    def step(self, tie_tol=None, forced_tokens=None, logit_tol=None):
+        assert (tie_tol is None) != (logit_tol is None)
         torch, gpu, orc, beam = self.torch, self.gpu, self.orc, self.beam
         rows, V = self.rows, self.V
         gpu.decode_step(self.tokens, self.logits)
@@ -88,6 +92,11 @@ class Lockstep:
             lp_o[done, orc.eos_id] = 0.0
         exact = True
         for i, b in enumerate(self.subset):
+            if logit_tol is not None:
+                live_cum = cum_np[b * beam:(b + 1) * beam]
+                live_cum = np.abs(live_cum[np.isfinite(live_cum)])
+                tie_tol = (2 * logit_tol * np.abs(lo[i * beam:(i + 1) * beam]).max()
+                           + 4 * np.finfo(np.float32).eps * (live_cum.max() if live_cum.size else 0.0) + 1e-6)
             pl = par_g[b] - b * beam                       # local beam index of each pick
             assert ((pl >= 0) & (pl < beam)).all() and ((tok_g[b] >= 0) & (tok_g[b] < V)).all()
             flat = pl * V + tok_g[b]
@@ -169,14 +178,35 @@ def gpu_free_run(gpu, src, lens, beam, steps, bos_id=wl.BOS_ID, keep_logits=Fals
     return out
 
 
-def pick_seed_with_margin(cfg, self_pi, encdec_pi, share, steps, beam, min_margin, sharp=1.0, tries=20):
-    """First seed whose oracle search never meets a top-k margin below
-    min_margin (so fp32 rounding cannot flip a beam decision)."""
-    for seed in range(tries):
+def smallest_score_gap(out, batch, beam):
+    """Smallest difference between two consecutive kept scores of a sentence over an oracle
+    search (the order inside the kept set is part of what a bit-exact comparison checks)."""
+    gap = np.inf
+    for sc in out["scores"]:
+        s = np.asarray(sc).reshape(batch, beam)
+        d = s[:, :-1] - s[:, 1:]
+        d = d[np.isfinite(d)]
+        if d.size:
+            gap = min(gap, float(d.min()))
+    return gap
+
+
+def pick_seed_with_margin(cfg, self_pi, encdec_pi, share, steps, beam, min_margin, sharp=1.0, tries=20,
+                          eos_id=-1, out_scale=1.0, src_clip=None, seeds=None, accept=None, min_gap=0.0):
+    """First seed whose oracle search never meets a top-k margin below min_margin (so fp32
+    rounding cannot flip a beam decision), nor two kept scores closer than min_gap.
+    out_scale multiplies the output embedding (spreads the scores); src_clip caps the source
+    ids (tiny vocabularies); accept(out) may ask for more (e.g. that sentences finish)."""
+    for seed in (range(tries) if seeds is None else seeds):
         w = wl.make_weights(cfg, seed=seed, sharp=sharp)
+        if out_scale != 1.0:
+            w["w_out"] = w["w_out"] * np.float32(out_scale)
         src, lens = wl.make_source(cfg, seed)
-        orc = make_oracle(cfg, w, self_pi, encdec_pi, share)
+        if src_clip is not None:
+            src = np.minimum(src, src_clip)
+        orc = make_oracle(cfg, w, self_pi, encdec_pi, share, eos_id=eos_id)
         out = orc.search(src, lens, steps, beam)
-        if out["margin"] > min_margin:
+        if out["margin"] > min_margin and smallest_score_gap(out, src.shape[0], beam) > min_gap \
+                and (accept is None or accept(out)):
             return seed, w, src, lens, out
     raise RuntimeError("no seed with a safe margin")

@@ -22,6 +22,13 @@ def lib():
     return sb.lib()
 
 
+def test_library_is_built_from_the_current_sources(lib):
+    """the binary that the GPU tests and the benchmark will load is the one csrc/ describes"""
+    st = sb.lib_state()
+    assert st["built_from"], "no build record next to libsan.so: run python -m paper_1906_11024_amd.build"
+    assert not st["stale"], st
+
+
 def test_exports_match_header(lib):
     hdr = open(os.path.join(ROOT, "include", "san.h")).read()
     declared = re.findall(r"SAN_API\s+[\w\s\*]+?\b(san_\w+)\s*\(", hdr)
@@ -65,7 +72,8 @@ def _init(lib, sc, self_pi, ctx_pi, nbytes=None, enc_pi=()):
 @pytest.mark.parametrize("field,value", [("d_model", 100), ("d_model", 4096), ("n_heads", 3), ("n_heads", 64),
                                          ("d_ff", 100), ("vocab", 1001), ("beam", 0), ("beam", 33),
                                          ("dtype", 7), ("self_kind", 2), ("encdec_share", 5), ("max_tgt_len", 0),
-                                         ("ln_eps", 0.0), ("n_dec_layers", 0)])
+                                         ("ln_eps", 0.0), ("n_dec_layers", 0), ("pad_id", -1), ("bos_id", 1000),
+                                         ("eos_id", 1000)])
 def test_bad_config_is_einval(lib, field, value):
     sc = sb.make_config(wl.get_config("tiny"))
     setattr(sc, field, value)

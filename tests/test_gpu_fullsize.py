@@ -1,7 +1,15 @@
 """Parity at the full workload sizes, in the launch configuration the benchmark
-times.  The GPU decodes the whole batch; the oracle decodes a sample of the
-sentences (sentences never interact, so a sentence's rows can be computed one by
-one) in lock-step, forced onto the GPU's beam choices."""
+times.  The GPU decodes the whole batch.  First pass: the oracle decodes EVERY
+sentence for the first steps, so that every row tile of the M = 256...1024 GEMMs and
+every workgroup of the attention launches is compared.  Second pass: the oracle decodes
+a sample of the sentences (sentences never interact, so a sentence's rows can be computed
+one by one) for the whole length, in lock-step, forced onto the GPU's beam choices.
+
+Beam decisions: every GPU pick must be a valid top-k of the oracle's scores within the
+tolerance that follows from the logits bound asserted on the same step (see
+harness.Lockstep), and identical wherever the oracle's margins exceed twice that.  For
+fp32 the share of steps whose picks are identical is also asserted; for bf16 it is only
+printed: with a 2e-2 logits tolerance near-ties are the rule, not the exception."""
 import numpy as np
 import pytest
 
@@ -9,11 +17,33 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
+from paper_1906_11024_amd import binding as sb
 from paper_1906_11024_amd import workloads as wl
 from tests import harness as hz
 
 
-def _run(name, subset_n, steps=None, tol=1e-4, tie_tol=5e-4, min_exact=0.8, **over):
+def _lockstep(name, gpu, orc, src, lens, cfg, subset, steps, tol, min_exact, tag):
+    ls = hz.Lockstep(gpu, orc, src, lens, cfg["beam"], subset=subset)
+    for t in range(steps):
+        lg, lo = ls.step(logit_tol=tol)
+        # top-1 word of every compared row agrees wherever the oracle's own margin
+        # is larger than twice the logits tolerance
+        top2 = np.sort(lo, axis=-1)[:, -2:]
+        safe = (top2[:, 1] - top2[:, 0]) > 2 * tol * np.abs(lo).max(-1)
+        assert np.array_equal(lg.argmax(-1)[safe], lo.argmax(-1)[safe]), t
+        if t % 16 == 0:
+            print(f"{name} {tag} step {t} err {ls.log['logit_err'][-1]:.2e}", flush=True)
+    torch.cuda.synchronize()
+    err = max(ls.log["logit_err"])
+    print(f"{name} {tag}: max logits rel err {err:.3e}, identical beam steps {sum(ls.log['exact'])}/{steps}, "
+          f"kernels/step {gpu.last_launch_count}", flush=True)
+    assert err <= tol
+    if min_exact is not None:
+        assert sum(ls.log["exact"]) >= min_exact * steps
+    return ls
+
+
+def _run(name, subset_n, steps=None, tol=1e-4, min_exact=0.8, all_steps=8, share="A", check_encoder=False, **over):
     if not torch.cuda.is_available():
         pytest.fail("needs a GPU")
     cfg = wl.get_config(name, **over)
@@ -23,49 +53,57 @@ def _run(name, subset_n, steps=None, tol=1e-4, tie_tol=5e-4, min_exact=0.8, **ov
     order = np.argsort(lens, kind="stable")
     # shortest, longest and evenly spaced sentences in between
     subset = np.unique(order[np.linspace(0, len(order) - 1, subset_n).astype(int)])
-    gpu = hz.make_gpu(cfg, w)
-    orc = hz.make_oracle(cfg, w)
-    ls = hz.Lockstep(gpu, orc, src, lens, cfg["beam"], subset=subset)
-    for t in range(steps):
-        lg, lo = ls.step(tie_tol=tie_tol)
-        # top-1 word of every sampled row agrees wherever the oracle's own margin
-        # is larger than twice the logits tolerance
-        top2 = np.sort(lo, axis=-1)[:, -2:]
-        safe = (top2[:, 1] - top2[:, 0]) > 2 * tol * np.abs(lo).max(-1)
-        assert np.array_equal(lg.argmax(-1)[safe], lo.argmax(-1)[safe]), t
-        if t % 16 == 0:
-            print(f"{name} step {t} err {ls.log['logit_err'][-1]:.2e}", flush=True)
-    torch.cuda.synchronize()
-    err = max(ls.log["logit_err"])
-    print(f"{name}: max logits rel err {err:.3e}, exact beam steps {sum(ls.log['exact'])}/{steps}, "
-          f"kernels/step {gpu.last_launch_count}", flush=True)
-    assert err <= tol
-    assert sum(ls.log["exact"]) >= min_exact * steps
+    gpu = hz.make_gpu(cfg, w, share=share, debug=1 if check_encoder else 0)
+    orc = hz.make_oracle(cfg, w, share=share)
+    if all_steps:
+        _lockstep(name, gpu, orc, src, lens, cfg, None, all_steps, tol, min_exact, "all sentences")
+        if check_encoder:
+            # row E: the encoder output and the encoder-decoder keys/values themselves (the
+            # oracle has just encoded the whole batch)
+            valid = np.arange(src.shape[1])[None, :] < lens[:, None]
+            H_g = gpu.debug_get(sb.SAN_DBG_ENC_OUT, 0).cpu().numpy()
+            assert hz.rel_err_rows(H_g[valid], orc.enc_out[valid]).max() <= tol
+            for n in range(cfg["n_dec"]):
+                if orc.ctx_head[n] != n:
+                    continue
+                kv = gpu.debug_get(sb.SAN_DBG_MEM, n).cpu().numpy()
+                K_o = np.moveaxis(orc.mem_K[n], 1, 2).reshape(src.shape[0], src.shape[1], cfg["d"])
+                V_o = np.moveaxis(orc.mem_V[n], 1, 2).reshape(src.shape[0], src.shape[1], cfg["d"])
+                assert hz.rel_err_rows(kv[..., :cfg["d"]][valid], K_o[valid]).max() <= tol, n
+                assert hz.rel_err_rows(kv[..., cfg["d"]:][valid], V_o[valid]).max() <= tol, n
+    _lockstep(name, gpu, orc, src, lens, cfg, subset, steps, tol, min_exact, f"{len(subset)} sentences")
     gpu.close()
     del w
     torch.cuda.empty_cache()
 
 
-@pytest.mark.timeout(400)
+@pytest.mark.timeout(600)
 def test_base_full_fp32():
-    _run("base", 8)
+    _run("base", 8, check_encoder=True)
 
 
 @pytest.mark.timeout(400)
-def test_base_unshared_and_share_s_fp32():
-    _run("base", 3, steps=24, self_pi=[1] * 6, encdec_pi=[1] * 6)
+def test_base_unshared_fp32():
+    """singleton policies: the standard Transformer (Fig. 3(a)) at the base size"""
+    _run("base", 3, steps=24, all_steps=2, self_pi=[1] * 6, encdec_pi=[1] * 6)
+
+
+@pytest.mark.timeout(400)
+def test_base_share_s_fp32():
+    """enc-dec blocks that share only the weights, each layer with its own V (Tab. 4, "shared V: no")"""
+    _run("base", 3, steps=24, all_steps=4, share="S")
 
 
 @pytest.mark.timeout(600)
 def test_long_full_fp32():
-    _run("long", 3)
+    _run("long", 3, all_steps=4)
 
 
-@pytest.mark.timeout(600)
+@pytest.mark.timeout(900)
 def test_big_full_bf16():
-    _run("big", 3, tol=2e-2, tie_tol=0.2, min_exact=0.0)
+    _run("big", 3, tol=2e-2, min_exact=None)
 
 
-@pytest.mark.timeout(600)
+@pytest.mark.timeout(900)
 def test_aan_full_bf16():
-    _run("aan", 3, tol=2e-2, tie_tol=0.2, min_exact=0.0)
+    _run("aan", 3, tol=2e-2, min_exact=None, all_steps=4)
