@@ -68,7 +68,8 @@ class Lockstep:
         self.o_sc = torch.empty((batch, beam), dtype=torch.float32, device=dev)
         # rows of the subset inside the GPU batch
         self.rows = (self.subset[:, None] * beam + np.arange(beam)[None, :]).reshape(-1)
-        self.log = {"logit_err": [], "exact": [], "margin": [], "tokens": [], "parents": [], "scores": []}
+        self.log = {"logit_err": [], "exact": [], "same_frac": [], "flip_gap": [], "margin": [], "tokens": [],
+                    "parents": [], "scores": []}
 
     def step(self, tie_tol=None, forced_tokens=None, logit_tol=None):
         assert (tie_tol is None) != (logit_tol is None)
@@ -90,7 +91,7 @@ class Lockstep:
             done = tok_in[rows] == orc.eos_id
             lp_o[done, :] = -np.inf
             lp_o[done, orc.eos_id] = 0.0
-        exact = True
+        exact, n_same, flip_gap = True, 0, np.inf
         for i, b in enumerate(self.subset):
             if logit_tol is not None:
                 live_cum = cum_np[b * beam:(b + 1) * beam]
@@ -107,10 +108,16 @@ class Lockstep:
             assert np.all(np.abs(s_true[live] - sc_o[i][live]) <= tie_tol), (b, s_true, sc_o[i])
             assert np.all(np.abs(sc_g[b][live] - s_true[live]) <= tie_tol), (b, sc_g[b], s_true)
             same = np.array_equal(tok_g[b], tok_o[i]) and np.array_equal(pl, par_o[i] - i * beam)
-            if margin[i] > 2 * tie_tol and np.all(np.abs(np.diff(sc_o[i][live])) > 2 * tie_tol):
+            inner = np.abs(np.diff(sc_o[i][live]))
+            if margin[i] > 2 * tie_tol and np.all(inner > 2 * tie_tol):
                 assert same, (b, tok_g[b], tok_o[i], par_g[b], par_o[i])
             exact &= bool(same)
+            n_same += bool(same)
+            if not same:   # the oracle's closest pair of scores in this decision: how near the tie was
+                flip_gap = min(flip_gap, float(min(margin[i], inner.min() if inner.size else np.inf)))
         self.log["exact"].append(exact)
+        self.log["same_frac"].append(n_same / len(self.subset))
+        self.log["flip_gap"].append(flip_gap)
         self.log["margin"].append(float(np.min(margin)))
         # both sides follow the GPU's choice
         parent_g = self.o_par.reshape(-1)
@@ -192,16 +199,17 @@ def smallest_score_gap(out, batch, beam):
 
 
 def pick_seed_with_margin(cfg, self_pi, encdec_pi, share, steps, beam, min_margin, sharp=1.0, tries=20,
-                          eos_id=-1, out_scale=1.0, src_clip=None, seeds=None, accept=None, min_gap=0.0):
+                          eos_id=-1, out_scale=1.0, src_clip=None, seeds=None, accept=None, min_gap=0.0,
+                          src_cfg=None):
     """First seed whose oracle search never meets a top-k margin below min_margin (so fp32
     rounding cannot flip a beam decision), nor two kept scores closer than min_gap.
-    out_scale multiplies the output embedding (spreads the scores); src_clip caps the source
-    ids (tiny vocabularies); accept(out) may ask for more (e.g. that sentences finish)."""
+    out_scale multiplies the output embedding (spreads the scores); the source batch is drawn for
+    src_cfg (default cfg) and its ids capped at src_clip (tiny vocabularies); accept(out) may ask for more (e.g. that sentences finish)."""
     for seed in (range(tries) if seeds is None else seeds):
         w = wl.make_weights(cfg, seed=seed, sharp=sharp)
         if out_scale != 1.0:
             w["w_out"] = w["w_out"] * np.float32(out_scale)
-        src, lens = wl.make_source(cfg, seed)
+        src, lens = wl.make_source(src_cfg or cfg, seed)
         if src_clip is not None:
             src = np.minimum(src, src_clip)
         orc = make_oracle(cfg, w, self_pi, encdec_pi, share, eos_id=eos_id)

@@ -8,8 +8,8 @@ one by one) for the whole length, in lock-step, forced onto the GPU's beam choic
 Beam decisions: every GPU pick must be a valid top-k of the oracle's scores within the
 tolerance that follows from the logits bound asserted on the same step (see
 harness.Lockstep), and identical wherever the oracle's margins exceed twice that.  For
-fp32 the share of steps whose picks are identical is also asserted; for bf16 it is only
-printed: with a 2e-2 logits tolerance near-ties are the rule, not the exception."""
+fp32 the share of (sentence, step) decisions that are identical is also asserted; for bf16
+it is only printed: with a 2e-2 logits tolerance near-ties are the rule, not the exception."""
 import numpy as np
 import pytest
 
@@ -35,15 +35,17 @@ def _lockstep(name, gpu, orc, src, lens, cfg, subset, steps, tol, min_exact, tag
             print(f"{name} {tag} step {t} err {ls.log['logit_err'][-1]:.2e}", flush=True)
     torch.cuda.synchronize()
     err = max(ls.log["logit_err"])
-    print(f"{name} {tag}: max logits rel err {err:.3e}, identical beam steps {sum(ls.log['exact'])}/{steps}, "
+    same = float(np.mean(ls.log["same_frac"]))
+    print(f"{name} {tag}: max logits rel err {err:.3e}, beam decisions identical to the oracle's: {same:.4f} of "
+          f"(sentence, step) pairs, closest oracle score pair among the others {min(ls.log['flip_gap']):.2e}, "
           f"kernels/step {gpu.last_launch_count}", flush=True)
     assert err <= tol
     if min_exact is not None:
-        assert sum(ls.log["exact"]) >= min_exact * steps
+        assert same >= min_exact
     return ls
 
 
-def _run(name, subset_n, steps=None, tol=1e-4, min_exact=0.8, all_steps=8, share="A", check_encoder=False, **over):
+def _run(name, subset_n, steps=None, tol=1e-4, min_exact=0.98, all_steps=8, share="A", check_encoder=False, **over):
     if not torch.cuda.is_available():
         pytest.fail("needs a GPU")
     cfg = wl.get_config(name, **over)

@@ -537,7 +537,7 @@ def _eos_case(batch, beam, T, seeds, accept):
     cfg = mid_cfg(steps=T, V=V, batch=batch, beam=beam)
     seed, w, src, lens, ref = hz.pick_seed_with_margin(cfg, cfg["self_pi"], cfg["encdec_pi"], "A", T, beam, 5e-4,
                                                        eos_id=wl.EOS_ID, src_clip=V - 1, seeds=seeds, accept=accept,
-                                                       min_gap=5e-4)
+                                                       min_gap=5e-4, src_cfg=mid_cfg(batch=batch))
     done = np.stack([(ref["tokens"][t].reshape(batch, beam) == wl.EOS_ID).all(axis=1) for t in range(T)])
     return cfg, seed, w, src, lens, ref, done
 
