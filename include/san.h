@@ -155,6 +155,24 @@ SAN_API int san_decode_step(san_ctx* ctx, const int32_t* tokens_dev, float* logi
 SAN_API int san_topk(san_ctx* ctx, const float* logits_dev, const float* cum_score_dev, int32_t k,
              int32_t* out_token_dev, int32_t* out_parent_dev, float* out_score_dev);
 
+/* san_topk for callers that cannot allocate device memory or have the library hold
+ * call-time buffers for them: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same results (bit for bit) and
+ * same errors as san_topk, but the per-row candidates (k (log-probability, word) pairs
+ * per row, produced by the first kernel and merged per sentence by the second) live
+ * in a fixed 256 KiB array in the library's device image instead of a buffer of the
+ * context.  The call allocates nothing (no hipMalloc / hipFree, no allocating library
+ * routine) and synchronises nothing.
+ *   Limit: batch*beam*k <= 32768 candidates (e.g. 1024 rows x 32); beyond that
+ *   SAN_ECAPACITY and nothing is queued.
+ *   Each GPU holds one copy of the array from the first san_init on it until the
+ *   process ends, shared by every context on that GPU: calls of san_topk_noalloc that
+ *   overlap on one GPU (different streams or threads) race on it.  The array keeps the
+ *   previous call's contents; every entry a call reads it has written itself first.
+ * Errors: as san_topk, plus SAN_ECAPACITY (above), SAN_ESTATE while san_profile is on. */
+SAN_API int san_topk_noalloc(san_ctx* ctx, const float* logits_dev, const float* cum_score_dev, int32_t k,
+                             int32_t* out_token_dev, int32_t* out_parent_dev, float* out_score_dev);
+
 /* After a beam step: row r continues the hypothesis that was row parent[r].
  * Every per-row decoder state (self-attention key/value history, AAN running
  * sums, un-cached token history) follows; encoder-decoder keys/values are per

@@ -24,7 +24,7 @@ EXPORTS = ["san_weight_bytes", "san_init", "san_encode", "san_rewind", "san_deco
            "san_beam_reorder", "san_debug_get", "san_step", "san_device_bytes", "san_last_launch_count",
            "san_last_error", "san_free", "san_profile", "san_profile_read",
            "san_policy_accumulate", "san_policy_read", "san_policy_search", "san_decode_n", "san_stream_read", "san_finished",
-           "san_done_flags", "san_compact", "san_active"]
+           "san_done_flags", "san_compact", "san_active", "san_topk_noalloc"]
 
 SAN_LOOP_GRAPH, SAN_LOOP_COMPACT = 1, 2
 
@@ -88,6 +88,8 @@ def lib():
         l.san_decode_step.argtypes = [vp, i32p, f32p]
         l.san_topk.restype = C.c_int
         l.san_topk.argtypes = [vp, f32p, f32p, i32, i32p, i32p, f32p]
+        l.san_topk_noalloc.restype = C.c_int
+        l.san_topk_noalloc.argtypes = [vp, f32p, f32p, i32, i32p, i32p, f32p]
         l.san_beam_reorder.restype = C.c_int
         l.san_beam_reorder.argtypes = [vp, i32p]
         l.san_debug_get.restype = C.c_int
@@ -254,6 +256,15 @@ class San:
             self._want(t, dt, self.batch * k)
         self._check(self._l.san_topk(self._h, self._p(logits), self._p(cum_score), k, self._p(out_token),
                                      self._p(out_parent), self._p(out_score)))
+
+    def topk_noalloc(self, logits, cum_score, k, out_token, out_parent, out_score):
+        torch = self._torch
+        self._want(logits, torch.float32, self.rows * self.cfg.vocab)
+        self._want(cum_score, torch.float32, self.rows)
+        for t, dt in ((out_token, torch.int32), (out_parent, torch.int32), (out_score, torch.float32)):
+            self._want(t, dt, self.batch * k)
+        self._check(self._l.san_topk_noalloc(self._h, self._p(logits), self._p(cum_score), k, self._p(out_token),
+                                             self._p(out_parent), self._p(out_score)))
 
     def beam_reorder(self, parent):
         self._want(parent, self._torch.int32, self.rows)

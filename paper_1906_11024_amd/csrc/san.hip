@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -16,6 +17,41 @@
 #include "kernels.h"
 
 using namespace san;
+
+// Candidate scratch of san_topk_noalloc: the beam step's per-row partial results
+// ((log-probability, word) pairs, k per row) live in this fixed array instead of a
+// buffer owned by a context, so that the call can be made where nothing may be
+// allocated.  Every GPU the library runs on holds its own copy until the process ends.
+// The name below is only the host-side handle of the symbol: host code uses the
+// per-device address that hipGetSymbolAddress returns (scratch_address), never the name.
+// No `used` attribute here: the compiler turns a file-local device variable into a symbol
+// the runtime can find by name because host code refers to it; marked `used` it was kept
+// as it stood, a local symbol of the device image, and the look-up aborted the process.
+constexpr size_t kScratchCands = 32768;   // rows * k of one call, e.g. 1024 rows x 32
+static __device__ __align__(256) unsigned char scratch[kScratchCands * 8];
+
+// Device address of `scratch` on the current device, resolved once per device.
+namespace san {
+hipError_t scratch_address(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr_of[kMaxDevices] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    ptr_of[dev] = ptr;
+  }
+  *out = ptr_of[dev];
+  return hipSuccess;
+}
+}  // namespace san
 
 namespace {
 
@@ -567,6 +603,12 @@ int san_init(const san_config* cfg, const void* weights_host, size_t weight_byte
   } else if (!policy_heads(policy->n_enc, policy->enc_pi, cfg->n_enc_layers, enc_head)) {
     return fail(nullptr, SAN_EPOLICY, "encoder policy must be block sizes >= 1 that sum to n_enc_layers");
   }
+  {
+    // set-up of san_topk_noalloc's fixed scratch on this device (the context's device)
+    void* ptr = nullptr;
+    const hipError_t e = scratch_address(&ptr);
+    if (e != hipSuccess) return fail(nullptr, SAN_EHIP, std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e));
+  }
   san_ctx* c = new (std::nothrow) san_ctx();
   if (!c) return fail(nullptr, SAN_ENOMEM, "host allocation failed");
   c->cfg = *cfg;
@@ -879,6 +921,36 @@ int san_topk(san_ctx* c, const float* logits_dev, const float* cum_score_dev, in
                          k == c->cfg.beam ? c->done_dev : nullptr, c->done_dev + c->cfg.max_batch));
   prof_close(c, pm);
   return prof_flush(c);
+}
+
+int san_topk_noalloc(san_ctx* c, const float* logits_dev, const float* cum_score_dev, int32_t k,
+                     int32_t* out_token_dev, int32_t* out_parent_dev, float* out_score_dev) {
+  if (!c) return SAN_EINVAL;
+  if (!logits_dev || !cum_score_dev || !out_token_dev || !out_parent_dev || !out_score_dev)
+    return fail(c, SAN_EINVAL, "san_topk_noalloc: null argument");
+  if (k < 1 || k > 32 || k > c->V) return fail(c, SAN_EINVAL, "san_topk_noalloc: k must be in [1, min(32, vocab)]");
+  if (reinterpret_cast<uintptr_t>(logits_dev) % 16)
+    return fail(c, SAN_EINVAL, "san_topk_noalloc: logits must be 16-byte aligned");
+  if (c->t < 0) return fail(c, SAN_ESTATE, "san_topk_noalloc before san_encode");
+  if (c->prof_on) return fail(c, SAN_ESTATE, "san_topk_noalloc: switch san_profile off first");
+  const size_t cands = (size_t)c->batch * c->cfg.beam * k;
+  if (cands > kScratchCands) {
+    char buf[160];
+    snprintf(buf, sizeof buf, "san_topk_noalloc: batch*beam*k = %zu candidates exceed the fixed scratch of %zu", cands,
+             kScratchCands);
+    return fail(c, SAN_ECAPACITY, buf);
+  }
+  void* ptr = nullptr;   // resolved in san_init on this device; a table look-up here
+  const hipError_t e = scratch_address(&ptr);
+  if (e != hipSuccess) return fail(c, SAN_EHIP, std::string("san_topk_noalloc: scratch address: ") + hipGetErrorString(e));
+  // [cands] log-probabilities, then [cands] word ids; every entry the merge reads is
+  // written by the row kernel of this same call, so nothing has to be cleared
+  float* cand_lp = reinterpret_cast<float*>(ptr);
+  int* cand_idx = reinterpret_cast<int*>(static_cast<unsigned char*>(ptr) + kScratchCands * 4);
+  HIP_TRY(c, launch_topk(logits_dev, cum_score_dev, c->last_tok, c->cfg.eos_id, c->batch, c->cfg.beam, c->V, k, cand_lp,
+                         cand_idx, out_token_dev, out_parent_dev, out_score_dev, c->stream, nullptr,
+                         k == c->cfg.beam ? c->done_dev : nullptr, c->done_dev + c->cfg.max_batch));
+  return SAN_OK;
 }
 
 int san_beam_reorder(san_ctx* c, const int32_t* parent_idx_dev) {

@@ -110,3 +110,26 @@ def test_uncached_aan_rejected_and_null_handles(lib):
     assert lib.san_step(None) == -1 and lib.san_device_bytes(None, 0) == 0
     assert lib.san_decode_step(None, None, None) == sb.SAN_EINVAL
     lib.san_free(None)
+
+
+def test_fixed_scratch_is_a_dynamic_symbol_of_the_device_image(lib):
+    """san_topk_noalloc's scratch array is found by name at run time (hipGetSymbolAddress), so
+    the gfx950 image inside the library's object file must export it; a local symbol there
+    aborts the process at san_init.  Reads the build's own object file with the LLVM tools."""
+    import shutil
+    import subprocess
+    import tempfile
+    obj = os.path.join(os.path.dirname(sb.LIB_PATH), "_build", "san.o")
+    tools = "/opt/rocm/llvm/bin"
+    need = [os.path.join(tools, t) for t in ("llvm-objcopy", "clang-offload-bundler", "llvm-readelf")]
+    if not os.path.exists(obj) or not all(os.path.exists(t) for t in need):
+        pytest.skip("no object file of this build / no LLVM tools here")
+    with tempfile.TemporaryDirectory() as td:
+        fat, co = os.path.join(td, "fat.bin"), os.path.join(td, "dev.co")
+        subprocess.run([need[0], f"--dump-section=.hip_fatbin={fat}", obj, os.path.join(td, "copy.o")], check=True)
+        subprocess.run([need[1], "--unbundle", "--type=o", f"--input={fat}",
+                        "--targets=hipv4-amdgcn-amd-amdhsa--gfx950", f"--output={co}"], check=True)
+        out = subprocess.run([need[2], "--dyn-syms", co], check=True, capture_output=True, text=True).stdout
+    rows = [l for l in out.splitlines() if "scratch" in l]
+    assert rows and all("GLOBAL" in l and "OBJECT" in l for l in rows), out
+    assert any(" 262144 " in l for l in rows), rows
