@@ -5,18 +5,31 @@ A "step" is one pass of the whole hot path over all batch*beam rows:
 san_decode_step (embedding, every decoder layer under the sharing policy, output
 layer) + san_topk + san_beam_reorder, on the Transformer-base workload (64
 sentences x beam 4, source lengths U[20,60], 64 decode steps per sentence batch,
-fp32, self-attention shared in pairs, enc-dec attention in groups of 3).  K steps
-are timed as K/64 full decodes (the cache grows from 1 to 64 positions in each),
-inputs and weights resident in HBM, the encoder run once beforehand.
+fp32, self-attention shared in pairs, enc-dec attention in groups of 3), inputs and
+weights resident in HBM, the encoder run once beforehand.
+
+What is timed.  The cost of a step grows with the number of cached positions, so a
+timed window must see the same mix of cache lengths as a whole decode:
+  --steps K >= 64 : K is rounded down to whole decodes (the cache grows 1..64 in each);
+  --steps K <  64 : the K positions in the middle of a decode, (64-K)/2 .. (64+K)/2 - 1,
+                    whose mean cache length is the decode's; the run-up to the first of
+                    them is not timed.
+The window is timed REPS times (11 by default), each bracketed by device
+synchronisations, and the median is reported; `steps` stays K.  Every comparison leg
+(unshared, mode S, un-cached ...) is timed over the same positions.
 
 Prints ONE JSON line: metric/value (decoded tokens/s over batch*beam rows), the
 roofline of the dominant attention kernel (HIP events on the library's stream,
-second identical pass), the same kernels under the unshared / share-S / un-cached
-configurations, and the CPU oracle timed on the host cores.
+second identical pass; next to it the rocprofv3 figures kept under profiles/), the
+same kernels under the unshared / share-S / un-cached configurations, a short leg for
+each of the other workloads (long, big, aan), and the CPU oracle timed on the host
+cores over the same window.
 """
 import argparse
+import glob
 import json
 import os
+import re
 import sys
 import time
 
@@ -26,15 +39,6 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
-# HBM bytes per launch (fetch + write) of the dominant attention kernel, from two
-# rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE) of this script with
-# --calib-copy-mb 512, each scaled by what the same counter reads for that plain
-# 512 MiB copy (FETCH_SIZE x2.000, WRITE_SIZE x1.000); see profiles/.  It is BELOW the
-# algorithmic bytes: the hypotheses of a sentence name the same cache rows for most past
-# positions and run on one XCD, so a shared row leaves HBM once and is an L2 hit for the
-# others (with the rows spread over the XCDs the counter read 34.93 + 0.82 MB on base).
-MEASURED_TRAFFIC = {"base": {"attn_self": 11.10e6 + 0.82e6}, "big": {"attn_self": 33.75e6 + 2.75e6},
-                    "aan": {"attn_ctx": 22.46e6 + 1.05e6}}
 
 
 def parse():
@@ -42,17 +46,29 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=640)
     ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--reps", type=int, default=11, help="how often the timed window is repeated (median reported)")
     ap.add_argument("--config", default="base", choices=["tiny", "base", "big", "long", "aan"])
     ap.add_argument("--no-compare", action="store_true", help="skip the unshared / share-S / un-cached runs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
-    ap.add_argument("--cpu-steps", type=int, default=16)
+    ap.add_argument("--no-configs", action="store_true", help="skip the short legs on the other workloads")
+    ap.add_argument("--cpu-steps", type=int, default=20,
+                    help="decode steps the CPU oracle is timed on (the middle of a decode, like a short GPU window)")
     ap.add_argument("--beam-sweep", default="", help="comma-separated beam sizes: also time SAN vs unshared "
                     "cached decoding at these beams (the paper's Fig. 5 axis), e.g. 4,8,12,16,20")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a kernel of known "
                          "traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
+
+
+def window_of(T, steps):
+    """(first position, number of steps, text) of the timed window, see the module docstring."""
+    if steps >= T:
+        k = (steps // T) * T
+        return 0, k, f"{k // T} whole decode(s): positions 0-{T - 1} of {T}, {k // T} time(s) per repetition"
+    p0 = (T - steps) // 2
+    return p0, steps, f"positions {p0}-{p0 + steps - 1} of {T} (the middle of a decode: its mean cache length)"
 
 
 class Runner:
@@ -93,18 +109,23 @@ class Runner:
             g.beam_reorder(self.par[o].view(-1))
             self.pos = (self.pos + 1) % self.T
 
-    def timed(self, k, warmup):
+    def window(self, p0, k, reps, warmup=0):
+        """Median wall time of the k steps that start at position p0 of a decode, over `reps`
+        repetitions; each repetition starts from a rewound decoder and runs up to p0 untimed."""
         torch = self.torch
         self.pos = 0
         self.steps(warmup)
-        # start the timed region at the beginning of a decode
-        while self.pos != 0:
-            self.steps(1)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        self.steps(k)
-        torch.cuda.synchronize()
-        return time.perf_counter() - t0
+        times = []
+        for _ in range(reps):
+            self.pos = 0
+            self.steps(p0)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            self.steps(k)
+            torch.cuda.synchronize()
+            times.append(time.perf_counter() - t0)
+        times.sort()
+        return times[len(times) // 2], times
 
 
 def ragged_finish(torch, gpu, cfg, src, lens, compact, reps=3):
@@ -206,6 +227,93 @@ def step_roofline(cfg, esz, self_pi, ctx_pi, mean_src, ms_per_step):
             "bound_us": bound, "measured_us": ms_per_step * 1e3, "frac": bound / (ms_per_step * 1e3)}
 
 
+def profiled_figures(config, key):
+    """The rocprofv3 figures kept under profiles/ for this workload's dominant kernel: average
+    duration from the --kernel-trace summary, HBM bytes per launch from the two --pmc
+    summaries.  They come from earlier runs of this same command under the profiler, NOT from
+    this run; absent files or lines give None."""
+    role = {"attn_self": "head", "attn_ctx": "ctx", "attn_apply": "apply"}[key]
+    out = {"rocprofv3_avg_us": None, "rocprofv3_source": None, "fetch_MB": None, "write_MB": None,
+           "traffic_source": None}
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", f"attention_and_step_kernels_{config}*.txt"))):
+        for line in open(path):
+            m = re.match(rf"{role}\s+all steps: avg ([0-9.]+) us per launch", line)
+            if m:
+                out["rocprofv3_avg_us"] = float(m.group(1))
+                out["rocprofv3_source"] = "profiles/" + os.path.basename(path)
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", f"attention_hbm_traffic_{config}*.txt"))):
+        counter = None
+        for line in open(path):
+            m = re.match(r"(FETCH_SIZE|WRITE_SIZE):", line)
+            if m:
+                counter = m.group(1)
+            m = re.match(rf"attention {role}\s*:.*->\s*([0-9.]+) MB per launch", line)
+            if m and counter:
+                out["fetch_MB" if counter == "FETCH_SIZE" else "write_MB"] = float(m.group(1))
+                out["traffic_source"] = "profiles/" + os.path.basename(path)
+    return out
+
+
+def kernel_pass(torch, gpu, run, cfg, esz, mean_src, config_name):
+    """Second, identical pass over one decode with every launch bracketed by event markers on
+    the library's stream.  A marker pair costs about 2 us of stream time per launch; that cost
+    is estimated as (sum of bracketed times - unmarked wall time of the same decode) / launches
+    and taken off every launch, so that the per-kernel figures add up to the unmarked step time
+    (the decode is GPU-bound: kernels run back to back).  rocprofv3 --kernel-trace gives the
+    same per-kernel averages (profiles/)."""
+    T = cfg["steps"]
+    wall_T, _ = run.window(0, T, 3)          # unmarked time of exactly one decode
+    run.pos = 0
+    gpu.profile(True)
+    gpu.profile_read(reset=True)
+    run.steps(T)
+    prof = gpu.profile_read(reset=True)
+    gpu.profile(False)
+    raw_ms = sum(ms for ms, n in prof.values())
+    n_pairs = sum(n for ms, n in prof.values())
+    marker_us = max(0.0, (raw_ms - wall_T * 1e3) / n_pairs * 1e3)
+    prof = {k: (max(ms - n * marker_us * 1e-3, 0.0), n) for k, (ms, n) in prof.items()}
+    aan = cfg["self_kind"] == "aan"
+    hs, fs = (0, 0) if aan else (len(cfg["self_pi"]), sum(cfg["self_pi"]) - len(cfg["self_pi"]))
+    hc = len(cfg["encdec_pi"])
+    ab = attention_bytes(cfg, esz, hs, fs, hc, 0, mean_src)
+    gf = gemm_flops_per_step(cfg, hs, fs, hc)
+    kernels = {}
+    for k, (ms, n) in prof.items():
+        if n == 0:
+            continue
+        ent = {"ms_per_step": ms / T, "launches_per_step": n / T, "avg_us": ms / n * 1e3}
+        if k in ab and ab[k] > 0:
+            ent["algo_GBps"] = ab[k] / (ms * 1e-3) / 1e9
+            ent["frac_hbm_peak"] = ent["algo_GBps"] / HBM_PEAK_GBS
+        if k in gf:
+            ent["TFLOPs"] = gf[k] * T / (ms * 1e-3) / 1e12
+            ent["frac_mfma_peak"] = ent["TFLOPs"] / MFMA_PEAK_TFLOPS[cfg["dtype"]]
+        kernels[k] = ent
+    key = "attn_ctx" if aan else "attn_self"
+    ms, n = prof[key]
+    achieved = ab[key] / (ms * 1e-3) / 1e9
+    pf = profiled_figures(config_name, key)
+    traffic = None
+    if pf["fetch_MB"] is not None and pf["write_MB"] is not None:
+        traffic = (pf["fetch_MB"] + pf["write_MB"]) * 1e6
+    roofline = {"kernel": "attention_kernel (block-head " + ("enc-dec" if aan else "self") + " attention)",
+                "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                "traffic_note": "HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE runs of this command "
+                                "kept under profiles/ (not measured in this run)" if traffic else
+                                "no counter run of this workload is kept under profiles/: unmeasured",
+                "traffic_source": pf["traffic_source"],
+                "bytes_per_launch": ab[key] / n, "avg_launch_us": ms / n * 1e3, "launches": n,
+                "event_marker_us_removed_per_launch": marker_us,
+                "rocprofv3_avg_launch_us": pf["rocprofv3_avg_us"], "rocprofv3_source": pf["rocprofv3_source"]}
+    if traffic:
+        roofline["counter_GBps"] = traffic / (ms / n * 1e-3) / 1e9     # what actually left / entered HBM
+    if pf["rocprofv3_avg_us"]:
+        roofline["frac_by_rocprofv3"] = ab[key] / n / (pf["rocprofv3_avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS
+    return kernels, roofline
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -221,6 +329,7 @@ def main():
         from paper_1906_11024_amd import build
         build.build(verbose=False)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    lib_state = sb.lib_state()
 
     cfg = wl.get_config(args.config)
     T = cfg["steps"]
@@ -235,64 +344,19 @@ def main():
         sc = sb.make_config(cfg, encdec_share=share, use_cache=use_cache)
         return sb.San(sc, blob, self_pi, ctx_pi)
 
-    def heads(pi):
-        return len(pi), sum(pi) - len(pi)
-
     # ------------------------------------------------ headline: SAN policy, cached
+    p0, K, window_text = window_of(T, args.steps)
     gpu = make(cfg["self_pi"], cfg["encdec_pi"])
     run = Runner(torch, gpu, cfg, src, lens)
-    K = max(T, (args.steps // T) * T) if args.steps >= T else args.steps
-    wall = run.timed(K, args.warmup)
+    wall, walls = run.window(p0, K, max(1, args.reps), args.warmup)
     tok_per_s = B * K / wall
     ms_per_step = wall / K * 1e3
     launches = gpu.last_launch_count
 
     # ------------------------------------------------ per-kernel pass (HIP events)
-    # Second, identical pass over one decode with every launch bracketed by event
-    # markers on the library's stream.  A marker pair costs about 2 us of stream
-    # time per launch; that cost is estimated as (sum of bracketed times - unmarked
-    # wall time of the same decode) / launches and taken off every launch, so that
-    # the per-kernel figures add up to the unmarked step time (the decode is
-    # GPU-bound: kernels run back to back).  rocprofv3 --kernel-trace gives the
-    # same per-kernel averages (profiles/).
     kernels, roofline = {}, None
     if not args.no_profile:
-        wall_T = run.timed(T, 0)          # unmarked time of exactly one decode
-        run.pos = 0
-        gpu.profile(True)
-        gpu.profile_read(reset=True)
-        run.steps(T)
-        prof = gpu.profile_read(reset=True)
-        gpu.profile(False)
-        raw_ms = sum(ms for ms, n in prof.values())
-        n_pairs = sum(n for ms, n in prof.values())
-        marker_us = max(0.0, (raw_ms - wall_T * 1e3) / n_pairs * 1e3)
-        prof = {k: (max(ms - n * marker_us * 1e-3, 0.0), n) for k, (ms, n) in prof.items()}
-        aan = cfg["self_kind"] == "aan"
-        hs, fs = (0, 0) if aan else heads(cfg["self_pi"])
-        hc, fc = heads(cfg["encdec_pi"])
-        ab = attention_bytes(cfg, esz, hs, fs, hc, 0, mean_src)
-        gf = gemm_flops_per_step(cfg, hs, fs, hc)
-        for k, (ms, n) in prof.items():
-            if n == 0:
-                continue
-            ent = {"ms_per_step": ms / T, "launches_per_step": n / T, "avg_us": ms / n * 1e3}
-            if k in ab and ab[k] > 0:
-                ent["algo_GBps"] = ab[k] / (ms * 1e-3) / 1e9
-                ent["frac_hbm_peak"] = ent["algo_GBps"] / HBM_PEAK_GBS
-            if k in gf:
-                ent["TFLOPs"] = gf[k] * T / (ms * 1e-3) / 1e12
-                ent["frac_mfma_peak"] = ent["TFLOPs"] / MFMA_PEAK_TFLOPS[cfg["dtype"]]
-            kernels[k] = ent
-        key = "attn_ctx" if aan else "attn_self"
-        ms, n = prof[key]
-        achieved = ab[key] / (ms * 1e-3) / 1e9
-        traffic = MEASURED_TRAFFIC.get(args.config, {}).get(key)
-        roofline = {"kernel": "attention_kernel (block-head " + ("enc-dec" if aan else "self") + " attention)",
-                    "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                    "bytes_per_launch": ab[key] / n, "avg_launch_us": ms / n * 1e3, "launches": n,
-                    "event_marker_us_removed_per_launch": marker_us}
+        kernels, roofline = kernel_pass(torch, gpu, run, cfg, esz, mean_src, args.config)
     # ------------------------------------------------ latency, encode time, streaming-read yardstick
     # (after the timed region; each of these synchronises per call, the headline loop does not)
     extras = {"step_roofline": step_roofline(cfg, esz, cfg["self_pi"], cfg["encdec_pi"], mean_src, ms_per_step)}
@@ -334,28 +398,32 @@ def main():
     gpu.close()
     del run
 
-    # ------------------------------------------------ same kernels, other policies
+    # ------------------------------------------------ same kernels, other policies, same positions
     compare = {}
     if not args.no_compare:
         Ld = cfg["n_dec"]
-        variants = [("unshared_cached", [1] * Ld, [1] * Ld, sb.SAN_SHARE_A, 1, 2 * T)]
-        if cfg["self_kind"] != "aan":
-            variants.append(("san_share_s", cfg["self_pi"], cfg["encdec_pi"], sb.SAN_SHARE_S, 1, 2 * T))
+        aan = cfg["self_kind"] == "aan"
+        variants = [("unshared_cached", [1] * Ld, [1] * Ld, sb.SAN_SHARE_A, 1)]
+        if not aan:
+            variants.append(("san_share_s", cfg["self_pi"], cfg["encdec_pi"], sb.SAN_SHARE_S, 1))
             if Ld == 6:
                 # the uniform policy of Sec. 4.2: one self-attention block over the stack, enc-dec {3,3}
-                variants.append(("san_uniform_policy", [6], [3, 3], sb.SAN_SHARE_A, 1, 2 * T))
-            variants.append(("san_no_cache", cfg["self_pi"], cfg["encdec_pi"], sb.SAN_SHARE_A, 0, T))
-            variants.append(("unshared_no_cache", [1] * Ld, [1] * Ld, sb.SAN_SHARE_A, 0, T))
-        for name, spi, cpi, share, cache, k in variants:
+                variants.append(("san_uniform_policy", [6], [3, 3], sb.SAN_SHARE_A, 1))
+        if not aan:
+            variants.append(("san_no_cache", cfg["self_pi"], cfg["encdec_pi"], sb.SAN_SHARE_A, 0))
+            variants.append(("unshared_no_cache", [1] * Ld, [1] * Ld, sb.SAN_SHARE_A, 0))
+        # the comparison legs run at most two decodes per repetition (the un-cached ones: one)
+        for name, spi, cpi, share, cache in variants:
+            k_leg = K if K < T else (min(K, 2 * T) if cache else T)
             g = make(spi, cpi, share, cache)
             r = Runner(torch, g, cfg, src, lens)
-            w = r.timed(k, T if cache else 0)
-            compare[name] = {"tokens_per_s": B * k / w, "ms_per_step": w / k * 1e3, "steps": k,
-                             "kernels_per_step": g.last_launch_count,
+            w, _ = r.window(p0, k_leg, 5 if cache else 3, T if cache else 0)
+            compare[name] = {"tokens_per_s": B * k_leg / w, "ms_per_step": w / k_leg * 1e3, "steps": k_leg,
+                             "first_position": p0, "kernels_per_step": g.last_launch_count,
                              "weight_MB": g.device_bytes(0) / 1e6, "state_MB": g.device_bytes(1) / 1e6}
             g.close()
             del r
-        # the same decode driven by san_decode_n: one host call per 64 steps, pairs of
+        # the same decode driven by san_decode_n: one host call per decode, pairs of
         # steps replayed from a captured HIP graph (own stream: the NULL stream cannot be captured)
         for name, use_graph in (("san_decode_n_eager", False), ("san_decode_n_graph", True)):
             st = torch.cuda.Stream()
@@ -372,12 +440,15 @@ def main():
 
                 one_decode()
                 st.synchronize()
-                t0 = time.perf_counter()
-                for _ in range(4):
+                ts = []
+                for _ in range(5):
+                    t0 = time.perf_counter()
                     one_decode()
-                st.synchronize()
-                w = time.perf_counter() - t0
-                compare[name] = {"tokens_per_s": B * 4 * T / w, "ms_per_step": w / (4 * T) * 1e3, "steps": 4 * T}
+                    st.synchronize()
+                    ts.append(time.perf_counter() - t0)
+                w = float(np.median(ts))
+                compare[name] = {"tokens_per_s": B * T / w, "ms_per_step": w / T * 1e3, "steps": T,
+                                 "window": "one whole decode per repetition, median of 5"}
                 g.close()
                 del r
         # sentences of different lengths: finished ones leave the batch (san_compact) or ride along
@@ -390,10 +461,44 @@ def main():
         rf["speedup"] = rf["fixed_batch"]["ms_per_decode"] / rf["compacting"]["ms_per_decode"]
         rf["schedule"] = "sentence b ends after T/2 + b*T/(2*batch) steps; the batch is compacted every 8 steps"
         compare["ragged_finish"] = rf
-        compare["san_cached"] = {"tokens_per_s": tok_per_s, "ms_per_step": ms_per_step}
+        compare["san_cached"] = {"tokens_per_s": tok_per_s, "ms_per_step": ms_per_step, "steps": K, "first_position": p0}
+        compare["positions"] = "every leg above san_decode_n_* is timed over the same positions as the headline " \
+                               "(whole decodes when the headline is whole decodes)"
         compare["speedup_san_vs_unshared_cached"] = tok_per_s / compare["unshared_cached"]["tokens_per_s"]
         if "unshared_no_cache" in compare:
             compare["speedup_san_vs_unshared_no_cache"] = tok_per_s / compare["unshared_no_cache"]["tokens_per_s"]
+            compare["speedup_cache_vs_no_cache_unshared"] = (compare["unshared_cached"]["tokens_per_s"]
+                                                             / compare["unshared_no_cache"]["tokens_per_s"])
+
+    # ------------------------------------------------ the other workloads, one short leg each
+    configs = {}
+    if not args.no_configs and args.config == "base":
+        for name in ("long", "big", "aan"):
+            c2 = wl.get_config(name)
+            e2 = 2 if c2["dtype"] == "bf16" else 4
+            w2 = wl.make_weights(c2, seed=0)
+            blob2 = wl.pack_weights(c2, w2)
+            del w2
+            src2, lens2 = wl.make_source(c2, 0)
+            g = sb.San(sb.make_config(c2), blob2, c2["self_pi"], c2["encdec_pi"])
+            del blob2
+            r = Runner(torch, g, c2, src2, lens2)
+            T2, B2 = c2["steps"], c2["batch"] * c2["beam"]
+            w, _ = r.window(0, T2, 3, T2)            # one whole decode per repetition
+            ent = {"workload": f"transformer-{name}: batch {c2['batch']} x beam {c2['beam']}, {T2} decode steps, "
+                               f"{c2['dtype']}, self policy {c2['self_pi'] if c2['self_kind'] != 'aan' else 'AAN'}, "
+                               f"enc-dec policy {c2['encdec_pi']}",
+                   "window": f"one whole decode (positions 0-{T2 - 1}) per repetition, median of 3",
+                   "tokens_per_s": B2 * T2 / w, "ms_per_step": w / T2 * 1e3, "kernels_per_step": g.last_launch_count,
+                   "dtype": c2["dtype"]}
+            ks, rl = kernel_pass(torch, g, r, c2, e2, float(lens2.mean()), name)
+            ent["roofline"] = rl
+            ent["kernels"] = {k: v for k, v in ks.items() if k.startswith("attn") or k in ("logits", "ffn", "proj", "out")}
+            ent["step_roofline"] = step_roofline(c2, e2, c2["self_pi"], c2["encdec_pi"], float(lens2.mean()), w / T2 * 1e3)
+            g.close()
+            del r
+            torch.cuda.empty_cache()
+            configs[name] = ent
 
     # ------------------------------------------------ beam-size sweep (Fig. 5 axis)
     beam_sweep = {}
@@ -405,7 +510,7 @@ def main():
             for name, spi, cpi in (("san", cfg["self_pi"], cfg["encdec_pi"]), ("unshared", [1] * Ld, [1] * Ld)):
                 g = sb.San(sb.make_config(c2), blob, spi, cpi)
                 r = Runner(torch, g, c2, src, lens)
-                w = r.timed(2 * T, T)
+                w, _ = r.window(0, 2 * T, 3, T)
                 ent[name] = {"tokens_per_s": c2["batch"] * bm * 2 * T / w, "sentence_tokens_per_s": c2["batch"] * 2 * T / w,
                              "ms_per_step": w / (2 * T) * 1e3}
                 g.close()
@@ -425,19 +530,23 @@ def main():
         orc = so.SanOracle(cfg, weights, cfg["self_pi"], cfg["encdec_pi"])
         orc.encode(src, lens)
         ksteps = min(args.cpu_steps, T)
+        c0 = (T - ksteps) // 2                       # the middle of a decode, as the GPU's short window
         tokens = np.full(B, 1, dtype=np.int64)
         cum = np.full(B, -np.inf)
         cum[0::cfg["beam"]] = 0.0
-        t0 = time.perf_counter()
-        for _ in range(ksteps):
+        t0 = None
+        for s in range(c0 + ksteps):
+            if s == c0:
+                t0 = time.perf_counter()
             lg = orc.decode_step(tokens)
             tk, par, sc, _ = orc.topk(lg, cum, cfg["beam"])
             orc.beam_reorder(par.reshape(-1))
             tokens, cum = tk.reshape(-1).astype(np.int64), sc.reshape(-1)
         cw = time.perf_counter() - t0
         cpu = {"value": B * ksteps / cw, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-               "sample": f"first {ksteps} of {T} decode steps of the same batch ({cfg['batch']} sentences x beam "
-                         f"{cfg['beam']}), numpy fp64; early steps have short caches, so this flatters the CPU",
+               "sample": f"positions {c0}-{c0 + ksteps - 1} of the {T} decode steps of the same batch ({cfg['batch']} "
+                         f"sentences x beam {cfg['beam']}; mean cache length = the decode's), the oracle as it stands "
+                         f"(numpy fp64, BLAS threads = cores); the {c0} steps before them run untimed",
                "ms_per_step": cw / ksteps * 1e3}
 
     if args.calib_copy_mb:
@@ -457,11 +566,17 @@ def main():
         "config": {"workload": f"transformer-{args.config}: {cfg['n_enc']}+{cfg['n_dec']} layers, d={cfg['d']}, "
                                f"H={cfg['H']}, d_ff={cfg['F']}, vocab={cfg['V']}, batch {cfg['batch']} x beam "
                                f"{cfg['beam']}, src len U{list(cfg['src_len'])}, {T} decode steps, cached, "
-                               f"self policy {cfg['self_pi']}, enc-dec policy {cfg['encdec_pi']} (share A)",
+                               f"self policy {cfg['self_pi']}, enc-dec policy {cfg['encdec_pi']} (share A); "
+                               f"timed window: {window_text}",
+                   "window_first_position": p0, "window_steps": K, "repetitions": len(walls),
+                   "ms_per_step_min_max": [min(walls) / K * 1e3, max(walls) / K * 1e3],
                    "rows": B, "kernels_per_step": launches,
-                   "sentence_tokens_per_s": cfg["batch"] * K / wall},
+                   "sentence_tokens_per_s": cfg["batch"] * K / wall,
+                   "lib_source_hash": lib_state["built_from"], "lib_stale": lib_state["stale"]},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "compare": compare, **extras,
     }
+    if configs:
+        out["configs"] = configs
     if beam_sweep:
         out["beam_sweep"] = beam_sweep
     print(json.dumps(out))
