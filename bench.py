@@ -409,9 +409,8 @@ def main():
             if Ld == 6:
                 # the uniform policy of Sec. 4.2: one self-attention block over the stack, enc-dec {3,3}
                 variants.append(("san_uniform_policy", [6], [3, 3], sb.SAN_SHARE_A, 1))
-        if not aan:
-            variants.append(("san_no_cache", cfg["self_pi"], cfg["encdec_pi"], sb.SAN_SHARE_A, 0))
-            variants.append(("unshared_no_cache", [1] * Ld, [1] * Ld, sb.SAN_SHARE_A, 0))
+        variants.append(("san_no_cache", cfg["self_pi"], cfg["encdec_pi"], sb.SAN_SHARE_A, 0))
+        variants.append(("unshared_no_cache", [1] * Ld, [1] * Ld, sb.SAN_SHARE_A, 0))
         # the comparison legs run at most two decodes per repetition (the un-cached ones: one)
         for name, spi, cpi, share, cache in variants:
             k_leg = K if K < T else (min(K, 2 * T) if cache else T)

@@ -73,7 +73,8 @@ typedef struct {
   int32_t self_kind;   /* SAN_SELF_DOT | SAN_SELF_AAN                                 */
   int32_t encdec_share;/* SAN_SHARE_A | SAN_SHARE_S                                   */
   int32_t use_cache;   /* 1: key/value cache (Sec. 4.1 baseline); 0: recompute every
-                          target position at every step (Tab. 6 row "-Cache")         */
+                          target position at every step (Tab. 6 row "-Cache"), with
+                          either self_kind                                            */
   int32_t pad_id, bos_id, eos_id; /* word ids in [0, vocab); eos_id < 0 switches EOS handling
                                      off in san_topk                                          */
   int32_t debug;       /* 1: keep per-layer S / A / hidden copies for san_debug_get   */

@@ -99,6 +99,9 @@ hipError_t launch_compact_S(const float* src, int ldS, float* dst, int rows_h, i
 // ------------------------------------------------------------------- AAN layer
 hipError_t launch_aan_pre(int dtype, float* sum, const void* x, void* avg, void* cat, const int* t_dev, int rows,
                           int d, hipStream_t stream);
+// un-cached decoding: x is [hyps][np][d]; avg[h][i] = mean of x[h][0..i], cat[h*np + i][0..d) = x[h][i]
+hipError_t launch_aan_prefix_mean(int dtype, const void* x, void* avg, void* cat, int hyps, int np, int d,
+                                  hipStream_t stream);
 // x = LN(x + sigmoid(zi) * x + sigmoid(zf) * g), z = gate pre-activations (fp32, bias not yet added)
 hipError_t launch_aan_post(int dtype, const float* z, const void* bg, const void* cat, const void* gamma,
                            const void* beta, void* x, float* out_f32, int rows, int d, float eps,

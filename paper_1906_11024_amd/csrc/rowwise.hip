@@ -267,6 +267,38 @@ hipError_t launch_aan_pre(int dtype, float* sum, const void* x, void* avg, void*
   return hipGetLastError();
 }
 
+// Nothing cached: the mean over positions 0..i of every position i of every hypothesis
+// (x is [hyps][np][d]); a thread owns 4 columns of one hypothesis and walks its positions,
+// adding in the order and precision of the running sum above.
+template <typename T>
+__global__ __launch_bounds__(256) void aan_prefix_mean_kernel(const T* x, T* avg, T* cat, int hyps, int np, int d) {
+  const size_t i4 = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i4 >= (size_t)hyps * d) return;
+  const int b = (int)(i4 / d), c = (int)(i4 % d);
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int i = 0; i < np; ++i) {
+    const size_t row = (size_t)b * np + i;
+    const float4 xv = load4(x + row * d + c);
+    s.x += xv.x; s.y += xv.y; s.z += xv.z; s.w += xv.w;
+    const float inv = 1.0f / (float)(i + 1);
+    store4(avg + row * d + c, make_float4(s.x * inv, s.y * inv, s.z * inv, s.w * inv));
+    store4(cat + row * 2 * d + c, xv);
+  }
+}
+hipError_t launch_aan_prefix_mean(int dtype, const void* x, void* avg, void* cat, int hyps, int np, int d,
+                                  hipStream_t stream) {
+  const size_t total = (size_t)hyps * d / 4;
+  if (!total || np <= 0) return hipSuccess;
+  dim3 grid((unsigned)((total + 255) / 256));
+  if (dtype == 1)
+    hipLaunchKernelGGL(aan_prefix_mean_kernel<bf16_t>, grid, dim3(256), 0, stream, (const bf16_t*)x, (bf16_t*)avg,
+                       (bf16_t*)cat, hyps, np, d);
+  else
+    hipLaunchKernelGGL(aan_prefix_mean_kernel<float>, grid, dim3(256), 0, stream, (const float*)x, (float*)avg,
+                       (float*)cat, hyps, np, d);
+  return hipGetLastError();
+}
+
 template <typename T>
 __global__ __launch_bounds__(kLnMaxWaves * 64) void aan_post_kernel(const float* z, const T* bg, const T* cat,
                                                                     const T* gamma, const T* beta, T* x,

@@ -265,7 +265,6 @@ const char* check_config(const san_config& c) {
   if (c.self_kind != SAN_SELF_DOT && c.self_kind != SAN_SELF_AAN) return "bad self_kind";
   if (c.encdec_share != SAN_SHARE_A && c.encdec_share != SAN_SHARE_S) return "bad encdec_share";
   if (c.use_cache != 0 && c.use_cache != 1) return "use_cache must be 0 or 1";
-  if (!c.use_cache && c.self_kind == SAN_SELF_AAN) return "the un-cached mode supports dot-product self-attention only";
   if (!c.use_cache && c.debug) return "debug copies need use_cache = 1";
   if (!(c.ln_eps > 0.f)) return "ln_eps must be > 0";
   if (c.pad_id < 0 || c.pad_id >= c.vocab || c.bos_id < 0 || c.bos_id >= c.vocab)
@@ -448,8 +447,10 @@ static int build_ctx(san_ctx* c, const Blob& bl, const void* blob, const std::ve
         TRY(wtensor(c, &L.ab2, blob, o.aan.b2, d));
         TRY(wtensor(c, &L.awg, blob, o.wg, 4 * d * d));
         TRY(wtensor(c, &L.abg, blob, o.bg, 2 * d));
-        if (n == 0) TRY(dalloc(c, (void**)&c->aan_all, (size_t)Ld * c->rows_max * d * 4, false));
-        L.aan_sum = c->aan_all + (size_t)n * c->rows_max * d;   // all layers in one buffer: one reorder launch
+        if (!nocache) {   // running sums, all layers in one buffer: one reorder launch
+          if (n == 0) TRY(dalloc(c, (void**)&c->aan_all, (size_t)Ld * c->rows_max * d * 4, false));
+          L.aan_sum = c->aan_all + (size_t)n * c->rows_max * d;
+        }
       } else {
         if (L.self_head == n) {   // block head: fused [q;k;v] projection, key and value cache, weight scratch
           TRY(dalloc(c, &L.w_self, 3 * d * d * esz, true));
@@ -525,7 +526,7 @@ static int build_ctx(san_ctx* c, const Blob& bl, const void* blob, const std::ve
     TRY(dalloc(c, &c->qkv, mrows * 3 * d * esz, false));
     TRY(dalloc(c, &c->ab, mrows * d * esz, false));
     TRY(dalloc(c, &c->hb, mrows * wide * esz, false));
-    if (aan) TRY(dalloc(c, &c->cat, (size_t)c->rows_max * 2 * d * esz, false));
+    if (aan) TRY(dalloc(c, &c->cat, drows * 2 * d * esz, false));
     c->part_elems = mrows * 2 * d;
     if (c->part_elems < (size_t)4 << 20) c->part_elems = (size_t)4 << 20;
     TRY(dalloc(c, (void**)&c->part, c->part_elems * 4, false));
@@ -832,9 +833,22 @@ static int decode_uncached(san_ctx* c, const int32_t* tokens, float* logits) {
   LAUNCH(c, launch_embed(c->dt, c->hist, T, np, c->tgt_emb, c->pe, nullptr, c->x, M, d, c->V,
                          (float)std::sqrt((double)d), nullptr, nullptr, 0, c->stream));
   const int Ld = (int)c->dec.size();
+  const bool aan = c->cfg.self_kind == SAN_SELF_AAN;
   for (int n = 0; n < Ld; ++n) {
     DecLayer& L = c->dec[n];
     const bool head = L.self_head == n;
+    if (aan) {
+      // the average-attention layer over all positions: prefix means instead of running sums
+      c->kind = SAN_K_AAN;
+      LAUNCH(c, launch_aan_prefix_mean(c->dt, c->x, c->ab, c->cat, B, np, d, c->stream));
+      if ((rc = gemm(c, c->ab, d, L.aw1, L.ab1, M, c->F, d, 1, 0, c->hb, c->F))) return rc;
+      if ((rc = gemm(c, c->hb, c->F, L.aw2, L.ab2, M, d, c->F, 0, 0, (char*)c->cat + (size_t)d * c->esz, 2 * d))) return rc;
+      if ((rc = gemm(c, c->cat, 2 * d, L.awg, nullptr, M, 2 * d, 2 * d, 0, 2, c->part, 2 * d, 0, nullptr, 0, 0, nullptr, 0, 0,
+                     0, false, 1)))
+        return rc;
+      LAUNCH(c, launch_aan_post(c->dt, c->part, L.abg, c->cat, L.ln1g, L.ln1b, c->x, nullptr, M, d, c->cfg.ln_eps,
+                                c->stream));
+    } else {
     c->kind = SAN_K_PROJ;
     if (head) {
       if ((rc = gemm(c, c->x, d, L.w_self, L.b_self, M, 3 * d, d, 0, 0, c->qkv, 3 * d))) return rc;
@@ -858,6 +872,7 @@ static int decode_uncached(san_ctx* c, const int32_t* tokens, float* logits) {
     }
     c->kind = SAN_K_OUT;
     if ((rc = gemm_ln(c, c->ab, d, L.wo, L.bo, M, d, c->x, L.ln1g, L.ln1b, c->x, nullptr))) return rc;
+    }
     const bool chead = L.ctx_head == n;
     DecLayer& Hd = c->dec[L.ctx_head];
     const void* A = Hd.A_ctx;

@@ -10,6 +10,11 @@ under profiles/.
       FETCH_SIZE or WRITE_SIZE per launch, scaled by the reading of the plain
       copy kernel of known size that bench.py --calib-copy-mb adds to the run
 
+  python -m paper_1906_11024_amd.rocprof_summary mfma <counter_collection.csv> --dtype f32 [--trace <results.db>]
+      matrix-core use of every GEMM shape: SQ_VALU_MFMA_BUSY_CYCLES (summed over the SIMDs)
+      against GRBM_GUI_ACTIVE x 1024 SIMDs, and the flops the MFMA op counter saw
+      (SQ_INSTS_VALU_MFMA_MOPS_* x 512) against the algorithmic 2 M N K where the shape is known
+
 Only reads files; nothing here runs on the GPU.
 """
 from __future__ import annotations
@@ -133,9 +138,47 @@ def pmc(path: str, copy_mib: int, cfg_name: str) -> None:
         print(f"  {k:70s} n={len(v):5d} {sum(v) / len(v) * factor * 1024 / 1e6:10.2f}")
 
 
+def mfma(path: str, dtype: str) -> None:
+    """Per GEMM shape (kernel name + grid): MFMA-busy cycles summed over all SIMDs
+    (SQ_VALU_MFMA_BUSY_CYCLES; a 32x32x2 fp32 MFMA holds the pipe 64 cycles = its 4096 flops at
+    the 64 flops/cycle/SIMD behind the 157.3 TFLOP/s peak, so busy cycles / (SIMDs x cycles) IS
+    the fraction of the dense peak), set against
+      - the dispatch's own GPU-active cycles: GRBM_GUI_ACTIVE, which the CSV holds summed over the
+        8 XCDs, hence /8 (the profiler's MfmaUtil expression takes the max over XCDs instead);
+      - the dispatch's duration in this run (End - Start time stamps) at 2.4 GHz.
+    Kernels run slower while counters are collected (each dispatch is serialised), so both are
+    lower bounds of the utilisation in a normal run; the flops the MFMA op counter saw
+    (MOPS x 512) are printed to be checked against the algorithmic 2 M N K."""
+    simds, xcds, ghz = 256 * 4, 8, 2.4
+    rows = list(csv.DictReader(open(path)))
+    per = {}
+    for r in rows:
+        if "gemm_kernel" not in r["Kernel_Name"]:
+            continue
+        key = (_short(r["Kernel_Name"]), r["Grid_Size"])
+        d = per.setdefault(key, {})
+        d.setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
+        if r["Counter_Name"] == "GRBM_GUI_ACTIVE":
+            d.setdefault("dur_ns", []).append(float(r["End_Timestamp"]) - float(r["Start_Timestamp"]))
+    mops_name = "SQ_INSTS_VALU_MFMA_MOPS_BF16" if dtype == "bf16" else "SQ_INSTS_VALU_MFMA_MOPS_F32"
+    peak = 2500.0 if dtype == "bf16" else 157.3
+    print(f"{'kernel':50s} {'grid':>8s} {'calls':>5s} {'GFLOP':>8s} {'mfma_busy_cyc':>14s} {'active_cyc/XCD':>15s} {'dur_us':>8s} "
+          f"{'util(active)':>13s} {'util(dur)':>10s} {'TFLOP/s(dur)':>13s}")
+    for (name, grid), d in sorted(per.items(), key=lambda kv: -sum(kv[1].get("dur_ns", [0]))):
+        busy, act, mops, dur = (d.get(k, []) for k in ("SQ_VALU_MFMA_BUSY_CYCLES", "GRBM_GUI_ACTIVE", mops_name, "dur_ns"))
+        if not busy or not act or not dur:
+            continue
+        b, a, t = sum(busy) / len(busy), sum(act) / len(act) / xcds, sum(dur) / len(dur)
+        gf = (sum(mops) / len(mops)) * 512 / 1e9 if mops else float("nan")
+        print(f"{name:50s} {grid:>8s} {len(busy):5d} {gf:8.3f} {b:14.0f} {a:15.0f} {t / 1e3:8.2f} {b / (a * simds):13.3f} "
+              f"{b / (t * ghz * simds):10.3f} {gf / t * 1e6:13.1f}")
+    print(f"(dense peak for {dtype}: {peak} TFLOP/s; util = MFMA-busy cycles / (1024 SIMDs x cycles of the dispatch))")
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
-    ap.add_argument("mode", choices=["kernels", "attention", "pmc"])
+    ap.add_argument("mode", choices=["kernels", "attention", "pmc", "mfma"])
+    ap.add_argument("--dtype", default="f32")
     ap.add_argument("path")
     ap.add_argument("--config", default="base")
     ap.add_argument("--copy-mib", type=int, default=512)
@@ -144,6 +187,8 @@ def main() -> None:
         kernels(a.path)
     elif a.mode == "attention":
         attention(a.path, a.config)
+    elif a.mode == "mfma":
+        mfma(a.path, a.dtype)
     else:
         pmc(a.path, a.copy_mib, a.config)
 

@@ -103,9 +103,9 @@ def test_bad_encoder_policy_is_epolicy(lib):
         assert rc == sb.SAN_EPOLICY and "encoder" in msg
 
 
-def test_uncached_aan_rejected_and_null_handles(lib):
-    sc = sb.make_config(wl.get_config("tiny", self_kind="aan"), use_cache=0)
-    rc, _ = _init(lib, sc, [1, 1], [2], nbytes=16)
+def test_debug_needs_the_cache_and_null_handles(lib):
+    sc = sb.make_config(wl.get_config("tiny"), use_cache=0, debug=1)
+    rc, _ = _init(lib, sc, [2], [2], nbytes=16)
     assert rc == sb.SAN_EINVAL
     assert lib.san_step(None) == -1 and lib.san_device_bytes(None, 0) == 0
     assert lib.san_decode_step(None, None, None) == sb.SAN_EINVAL

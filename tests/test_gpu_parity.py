@@ -193,6 +193,30 @@ def test_mid_uncached_mode_matches_oracle_and_cached():
         gpu.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_mid_uncached_aan_matches_oracle(dtype):
+    """Tab. 6 puts "-Cache" and "+AAN" in one table: the average-attention layer with nothing
+    cached (prefix means over all re-computed positions) against the oracle, with beam reordering."""
+    cfg = mid_cfg(steps=12, self_kind="aan", self_pi=[1, 1, 1, 1], dtype=dtype)
+    w = wl.make_weights(cfg, seed=23, sharp=2.0)
+    src, lens = ragged(cfg, 23)
+    tol = F32_TOL if dtype == "f32" else BF16_TOL
+    gpu = hz.make_gpu(cfg, w, use_cache=0)
+    orc = hz.make_oracle(cfg, w)
+    ls = hz.Lockstep(gpu, orc, src, lens, cfg["beam"])
+    hist = [ls.tokens.cpu().numpy()]
+    for t in range(cfg["steps"]):
+        lg, lo = ls.step(logit_tol=tol)
+        if t in (0, 5):          # the oracle's own full re-forward of the same prefix (its un-cached mode)
+            full = orc.decode_full(np.stack(hist, axis=1))
+            assert hz.rel_err_rows(lg, full).max() <= tol
+        par = ls.log["parents"][-1].reshape(-1)
+        hist = [h[par] for h in hist] + [ls.tokens.cpu().numpy()]
+    assert max(ls.log["logit_err"]) <= tol
+    assert any((p.reshape(-1) != np.arange(20)).any() for p in ls.log["parents"][1:])
+    gpu.close()
+
+
 def test_mid_eos_handling():
     cfg = mid_cfg(steps=10, V=8, batch=4, beam=3)          # tiny vocabulary: EOS gets picked often
     w = wl.make_weights(cfg, seed=4)
