@@ -23,11 +23,11 @@ __device__ __forceinline__ void wave_lds_sync() {
 }
 
 // 16-byte fragment -> fp32 values
-__device__ __forceinline__ void widen(const uint4& raw, float (&out)[4]) {
+static __device__ __forceinline__ void widen(const uint4& raw, float (&out)[4]) {
   out[0] = __uint_as_float(raw.x); out[1] = __uint_as_float(raw.y);
   out[2] = __uint_as_float(raw.z); out[3] = __uint_as_float(raw.w);
 }
-__device__ __forceinline__ void widen(const uint4& raw, float (&out)[8]) {
+static __device__ __forceinline__ void widen(const uint4& raw, float (&out)[8]) {
   const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -423,6 +423,20 @@ template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p0
 
 hipError_t launch_attention(int dtype, const AttnParams& p, hipStream_t stream) {
   if (p.rows <= 0 || p.lmax <= 0) return hipSuccess;
+  // Long streams in a launch that has fewer of them than the chip has SIMDs are split over
+  // several waves each (attention_split.hip); measured on the 12-layer, 256-step workload
+  // (1024 streams of up to 256 cached positions, 256 sentence memories of 128 positions):
+  // enc-dec head 13.4 -> 9.4 us with 4 waves per stream and one query per workgroup,
+  // self-attention head 13.9 -> 13.4 us with 2 waves.  Everything else is faster with one
+  // wave per stream (at 2048 streams of <= 64 positions the split kernel's extra workgroup
+  // barrier and LDS combine cost more than its shorter chains save: 8.4 vs 7.7 us), and so
+  // are followers (their single pass over V is short already).
+  if (!p.apply) {
+    const long streams = p.self_mode ? (long)p.rows * p.H : (long)p.groups * p.H * ((p.rpg + 3) / 4);
+    if (p.self_mode && streams <= 1024 && p.lmax >= 128) return launch_attention_split(dtype, p, 2, false, stream);
+    if (!p.self_mode && !p.causal && p.rpg > 1 && streams < 1024 && p.lmax >= 96)
+      return launch_attention_split(dtype, p, 4, true, stream);
+  }
   if (p.lmax > 1024) return hipErrorInvalidValue;   // score rows must fit 64 KB of LDS
   if (p.ldk < 0 || p.ldv < 0 || p.ldk >= (1 << 24) || p.ldv >= (1 << 24)) return hipErrorInvalidValue;
   if (p.self_mode && p.ldk != p.ldv && !p.apply) return hipErrorInvalidValue;   // one offset table serves both caches

@@ -67,6 +67,9 @@ struct AttnParams {
   float scale;
 };
 hipError_t launch_attention(int dtype, const AttnParams& p, hipStream_t stream);
+// the same attention with each stream split over `waves` (1, 2, 4 or 8) waves of a workgroup; one_query:
+// grouped mode, one query per workgroup instead of four.  launch_attention picks between the two.
+hipError_t launch_attention_split(int dtype, const AttnParams& p, int waves, bool one_query, hipStream_t stream);
 
 // ------------------------------------------------------------------ row-wise
 // x[r] = emb[clamp(tok)] * scale + pe[pos]; row r = hyp*rpg + i reads token

@@ -852,6 +852,31 @@ def test_maximum_width(kind, dtype):
     gpu.close()
 
 
+@pytest.mark.parametrize("dtype,share", [("f32", "A"), ("f32", "S"), ("bf16", "A")])
+def test_long_streams_few_of_them(dtype, share):
+    """Streams of more than 128 cached positions and sentence memories of up to 100 positions
+    in a small batch: these launches split every stream over several waves of a workgroup
+    (partial softmax per wave, combined through LDS), self-attention with a chunk loop."""
+    cfg = mid_cfg(batch=2, beam=4, steps=140, src_len=(1, 100), n_dec=3, self_pi=[2, 1], encdec_pi=[1, 2], dtype=dtype)
+    w = wl.make_weights(cfg, seed=27, sharp=4.0)
+    src, lens = ragged(cfg, 27)
+    gpu = hz.make_gpu(cfg, w, share=share, debug=1)
+    orc = hz.make_oracle(cfg, w, share=share)
+    ls = hz.Lockstep(gpu, orc, src, lens, cfg["beam"])
+    tol = F32_TOL if dtype == "f32" else BF16_TOL
+    for t in range(cfg["steps"]):
+        ls.step(logit_tol=tol)
+        if dtype == "f32" and t in (0, 31, 32, 64, 65, 127, 128, 139):     # chunk and wave-share boundaries
+            for n in range(cfg["n_dec"]):
+                S = gpu.debug_get(sb.SAN_DBG_S_SELF, n).cpu().numpy()
+                assert np.abs(S.sum(-1) - 1).max() < 1e-5
+                assert np.abs(S - orc.dump["S_self"][n]).max() < 2e-6, (t, n)
+                Sc = gpu.debug_get(sb.SAN_DBG_S_CTX, n).cpu().numpy()
+                assert np.abs(Sc - orc.dump["S_ctx"][n]).max() < 2e-6, (t, n)
+    assert max(ls.log["logit_err"]) <= tol
+    gpu.close()
+
+
 def test_maximum_beam_and_long_cache():
     """beam = 32 (the largest the library takes) and a cache of 300 positions
     (several chunks of the attention pipeline plus a ragged tail)."""
