@@ -95,7 +95,7 @@ template <> struct QFrag<bf16_t> {
 // MULTI = 0: the launcher guarantees that a wave's share of the stream is at most one
 // chunk (U load instructions), so there is no loop and no running rescale.
 template <typename T, int LPP, int NQ, int MULTI>
-__global__ __launch_bounds__(kMaxWavesPerBlock * 64) void attention_split_kernel(AttnParams p) {
+__global__ __launch_bounds__(kMaxWavesPerBlock * 64) void attention_kernel_split(AttnParams p) {
   constexpr int EPL = Frag<T>::N;       // elements per lane per position
   constexpr int PPL = kWave / LPP;      // positions per load instruction
   constexpr int DH = LPP * EPL;
@@ -415,8 +415,8 @@ static hipError_t launch_nq(const AttnParams& p, dim3 grid, int nw, hipStream_t 
   constexpr int PPL = kWave / LPP, CH = PPL * (PPL >= 8 ? 4 : 8);   // positions per chunk, as in the kernel
   const size_t smem = sizeof(float) * ((p.emit ? (size_t)NQ * p.lmax : 0) + (size_t)nw * NQ * (2 + DH));
   const bool multi = p.lmax > nw * CH;
-  if (multi) hipLaunchKernelGGL((attention_split_kernel<T, LPP, NQ, 1>), grid, dim3(nw * 64), smem, stream, p);
-  else hipLaunchKernelGGL((attention_split_kernel<T, LPP, NQ, 0>), grid, dim3(nw * 64), smem, stream, p);
+  if (multi) hipLaunchKernelGGL((attention_kernel_split<T, LPP, NQ, 1>), grid, dim3(nw * 64), smem, stream, p);
+  else hipLaunchKernelGGL((attention_kernel_split<T, LPP, NQ, 0>), grid, dim3(nw * 64), smem, stream, p);
   return hipGetLastError();
 }
 

@@ -72,13 +72,24 @@ hipError_t launch_attention(int dtype, const AttnParams& p, hipStream_t stream);
 hipError_t launch_attention_split(int dtype, const AttnParams& p, int waves, bool one_query, hipStream_t stream);
 
 // ------------------------------------------------------------------ row-wise
+// Optional extra outputs of the kernel that produces a decoder layer's input x when that layer is
+// an average-attention layer (cached decoding): the running sum of the layer inputs over the
+// positions so far (fp32 state, reset at step 0), its mean, and x as the left half of the gate's
+// input [x ; g], without a launch of their own.
+struct AanFuse {
+  float* sum;          // [rows][d], nullptr: off
+  void* avg;           // T [rows][d]
+  void* cat;           // T [rows][2 d]
+  const int* t_dev;
+};
+
 // x[r] = emb[clamp(tok)] * scale + pe[pos]; row r = hyp*rpg + i reads token
 // tok[hyp*tok_stride + i]; pos = *t_dev when t_dev != nullptr, else i.
 // With last_tok / anc given (cached decoding, rpg == 1) the kernel also does the
 // step's bookkeeping: last_tok[r] = tok[r], anc[r*ld_anc + t] = r.
 hipError_t launch_embed(int dtype, const int* tok, int tok_stride, int rpg, const void* emb, const float* pe,
                         const int* t_dev, void* x, int rows, int d, int vocab, float scale, int* last_tok,
-                        int* anc, int ld_anc, hipStream_t stream);
+                        int* anc, int ld_anc, hipStream_t stream, const AanFuse* aan = nullptr);
 
 // out[m] = LayerNorm(sum_s part[s][m] + bias + res[m]) * g + b  (row-wise over n);
 // part is [nsplit][M][ldp] and may point at a column offset of a wider buffer
@@ -90,7 +101,8 @@ struct LnStage2 {
 };
 hipError_t launch_ln_reduce(int dtype, const float* part, int nsplit, int ldp, const void* bias, const void* res, int ldr,
                             const void* gamma, const void* beta, void* out, int ldo, float* out_f32, int M, int n,
-                            float eps, hipStream_t stream, const LnStage2* stage2 = nullptr);
+                            float eps, hipStream_t stream, const LnStage2* stage2 = nullptr,
+                            const AanFuse* aan = nullptr);
 
 // start of a decode step: last_tok[r] = tok[r]; anc[r][t] = r; hist[r][t] = tok[r]
 hipError_t launch_step_begin(const int* tok, int* last_tok, int* anc, int* hist, int ld, const int* t_dev, int rows,
@@ -100,8 +112,6 @@ hipError_t launch_to_f32(int dtype, const void* src, int lds, float* dst, int ro
 hipError_t launch_compact_S(const float* src, int ldS, float* dst, int rows_h, int n, hipStream_t stream);
 
 // ------------------------------------------------------------------- AAN layer
-hipError_t launch_aan_pre(int dtype, float* sum, const void* x, void* avg, void* cat, const int* t_dev, int rows,
-                          int d, hipStream_t stream);
 // un-cached decoding: x is [hyps][np][d]; avg[h][i] = mean of x[h][0..i], cat[h*np + i][0..d) = x[h][i]
 hipError_t launch_aan_prefix_mean(int dtype, const void* x, void* avg, void* cat, int hyps, int np, int d,
                                   hipStream_t stream);

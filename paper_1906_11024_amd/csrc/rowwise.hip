@@ -9,11 +9,29 @@
 
 namespace san {
 
+// The average-attention layer's running sum, mean and gate-input copy for 4 columns of row m
+// (x = the values just stored for the layer input, rounded to the storage type like a reader
+// of x would see them).
+template <typename T>
+__device__ __forceinline__ void aan_accumulate(const AanFuse& a, int m, int c, int d, float4 x) {
+  const float4 xv = make_float4(to_f32(from_f32<T>(x.x)), to_f32(from_f32<T>(x.y)), to_f32(from_f32<T>(x.z)),
+                                to_f32(from_f32<T>(x.w)));
+  const int t = *a.t_dev;
+  float* sp = a.sum + (size_t)m * d + c;
+  float4 s = (t == 0) ? make_float4(0.f, 0.f, 0.f, 0.f) : *reinterpret_cast<const float4*>(sp);
+  s = make_float4(s.x + xv.x, s.y + xv.y, s.z + xv.z, s.w + xv.w);
+  *reinterpret_cast<float4*>(sp) = s;
+  const float inv = 1.0f / (float)(t + 1);
+  store4(reinterpret_cast<T*>(a.avg) + (size_t)m * d + c, make_float4(s.x * inv, s.y * inv, s.z * inv, s.w * inv));
+  store4(reinterpret_cast<T*>(a.cat) + (size_t)m * 2 * d + c, xv);
+}
+
 // ---------------------------------------------------------------- embedding
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const int* tok, int tok_stride, int rpg, const T* emb,
                                                     const float* pe, const int* t_dev, T* x, int rows, int d,
-                                                    int vocab, float scale, int* last_tok, int* anc, int ld_anc) {
+                                                    int vocab, float scale, int* last_tok, int* anc, int ld_anc,
+                                                    AanFuse aan) {
   const int r = blockIdx.x;
   if (r >= rows) return;
   const int hyp = r / rpg, i = r % rpg;
@@ -29,23 +47,27 @@ __global__ __launch_bounds__(256) void embed_kernel(const int* tok, int tok_stri
   for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
     const float4 ev = load4(e + c);
     const float4 pv = *reinterpret_cast<const float4*>(pp + c);
-    store4(x + (size_t)r * d + c,
-           make_float4(fmaf(ev.x, scale, pv.x), fmaf(ev.y, scale, pv.y), fmaf(ev.z, scale, pv.z),
-                       fmaf(ev.w, scale, pv.w)));
+    const float4 xv = make_float4(fmaf(ev.x, scale, pv.x), fmaf(ev.y, scale, pv.y), fmaf(ev.z, scale, pv.z),
+                                  fmaf(ev.w, scale, pv.w));
+    store4(x + (size_t)r * d + c, xv);
+    if (aan.sum) aan_accumulate<T>(aan, r, c, d, xv);
   }
 }
 
 hipError_t launch_embed(int dtype, const int* tok, int tok_stride, int rpg, const void* emb, const float* pe,
                         const int* t_dev, void* x, int rows, int d, int vocab, float scale, int* last_tok,
-                        int* anc, int ld_anc, hipStream_t stream) {
+                        int* anc, int ld_anc, hipStream_t stream, const AanFuse* aan) {
   if (rows <= 0) return hipSuccess;
+  AanFuse af{};
+  if (aan) af = *aan;
+  if (af.sum && (!t_dev || rpg != 1)) return hipErrorInvalidValue;   // cached decoding only
   const int threads = d / 4 >= 256 ? 256 : (d / 4 >= 128 ? 128 : 64);
   if (dtype == 1)
     hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(rows), dim3(threads), 0, stream, tok, tok_stride, rpg,
-                       (const bf16_t*)emb, pe, t_dev, (bf16_t*)x, rows, d, vocab, scale, last_tok, anc, ld_anc);
+                       (const bf16_t*)emb, pe, t_dev, (bf16_t*)x, rows, d, vocab, scale, last_tok, anc, ld_anc, af);
   else
     hipLaunchKernelGGL(embed_kernel<float>, dim3(rows), dim3(threads), 0, stream, tok, tok_stride, rpg,
-                       (const float*)emb, pe, t_dev, (float*)x, rows, d, vocab, scale, last_tok, anc, ld_anc);
+                       (const float*)emb, pe, t_dev, (float*)x, rows, d, vocab, scale, last_tok, anc, ld_anc, af);
   return hipGetLastError();
 }
 
@@ -132,7 +154,7 @@ __global__ __launch_bounds__(kLnMaxWaves * 64) void ln_reduce_kernel(const float
                                                                      const T* bias, const T* res, int ldr,
                                                                      const T* gamma, const T* beta, T* out, int ldo,
                                                                      float* out_f32, int M, int n, float eps,
-                                                                     LnStage2 s2) {
+                                                                     LnStage2 s2, AanFuse aan) {
   __shared__ float slots[4 * kLnMaxWaves];
   const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
   const int m = blockIdx.x;
@@ -163,25 +185,28 @@ __global__ __launch_bounds__(kLnMaxWaves * 64) void ln_reduce_kernel(const float
   if (active) {
     store4(out + (size_t)m * ldo + c, y);
     if (out_f32) *reinterpret_cast<float4*>(out_f32 + (size_t)m * n + c) = y;
+    if (aan.sum) aan_accumulate<T>(aan, m, c, n, y);   // the next layer is an average-attention layer
   }
 }
 
 hipError_t launch_ln_reduce(int dtype, const float* part, int nsplit, int ldp, const void* bias, const void* res, int ldr,
                             const void* gamma, const void* beta, void* out, int ldo, float* out_f32, int M, int n,
-                            float eps, hipStream_t stream, const LnStage2* stage2) {
+                            float eps, hipStream_t stream, const LnStage2* stage2, const AanFuse* aan) {
   if (M <= 0) return hipSuccess;
   if (n <= 0 || n > kLnMaxWaves * 256 || n % 4) return hipErrorInvalidValue;
   LnStage2 s2{};
   if (stage2) s2 = *stage2;
+  AanFuse af{};
+  if (aan) af = *aan;
   dim3 grid(M), block(64 * ((n / 4 + 63) / 64));
   if (dtype == 1)
     hipLaunchKernelGGL(ln_reduce_kernel<bf16_t>, grid, block, 0, stream, part, nsplit, ldp, (const bf16_t*)bias,
                        (const bf16_t*)res, ldr, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)out, ldo,
-                       out_f32, M, n, eps, s2);
+                       out_f32, M, n, eps, s2, af);
   else
     hipLaunchKernelGGL(ln_reduce_kernel<float>, grid, block, 0, stream, part, nsplit, ldp, (const float*)bias,
                        (const float*)res, ldr, (const float*)gamma, (const float*)beta, (float*)out, ldo, out_f32,
-                       M, n, eps, s2);
+                       M, n, eps, s2, af);
   return hipGetLastError();
 }
 
@@ -236,37 +261,8 @@ hipError_t launch_compact_S(const float* src, int ldS, float* dst, int rows_h, i
 }
 
 // ----------------------------------------------------------------- AAN stages
-// Running sum of the layer inputs (fp32 state), its mean over the t+1 positions,
-// and a copy of x into the left half of the gate GEMM's input [x ; g].
-template <typename T>
-__global__ __launch_bounds__(256) void aan_pre_kernel(float* sum, const T* x, T* avg, T* cat, const int* t_dev,
-                                                      int rows, int d) {
-  const size_t i4 = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-  if (i4 >= (size_t)rows * d) return;
-  const int r = (int)(i4 / d), c = (int)(i4 % d);
-  const int t = *t_dev;
-  const float4 xv = load4(x + i4);
-  float4 s = (t == 0) ? make_float4(0.f, 0.f, 0.f, 0.f) : *reinterpret_cast<const float4*>(sum + i4);
-  s.x += xv.x; s.y += xv.y; s.z += xv.z; s.w += xv.w;
-  *reinterpret_cast<float4*>(sum + i4) = s;
-  const float inv = 1.0f / (float)(t + 1);
-  store4(avg + i4, make_float4(s.x * inv, s.y * inv, s.z * inv, s.w * inv));
-  store4(cat + (size_t)r * 2 * d + c, xv);
-}
-hipError_t launch_aan_pre(int dtype, float* sum, const void* x, void* avg, void* cat, const int* t_dev, int rows,
-                          int d, hipStream_t stream) {
-  const size_t total = (size_t)rows * d / 4;
-  if (!total) return hipSuccess;
-  dim3 grid((unsigned)((total + 255) / 256));
-  if (dtype == 1)
-    hipLaunchKernelGGL(aan_pre_kernel<bf16_t>, grid, dim3(256), 0, stream, sum, (const bf16_t*)x, (bf16_t*)avg,
-                       (bf16_t*)cat, t_dev, rows, d);
-  else
-    hipLaunchKernelGGL(aan_pre_kernel<float>, grid, dim3(256), 0, stream, sum, (const float*)x, (float*)avg,
-                       (float*)cat, t_dev, rows, d);
-  return hipGetLastError();
-}
-
+// (cached decoding: the running sum and mean are produced by aan_accumulate above, inside the
+// launch that writes the layer input)
 // Nothing cached: the mean over positions 0..i of every position i of every hypothesis
 // (x is [hyps][np][d]); a thread owns 4 columns of one hypothesis and walks its positions,
 // adding in the order and precision of the running sum above.

@@ -331,7 +331,7 @@ int gemm(san_ctx* c, const void* A, int lda, const void* W, const void* bias, in
 // x_out = LayerNorm(res + A W^T + bias): split-K GEMM into fp32 partials, reduced
 // by the LayerNorm kernel.
 int gemm_ln(san_ctx* c, const void* A, int lda, const void* W, const void* bias, int M, int K, const void* res,
-            const void* g, const void* b, void* out, float* dbg, int* defer_ks = nullptr) {
+            const void* g, const void* b, void* out, float* dbg, int* defer_ks = nullptr, const AanFuse* aan = nullptr) {
   const int N = c->d;
   int ks = gemm_pick_ksplit(M, N, K, c->dt);
   while (ks > 1 && (size_t)ks * M * N > c->part_elems) ks /= 2;
@@ -344,19 +344,22 @@ int gemm_ln(san_ctx* c, const void* A, int lda, const void* W, const void* bias,
   }
   const int k0 = c->kind;
   c->kind = SAN_K_LN;
-  LAUNCH(c, launch_ln_reduce(c->dt, c->part, ks, N, bias, res, N, g, b, out, N, dbg, M, N, c->cfg.ln_eps, c->stream));
+  LAUNCH(c, launch_ln_reduce(c->dt, c->part, ks, N, bias, res, N, g, b, out, N, dbg, M, N, c->cfg.ln_eps, c->stream,
+                             nullptr, aan));
   c->kind = k0;
   return SAN_OK;
 }
 
-int ffn_block(san_ctx* c, const DecLayer* L, const EncLayer* E, int M, float* dbg) {
+// next_aan: the layer that consumes this block's output is an average-attention layer of a
+// cached decode; its running sum / mean / gate input are produced by the LayerNorm launch
+int ffn_block(san_ctx* c, const DecLayer* L, const EncLayer* E, int M, float* dbg, const AanFuse* next_aan = nullptr) {
   const void* w1 = L ? L->w1 : E->w1; const void* b1 = L ? L->b1 : E->b1;
   const void* w2 = L ? L->w2 : E->w2; const void* b2 = L ? L->b2 : E->b2;
   const void* g = L ? L->ln3g : E->ln2g; const void* b = L ? L->ln3b : E->ln2b;
   if (L) c->kind = SAN_K_FFN;
   int rc = gemm(c, c->x, c->d, w1, b1, M, c->F, c->d, 1, 0, c->hb, c->F);
   if (rc) return rc;
-  return gemm_ln(c, c->hb, c->F, w2, b2, M, c->F, c->x, g, b, c->x, dbg);
+  return gemm_ln(c, c->hb, c->F, w2, b2, M, c->F, c->x, g, b, c->x, dbg, nullptr, next_aan);
 }
 
 int dbg_copy(san_ctx* c, const void* src, int lds, float* dst, int rows) {
@@ -709,8 +712,12 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
   const int* group_map = c->batch != c->batch_enc ? c->group_map : nullptr;
   int rc;
   c->kind = SAN_K_MISC;
+  // an average-attention layer's running sum, mean and gate input come out of the launch that
+  // writes its input x (the embedding for layer 0, the previous layer's last LayerNorm otherwise)
+  auto aan_of = [&](int n) { return AanFuse{c->dec[n].aan_sum, c->ab, c->cat, c->t_dev}; };
+  const AanFuse aan0 = aan ? aan_of(0) : AanFuse{};
   LAUNCH(c, launch_embed(c->dt, tokens, 1, 1, c->tgt_emb, c->pe, c->t_dev, c->x, B, d, c->V,
-                         (float)std::sqrt((double)d), c->last_tok, c->anc, T, c->stream));
+                         (float)std::sqrt((double)d), c->last_tok, c->anc, T, c->stream, aan ? &aan0 : nullptr));
   const int Ld = (int)c->dec.size();
   for (int n = 0; n < Ld; ++n) {
     DecLayer& L = c->dec[n];
@@ -718,7 +725,6 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
     int ks_self = 1;
     if (aan) {
       c->kind = SAN_K_AAN;
-      LAUNCH(c, launch_aan_pre(c->dt, L.aan_sum, c->x, c->ab, c->cat, c->t_dev, B, d, c->stream));
       if ((rc = gemm(c, c->ab, d, L.aw1, L.ab1, B, c->F, d, 1, 0, c->hb, c->F))) return rc;
       // g goes to the right half of [x ; g]
       if ((rc = gemm(c, c->hb, c->F, L.aw2, L.ab2, B, d, c->F, 0, 0, (char*)c->cat + (size_t)d * c->esz, 2 * d))) return rc;
@@ -813,7 +819,8 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
     } else {
       if ((rc = gemm_ln(c, A, d, L.wo_c, L.bo_c, B, d, c->x, L.ln2g, L.ln2b, c->x, nullptr))) return rc;
     }
-    if ((rc = ffn_block(c, &L, nullptr, B, L.dbg_hidden))) return rc;
+    const AanFuse nxt = (aan && n + 1 < Ld) ? aan_of(n + 1) : AanFuse{};
+    if ((rc = ffn_block(c, &L, nullptr, B, L.dbg_hidden, nxt.sum ? &nxt : nullptr))) return rc;
   }
   c->kind = SAN_K_LOGITS;
   return gemm(c, c->x, d, c->w_out, nullptr, B, c->V, d, 0, 1, logits, c->V, 0, nullptr, 0, 0, nullptr, 0, 0, 0, false,
