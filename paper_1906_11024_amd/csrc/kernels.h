@@ -130,12 +130,26 @@ struct TopkHistory {
   const int* t_dev; const int* t0_dev;
   const int* row_map; int ld;
 };
+// tail (optional, needs k == beam <= 32): the per-sentence merge runs inside a wider kernel that then
+// applies the beam step's consequences for that sentence, so that a multi-step loop needs no further
+// launch before the next step's first projection:
+//   - the rows of the ancestry table (anc, columns < *t_dev) or of the AAN running sums
+//     (aan_sum [layers][layer_stride]) are permuted by the chosen parents, in place;
+//   - emb != nullptr: the next step's input is embedded for the sentence's rows,
+//     x[r] = emb[token] * scale + pe[*t_dev], last_tok[r] = token, anc[r][*t_dev] = r
+//     (skipped when *t_dev == max_t: there is no next position).
+// *t_dev must already count the step whose logits are being searched.
+struct BeamTail {
+  int* anc; int ld_anc; int max_t; const int* t_dev;
+  float* aan_sum; size_t layer_stride; int layers;
+  const void* emb; const float* pe; void* x; int d; float scale; int dtype;
+};
 // done (optional, eos_id >= 0): int[batch]; done[b] becomes 1 once every pick of sentence b is EOS,
 // *done_count counts such sentences
 hipError_t launch_topk(const float* logits, const float* cum, const int* last_tok, int eos_id, int batch, int beam,
                        int vocab, int k, float* cand_lp, int* cand_idx, int* out_tok, int* out_parent,
                        float* out_score, hipStream_t stream, const TopkHistory* hist = nullptr, int* done = nullptr,
-                       int* done_count = nullptr);
+                       int* done_count = nullptr, const BeamTail* tail = nullptr, int* last_tok_out = nullptr);
 // per sentence, in place: tab[r][j] = tab[parent[r]][j] for j < *t_dev
 hipError_t launch_reorder_table(int* tab, int ld, const int* parent, const int* t_dev, int batch, int beam,
                                 int max_t, hipStream_t stream);

@@ -122,6 +122,7 @@ struct san_ctx {
   hipGraphExec_t graph2 = nullptr;
   const void* graph_key[3] = {nullptr, nullptr, nullptr};
   int graph_rows = 0, graph_entry_rows = 0;
+  bool graph_fused = false;    // the captured steps rely on the fused beam tail (see loop_step)
   int* row_map = nullptr;      // san_decode_n after a compaction: current row -> row of the caller's arrays
   float* cum_final = nullptr;  // scores in the caller's numbering
   int* drop_dev = nullptr;     // [max_batch] step at which each of the caller's sentences left the batch
@@ -702,7 +703,8 @@ int san_rewind(san_ctx* c) {
   return SAN_OK;
 }
 
-static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
+// skip_embed: the input of this step was embedded by the previous step's beam tail (san_decode_n)
+static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits, bool skip_embed = false) {
   const int d = c->d, B = c->batch * c->cfg.beam, T = c->cfg.max_tgt_len;
   const float scale = 1.0f / std::sqrt((float)c->dh);
   const bool aan = c->cfg.self_kind == SAN_SELF_AAN, shareS = c->cfg.encdec_share == SAN_SHARE_S;
@@ -716,8 +718,9 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits) {
   // writes its input x (the embedding for layer 0, the previous layer's last LayerNorm otherwise)
   auto aan_of = [&](int n) { return AanFuse{c->dec[n].aan_sum, c->ab, c->cat, c->t_dev}; };
   const AanFuse aan0 = aan ? aan_of(0) : AanFuse{};
-  LAUNCH(c, launch_embed(c->dt, tokens, 1, 1, c->tgt_emb, c->pe, c->t_dev, c->x, B, d, c->V,
-                         (float)std::sqrt((double)d), c->last_tok, c->anc, T, c->stream, aan ? &aan0 : nullptr));
+  if (!skip_embed)
+    LAUNCH(c, launch_embed(c->dt, tokens, 1, 1, c->tgt_emb, c->pe, c->t_dev, c->x, B, d, c->V,
+                           (float)std::sqrt((double)d), c->last_tok, c->anc, T, c->stream, aan ? &aan0 : nullptr));
   const int Ld = (int)c->dec.size();
   for (int n = 0; n < Ld; ++n) {
     DecLayer& L = c->dec[n];
@@ -916,16 +919,20 @@ static int decode_uncached(san_ctx* c, const int32_t* tokens, float* logits) {
               c->V, 0, nullptr, 0, 0, nullptr, 0, 0, 0, false, 0, true);
 }
 
-int san_decode_step(san_ctx* c, const int32_t* tokens_dev, float* logits_dev) {
+static int decode_step_impl(san_ctx* c, const int32_t* tokens_dev, float* logits_dev, bool skip_embed) {
   if (!c) return SAN_EINVAL;
   if (!tokens_dev || !logits_dev) return fail(c, SAN_EINVAL, "san_decode_step: null argument");
   if (c->t < 0) return fail(c, SAN_ESTATE, "san_decode_step before san_encode");
   if (c->t >= c->cfg.max_tgt_len) return fail(c, SAN_ECAPACITY, "san_decode_step: max_tgt_len steps already decoded");
   c->launches = 0;
-  int rc = c->cfg.use_cache ? decode_cached(c, tokens_dev, logits_dev) : decode_uncached(c, tokens_dev, logits_dev);
+  int rc = c->cfg.use_cache ? decode_cached(c, tokens_dev, logits_dev, skip_embed) : decode_uncached(c, tokens_dev, logits_dev);
   if (rc) return rc;
   c->t += 1;   // the device-side counter was advanced by the output-layer kernel
   return prof_flush(c);
+}
+
+int san_decode_step(san_ctx* c, const int32_t* tokens_dev, float* logits_dev) {
+  return decode_step_impl(c, tokens_dev, logits_dev, false);
 }
 
 int san_topk(san_ctx* c, const float* logits_dev, const float* cum_score_dev, int32_t k, int32_t* out_token_dev,
@@ -1142,10 +1149,29 @@ int san_compact(san_ctx* c, const int32_t* keep, int32_t n_keep) {
 // One beam-search step on the ping-pong buffers: parity p reads set p, writes set p^1.
 // entry_rows > 0: the batch was compacted during this call; the history goes to the rows
 // the caller knows (row_map), entry_rows apart per step.
-static int loop_step(san_ctx* c, int p, int32_t* out_tokens, int32_t* out_parents, float* logits, int entry_rows) {
-  int rc = san_decode_step(c, c->pp_tok[p], logits);
+// fused: the per-sentence merge, the reordering of the per-row state and (dot-product
+// self-attention) the embedding of the next step's input run as one kernel, and this step's
+// input was embedded by the previous step's (or by the call's prologue).
+static int loop_step(san_ctx* c, int p, int32_t* out_tokens, int32_t* out_parents, float* logits, int entry_rows,
+                     bool fused) {
+  const bool aan = c->cfg.self_kind == SAN_SELF_AAN;
+  int rc = decode_step_impl(c, c->pp_tok[p], logits, fused && !aan);
   if (rc) return rc;
   TopkHistory h{out_tokens, out_parents, c->t_dev, c->t0_dev, entry_rows > 0 ? c->row_map : nullptr, entry_rows};
+  if (fused) {
+    BeamTail tl{};
+    tl.t_dev = c->t_dev; tl.max_t = c->cfg.max_tgt_len; tl.d = c->d; tl.dtype = c->dt;
+    if (aan) {
+      tl.aan_sum = c->aan_all; tl.layer_stride = (size_t)c->rows_max * c->d; tl.layers = (int)c->dec.size();
+    } else {
+      tl.anc = c->anc; tl.ld_anc = c->cfg.max_tgt_len;
+      tl.emb = c->tgt_emb; tl.pe = c->pe; tl.x = c->x; tl.scale = (float)std::sqrt((double)c->d);
+    }
+    HIP_TRY(c, launch_topk(logits, c->pp_cum[p], c->last_tok, c->cfg.eos_id, c->batch, c->cfg.beam, c->V, c->cfg.beam,
+                           c->cand_lp, c->cand_idx, c->pp_tok[p ^ 1], c->pp_par, c->pp_cum[p ^ 1], c->stream, &h,
+                           c->done_dev, c->done_dev + c->cfg.max_batch, &tl, c->last_tok));
+    return SAN_OK;
+  }
   HIP_TRY(c, launch_topk(logits, c->pp_cum[p], c->last_tok, c->cfg.eos_id, c->batch, c->cfg.beam, c->V, c->cfg.beam,
                          c->cand_lp, c->cand_idx, c->pp_tok[p ^ 1], c->pp_par, c->pp_cum[p ^ 1], c->stream, &h,
                          c->done_dev, c->done_dev + c->cfg.max_batch));
@@ -1188,6 +1214,15 @@ int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io
   HIP_TRY(c, hipMemcpyAsync(c->t0_dev, c->t_dev, 4, hipMemcpyDeviceToDevice, c->stream));
   if (compact)
     HIP_TRY(c, hipMemcpyAsync(c->row_map, c->iota_dev, (size_t)rows0 * 4, hipMemcpyDeviceToDevice, c->stream));
+  // The beam step's tail is fused (see loop_step) unless finished sentences may leave the batch
+  // during this call (their state is then regathered between steps) or nothing is cached.
+  const bool fused = c->cfg.use_cache && !compact && c->cfg.beam <= 32;
+  if (fused && c->cfg.self_kind != SAN_SELF_AAN) {
+    // the first step's input; every later one is embedded by the step before it
+    c->kind = SAN_K_MISC;
+    LAUNCH(c, launch_embed(c->dt, c->pp_tok[0], 1, 1, c->tgt_emb, c->pe, c->t_dev, c->x, rows0, c->d, c->V,
+                           (float)std::sqrt((double)c->d), c->last_tok, c->anc, c->cfg.max_tgt_len, c->stream));
+  }
   // sentence i of the current batch is sentence ent[i] of the caller's; drop_from[b]: steps done
   // when the caller's sentence b left the batch (-1: still in)
   std::vector<int> ent(batch0), drop_from(batch0, -1);
@@ -1245,18 +1280,19 @@ int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io
       // the graph holds two steps (parity 0 then 1); it is rebuilt when the caller's
       // buffers or the batch change
       const bool stale = !c->graph2 || c->graph_key[0] != out_tokens_dev || c->graph_key[1] != out_parents_dev ||
-                         c->graph_key[2] != logits_work_dev || c->graph_rows != rows || c->graph_entry_rows != entry_rows;
+                         c->graph_key[2] != logits_work_dev || c->graph_rows != rows ||
+                         c->graph_entry_rows != entry_rows || c->graph_fused != fused;
       if (stale && n - done >= 4) {
         if (c->graph2) { (void)hipGraphExecDestroy(c->graph2); c->graph2 = nullptr; }
         // two ordinary steps first, so that one-time set-up inside the launchers
         // (per-kernel attributes) has happened before anything is captured
         for (int i = 0; i < 2; ++i, ++done)
-          if ((rc = loop_step(c, done & 1, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows))) return rc;
+          if ((rc = loop_step(c, done & 1, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows, fused))) return rc;
         hipGraph_t g = nullptr;
         const int t_before = c->t;
         HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
-        rc = loop_step(c, 0, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows);
-        if (!rc) rc = loop_step(c, 1, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows);
+        rc = loop_step(c, 0, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows, fused);
+        if (!rc) rc = loop_step(c, 1, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows, fused);
         const hipError_t e = hipStreamEndCapture(c->stream, &g);
         c->t = t_before;   // capturing queued nothing
         if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
@@ -1267,8 +1303,9 @@ int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io
         c->graph_key[0] = out_tokens_dev; c->graph_key[1] = out_parents_dev; c->graph_key[2] = logits_work_dev;
         c->graph_rows = rows;
         c->graph_entry_rows = entry_rows;
+        c->graph_fused = fused;
       }
-      const bool fresh = c->graph2 && c->graph_rows == rows && c->graph_entry_rows == entry_rows &&
+      const bool fresh = c->graph2 && c->graph_rows == rows && c->graph_entry_rows == entry_rows && c->graph_fused == fused &&
                          c->graph_key[0] == out_tokens_dev && c->graph_key[1] == out_parents_dev &&
                          c->graph_key[2] == logits_work_dev;
       while (fresh && done + 2 <= n) {
@@ -1284,7 +1321,7 @@ int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io
     while (done < n) {
       if ((rc = check(action))) return rc;
       if (action != kGoOn) break;
-      if ((rc = loop_step(c, done & 1, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows))) return rc;
+      if ((rc = loop_step(c, done & 1, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows, fused))) return rc;
       ++done;
     }
   }

@@ -265,16 +265,16 @@ __global__ __launch_bounds__(kTopkThreads) void topk_row_kernel(const float* log
   }
 }
 
-// One wave per sentence: merge the beam*k candidates, keep the k best.
-__global__ __launch_bounds__(64) void topk_merge_kernel(const float* cand_lp, const int* cand_idx, const float* cum,
-                                                        int beam, int vocab, int k, int* out_tok, int* out_parent,
-                                                        float* out_score, TopkHistory hist, int eos_id, int* done,
-                                                        int* done_count) {
-  const int b = blockIdx.x, lane = threadIdx.x;
+// Merge of one sentence's beam*k candidates by one wave; lanes 0..k-1 end up with the k best.
+// Writes the picks, the optional history and the finished flag; returns this lane's pick.
+__device__ __forceinline__ Cand merge_sentence(int b, int lane, const float* cand_lp, const int* cand_idx, const float* cum,
+                                               int beam, int vocab, int k, int nsent, int* out_tok, int* out_parent,
+                                               float* out_score, const TopkHistory& hist, int eos_id, int* done,
+                                               int* done_count) {
   // multi-step decoding: this step's picks are also appended to the caller's
   // [step][rows] arrays; the step index comes from the device-side counters
   const long long hoff =
-      hist.tok ? (long long)(*hist.t_dev - 1 - *hist.t0_dev) * (hist.row_map ? hist.ld : (int)gridDim.x * k) : 0;
+      hist.tok ? (long long)(*hist.t_dev - 1 - *hist.t0_dev) * (hist.row_map ? hist.ld : nsent * k) : 0;
   const Cand best = wave_topk(
       [&](int q) {
         const int bi = q / k;
@@ -307,12 +307,128 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(const float* cand_lp, co
       atomicAdd(done_count, 1);
     }
   }
+  return best;
+}
+
+// One wave per sentence: merge the beam*k candidates, keep the k best.
+__global__ __launch_bounds__(64) void topk_merge_kernel(const float* cand_lp, const int* cand_idx, const float* cum,
+                                                        int beam, int vocab, int k, int* out_tok, int* out_parent,
+                                                        float* out_score, TopkHistory hist, int eos_id, int* done,
+                                                        int* done_count) {
+  merge_sentence(blockIdx.x, threadIdx.x, cand_lp, cand_idx, cum, beam, vocab, k, (int)gridDim.x, out_tok, out_parent,
+                 out_score, hist, eos_id, done, done_count);
+}
+
+// The merge, then what the beam step means for the sentence's state (see BeamTail): wave 0
+// merges, all waves permute the sentence's ancestry rows (or AAN sums) by the parents and embed
+// the chosen words as the next step's input.  MAXB = compile-time cap of the beam.
+constexpr int kTailThreads = 256;
+template <typename T, int MAXB>
+__global__ __launch_bounds__(kTailThreads) void beam_tail_kernel(const float* cand_lp, const int* cand_idx,
+                                                                 const float* cum, int beam, int vocab, int* out_tok,
+                                                                 int* out_parent, float* out_score, TopkHistory hist,
+                                                                 int eos_id, int* done, int* done_count, BeamTail tl,
+                                                                 int* last_tok) {
+  __shared__ int s_tok[kMaxK], s_par[kMaxK];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  if (tid < kWave) {
+    const Cand best = merge_sentence(b, tid, cand_lp, cand_idx, cum, beam, vocab, beam, (int)gridDim.x, out_tok,
+                                     out_parent, out_score, hist, eos_id, done, done_count);
+    if (tid < beam) {
+      const bool ok = best.i != kNone;
+      s_tok[tid] = ok ? best.i % vocab : 0;
+      s_par[tid] = ok ? best.i / vocab : 0;     // index inside the sentence
+    }
+  }
+  __syncthreads();
+  const int t_now = *tl.t_dev;                  // steps done, this one included
+  int pl[MAXB];
+#pragma unroll
+  for (int q = 0; q < MAXB; ++q) pl[q] = s_par[min(q, beam - 1)];
+  if (tl.anc) {
+    // row r of the table continues row parent[r]: a thread owns a column, reads it for every
+    // old row of the sentence, then writes the permuted rows (safe in place)
+    const int ncol = min(t_now, tl.max_t);
+    for (int j = tid; j < ncol; j += kTailThreads) {
+      int old[MAXB];
+#pragma unroll
+      for (int q = 0; q < MAXB; ++q) old[q] = tl.anc[(size_t)(b * beam + min(q, beam - 1)) * tl.ld_anc + j];
+#pragma unroll
+      for (int q = 0; q < MAXB; ++q) {
+        if (q < beam && pl[q] != q) {
+          int v = old[0];
+#pragma unroll
+          for (int s = 1; s < MAXB; ++s)
+            if (s == pl[q]) v = old[s];
+          tl.anc[(size_t)(b * beam + q) * tl.ld_anc + j] = v;
+        }
+      }
+    }
+  }
+  if (tl.aan_sum) {
+    const int d4 = tl.d / 4;
+    for (int w = tid; w < tl.layers * d4; w += kTailThreads) {
+      const int l = w / d4, c = (w - l * d4) * 4;
+      float* base = tl.aan_sum + (size_t)l * tl.layer_stride + (size_t)b * beam * tl.d + c;
+      float4 old[MAXB];
+#pragma unroll
+      for (int q = 0; q < MAXB; ++q) old[q] = *reinterpret_cast<const float4*>(base + (size_t)min(q, beam - 1) * tl.d);
+#pragma unroll
+      for (int q = 0; q < MAXB; ++q) {
+        if (q < beam && pl[q] != q) {
+          float4 v = old[0];
+#pragma unroll
+          for (int s = 1; s < MAXB; ++s)
+            if (s == pl[q]) v = old[s];
+          *reinterpret_cast<float4*>(base + (size_t)q * tl.d) = v;
+        }
+      }
+    }
+  }
+  if (tl.emb && t_now < tl.max_t) {
+    const T* emb = reinterpret_cast<const T*>(tl.emb);
+    T* x = reinterpret_cast<T*>(tl.x);
+    const float* pp = tl.pe + (size_t)t_now * tl.d;
+    const int d4 = tl.d / 4;
+    for (int w = tid; w < beam * d4; w += kTailThreads) {
+      const int q = w / d4, c = (w - q * d4) * 4;
+      const int id = min(max(s_tok[q], 0), vocab - 1);
+      const float4 ev = load4(emb + (size_t)id * tl.d + c);
+      const float4 pv = *reinterpret_cast<const float4*>(pp + c);
+      store4(x + (size_t)(b * beam + q) * tl.d + c,
+             make_float4(fmaf(ev.x, tl.scale, pv.x), fmaf(ev.y, tl.scale, pv.y), fmaf(ev.z, tl.scale, pv.z),
+                         fmaf(ev.w, tl.scale, pv.w)));
+    }
+    if (tid < beam) {
+      const int r = b * beam + tid;
+      last_tok[r] = s_tok[tid];
+      // the new position of every row is its own; written after the permutation above, which
+      // only touches columns < t_now
+      tl.anc[(size_t)r * tl.ld_anc + t_now] = r;
+    }
+  }
+}
+
+template <typename T>
+static void launch_tail_t(int batch, int beam, hipStream_t stream, const float* cand_lp, const int* cand_idx,
+                          const float* cum, int vocab, int* out_tok, int* out_parent, float* out_score,
+                          const TopkHistory& h, int eos_id, int* done, int* done_count, const BeamTail& tl, int* last_tok) {
+#define SAN_TAIL(MB)                                                                                              \
+  hipLaunchKernelGGL((beam_tail_kernel<T, MB>), dim3(batch), dim3(kTailThreads), 0, stream, cand_lp, cand_idx, cum, beam, \
+                     vocab, out_tok, out_parent, out_score, h, eos_id, done, done_count, tl, last_tok)
+  if (beam <= 4) SAN_TAIL(4);
+  else if (beam <= 8) SAN_TAIL(8);
+  else if (beam <= 16) SAN_TAIL(16);
+  else SAN_TAIL(32);
+#undef SAN_TAIL
 }
 
 hipError_t launch_topk(const float* logits, const float* cum, const int* last_tok, int eos_id, int batch, int beam,
                        int vocab, int k, float* cand_lp, int* cand_idx, int* out_tok, int* out_parent,
-                       float* out_score, hipStream_t stream, const TopkHistory* hist, int* done, int* done_count) {
+                       float* out_score, hipStream_t stream, const TopkHistory* hist, int* done, int* done_count,
+                       const BeamTail* tail, int* last_tok_out) {
   const int rows = batch * beam;
+  if (tail && (k != beam || beam > kMaxK || (tail->emb && (!tail->anc || !last_tok_out || tail->d % 4)))) return hipErrorInvalidValue;
   if (rows <= 0) return hipSuccess;
   if (vocab <= kTopkVpt * kTopkThreads)
     hipLaunchKernelGGL(topk_row_kernel<true>, dim3(rows), dim3(kTopkThreads), 0, stream, logits, last_tok, eos_id,
@@ -324,6 +440,15 @@ hipError_t launch_topk(const float* logits, const float* cum, const int* last_to
   if (e != hipSuccess) return e;
   TopkHistory h{};
   if (hist) h = *hist;
+  if (tail) {
+    if (tail->dtype == 1)
+      launch_tail_t<bf16_t>(batch, beam, stream, cand_lp, cand_idx, cum, vocab, out_tok, out_parent, out_score, h, eos_id,
+                            done_count ? done : nullptr, done_count, *tail, last_tok_out);
+    else
+      launch_tail_t<float>(batch, beam, stream, cand_lp, cand_idx, cum, vocab, out_tok, out_parent, out_score, h, eos_id,
+                           done_count ? done : nullptr, done_count, *tail, last_tok_out);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(topk_merge_kernel, dim3(batch), dim3(64), 0, stream, cand_lp, cand_idx, cum, beam, vocab, k,
                      out_tok, out_parent, out_score, h, eos_id, done_count ? done : nullptr, done_count);
   return hipGetLastError();

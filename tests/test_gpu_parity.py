@@ -548,10 +548,69 @@ def test_decode_n_equals_oracle_search(use_graph):
                 assert np.array_equal(got_tok[t], ref["tokens"][t]), (seed, rep, t)
                 assert np.array_equal(got_par[t], ref["parents"][t]), (seed, rep, t)
             np.testing.assert_allclose(got_cum, ref["scores"][N - 1], rtol=0, atol=1e-3)
+        # single calls after the loop on the same context (the loop's last beam tail has already
+        # embedded the next input: a single step embeds it again, to the same effect)
+        gpu.rewind()
+        tokens = torch.full((B,), wl.BOS_ID, dtype=torch.int32, device="cuda")
+        cum = torch.from_numpy(_cum0(B, beam)).cuda()
+        gpu.decode_n(7, tokens, cum, out_tok, out_par, logits, use_graph)
+        tokens = out_tok[6].clone()
+        o_tok = torch.empty((cfg["batch"], beam), dtype=torch.int32, device="cuda")
+        o_par = torch.empty((cfg["batch"], beam), dtype=torch.int32, device="cuda")
+        o_sc = torch.empty((cfg["batch"], beam), dtype=torch.float32, device="cuda")
+        for t in range(7, 12):
+            gpu.decode_step(tokens, logits)
+            gpu.topk(logits, cum, beam, o_tok, o_par, o_sc)
+            gpu.beam_reorder(o_par.reshape(-1))
+            tokens, cum = o_tok.reshape(-1).clone(), o_sc.reshape(-1).clone()
+            assert np.array_equal(tokens.cpu().numpy(), ref["tokens"][t]), (seed, t)
+        gpu.decode_n(11, tokens, cum, out_tok[12:], out_par[12:], logits, use_graph)      # and back to the loop
+        stream.synchronize()
+        assert np.array_equal(out_tok[22].cpu().numpy(), ref["tokens"][22])
         big_t = torch.zeros((30, B), dtype=torch.int32, device="cuda")
         with pytest.raises(sb.SanError) as e:      # 23 steps done, 30 more would pass max_tgt_len = 40
             gpu.decode_n(30, tokens, cum, big_t, big_t.clone(), logits, use_graph)
         assert e.value.code == sb.SAN_ECAPACITY
+        gpu.close()
+
+
+@pytest.mark.parametrize("use_graph", [False, True])
+def test_decode_n_aan_then_single_steps(use_graph):
+    """The multi-step loop with average-attention self layers (its beam tail permutes the running
+    sums), followed by single calls on the same context: tokens and parents of the oracle's search."""
+    cfg = mid_cfg(steps=24, self_kind="aan", self_pi=[1, 1, 1, 1])
+    beam, B, V, N, n1 = cfg["beam"], cfg["batch"] * cfg["beam"], cfg["V"], 20, 13
+    seed, w, src, lens, ref = hz.pick_seed_with_margin(cfg, cfg["self_pi"], cfg["encdec_pi"], "A", N, beam, 1e-3,
+                                                       out_scale=8.0, min_gap=1e-3, tries=40)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        gpu = hz.make_gpu(cfg, w)
+        gpu.encode(torch.from_numpy(src).cuda(), torch.from_numpy(lens).cuda())
+        logits = torch.empty((B, V), dtype=torch.float32, device="cuda")
+        for rep in range(2):
+            gpu.rewind()
+            tokens = torch.full((B,), wl.BOS_ID, dtype=torch.int32, device="cuda")
+            cum = torch.from_numpy(_cum0(B, beam)).cuda()
+            out_tok = torch.zeros((n1, B), dtype=torch.int32, device="cuda")
+            out_par = torch.zeros((n1, B), dtype=torch.int32, device="cuda")
+            gpu.decode_n(n1, tokens, cum, out_tok, out_par, logits, use_graph)
+            stream.synchronize()
+            got_tok, got_par = out_tok.cpu().numpy(), out_par.cpu().numpy()
+            for t in range(n1):
+                assert np.array_equal(got_tok[t], ref["tokens"][t]), (seed, rep, t)
+                assert np.array_equal(got_par[t], ref["parents"][t]), (seed, rep, t)
+            tokens = out_tok[n1 - 1].clone()
+            o_tok = torch.empty((cfg["batch"], beam), dtype=torch.int32, device="cuda")
+            o_par = torch.empty((cfg["batch"], beam), dtype=torch.int32, device="cuda")
+            o_sc = torch.empty((cfg["batch"], beam), dtype=torch.float32, device="cuda")
+            for t in range(n1, N):
+                gpu.decode_step(tokens, logits)
+                gpu.topk(logits, cum, beam, o_tok, o_par, o_sc)
+                gpu.beam_reorder(o_par.reshape(-1))
+                tokens, cum = o_tok.reshape(-1).clone(), o_sc.reshape(-1).clone()
+                assert np.array_equal(tokens.cpu().numpy(), ref["tokens"][t]), (seed, rep, t)
+                assert np.array_equal(o_par.reshape(-1).cpu().numpy(), ref["parents"][t]), (seed, rep, t)
+            np.testing.assert_allclose(cum.cpu().numpy(), ref["scores"][N - 1], rtol=0, atol=1e-3)
         gpu.close()
 
 
