@@ -128,6 +128,35 @@ class Runner:
         return times[len(times) // 2], times
 
 
+def loop_leg(torch, make_gpu, cfg, src, lens, use_graph, keep_logits, reps=5):
+    """ms per whole decode driven by san_decode_n: one host call per decode on a stream of its own
+    (the NULL stream cannot be captured); median of `reps` after one untimed decode."""
+    T, B = cfg["steps"], cfg["batch"] * cfg["beam"]
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        g = make_gpu()
+        r = Runner(torch, g, cfg, src, lens)
+        o_tok = torch.zeros((T, B), dtype=torch.int32, device="cuda")
+        o_par = torch.zeros((T, B), dtype=torch.int32, device="cuda")
+
+        def one_decode():
+            g.rewind()
+            cum = r.cum0.clone()
+            g.decode_n(T, r.bos, cum, o_tok, o_par, r.logits, use_graph, keep_logits=keep_logits)
+
+        one_decode()
+        st.synchronize()
+        ts = []
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            one_decode()
+            st.synchronize()
+            ts.append(time.perf_counter() - t0)
+        g.close()
+        del r
+    return float(np.median(ts))
+
+
 def ragged_finish(torch, gpu, cfg, src, lens, compact, reps=3):
     """Wall time of one decode in which sentence b is taken to end after
     T/2 + b*T/(2*batch) steps (a mix of lengths; the synthetic weights never emit the
@@ -424,32 +453,13 @@ def main():
             del r
         # the same decode driven by san_decode_n: one host call per decode, pairs of
         # steps replayed from a captured HIP graph (own stream: the NULL stream cannot be captured)
-        for name, use_graph in (("san_decode_n_eager", False), ("san_decode_n_graph", True)):
-            st = torch.cuda.Stream()
-            with torch.cuda.stream(st):
-                g = make(cfg["self_pi"], cfg["encdec_pi"])
-                r = Runner(torch, g, cfg, src, lens)
-                o_tok = torch.zeros((T, B), dtype=torch.int32, device="cuda")
-                o_par = torch.zeros((T, B), dtype=torch.int32, device="cuda")
-
-                def one_decode():
-                    g.rewind()
-                    cum = r.cum0.clone()
-                    g.decode_n(T, r.bos, cum, o_tok, o_par, r.logits, use_graph)
-
-                one_decode()
-                st.synchronize()
-                ts = []
-                for _ in range(5):
-                    t0 = time.perf_counter()
-                    one_decode()
-                    st.synchronize()
-                    ts.append(time.perf_counter() - t0)
-                w = float(np.median(ts))
-                compare[name] = {"tokens_per_s": B * T / w, "ms_per_step": w / T * 1e3, "steps": T,
-                                 "window": "one whole decode per repetition, median of 5"}
-                g.close()
-                del r
+        # (default: the output layer hands the search per-tile candidates; *_logits: SAN_LOOP_LOGITS, the
+        # logits are stored and read back as in the separate calls)
+        for name, use_graph, keep in (("san_decode_n_eager", False, False), ("san_decode_n_graph", True, False),
+                                      ("san_decode_n_graph_logits", True, True)):
+            w = loop_leg(torch, lambda: make(cfg["self_pi"], cfg["encdec_pi"]), cfg, src, lens, use_graph, keep)
+            compare[name] = {"tokens_per_s": B * T / w, "ms_per_step": w / T * 1e3, "steps": T,
+                             "window": "one whole decode per repetition, median of 5"}
         # sentences of different lengths: finished ones leave the batch (san_compact) or ride along
         rf = {}
         for name, cmpct in (("fixed_batch", False), ("compacting", True)):
@@ -496,6 +506,12 @@ def main():
             ent["step_roofline"] = step_roofline(c2, e2, c2["self_pi"], c2["encdec_pi"], float(lens2.mean()), w / T2 * 1e3)
             g.close()
             del r
+            blob2 = wl.pack_weights(c2, wl.make_weights(c2, seed=0))
+            wl_ = loop_leg(torch, lambda: sb.San(sb.make_config(c2), blob2, c2["self_pi"], c2["encdec_pi"]), c2, src2,
+                           lens2, False, False, reps=3)
+            del blob2
+            ent["san_decode_n"] = {"ms_per_step": wl_ / T2 * 1e3, "tokens_per_s": B2 * T2 / wl_,
+                                   "window": "one whole decode per host call, median of 3"}
             torch.cuda.empty_cache()
             configs[name] = ent
 

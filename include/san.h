@@ -212,7 +212,8 @@ SAN_API int san_debug_get(san_ctx* ctx, int32_t what, int32_t layer, void* dst_d
  *   cum_io_dev      DEVICE fp32  [rows]     cumulative scores, in: before, out: after
  *   out_tokens_dev  DEVICE int32 [n][rows]  token chosen for every row at every step
  *   out_parents_dev DEVICE int32 [n][rows]  parent row of every row at every step
- *   logits_work_dev DEVICE fp32  [rows][vocab] scratch, 16-byte aligned
+ *   logits_work_dev DEVICE fp32  [rows][vocab] scratch, 16-byte aligned; with use_cache = 1
+ *                                           it is only written under SAN_LOOP_LOGITS
  * flags (SAN_LOOP_*, or-ed):
  *   SAN_LOOP_GRAPH: pairs of steps are replayed from a captured HIP graph (needs a
  *     stream other than the NULL stream and use_cache = 1; the graph is
@@ -227,9 +228,16 @@ SAN_API int san_debug_get(san_ctx* ctx, int32_t what, int32_t layer, void* dst_d
  *     without the flag except where two candidates' scores are within rounding
  *     (a smaller batch may run other GEMM tiles).  On return the context's batch
  *     is the sentences still unfinished (san_active); san_rewind restores it.
- * Allocates its small ping-pong buffers on first use.
+ *   SAN_LOOP_LOGITS: every step stores its logits in logits_work_dev (on return it
+ *     holds the last step's) and the search reads them back, as the separate calls do.
+ *     Without it (use_cache = 1, beam <= 8, at most 5120 / (2 beam) column tiles of the
+ *     output layer) the output layer hands the search, per row and column tile, the
+ *     tile's maximum, sum of exponentials and largest entries instead: the same tokens
+ *     and parents, scores equal up to the rounding of the log-sum-exp, and neither the
+ *     write nor the read of rows x vocab logits.
+ * Allocates its ping-pong buffers (and that candidate workspace) on first use.
  * Errors: SAN_ESTATE, SAN_ECAPACITY (step + n > max_tgt_len), SAN_EINVAL. */
-enum { SAN_LOOP_GRAPH = 1, SAN_LOOP_COMPACT = 2 };
+enum { SAN_LOOP_GRAPH = 1, SAN_LOOP_COMPACT = 2, SAN_LOOP_LOGITS = 4 };
 SAN_API int san_decode_n(san_ctx* ctx, int32_t n, const int32_t* tokens_dev, float* cum_io_dev,
                          int32_t* out_tokens_dev, int32_t* out_parents_dev, float* logits_work_dev,
                          int32_t flags);

@@ -26,7 +26,7 @@ EXPORTS = ["san_weight_bytes", "san_init", "san_encode", "san_rewind", "san_deco
            "san_policy_accumulate", "san_policy_read", "san_policy_search", "san_decode_n", "san_stream_read", "san_finished",
            "san_done_flags", "san_compact", "san_active", "san_topk_noalloc"]
 
-SAN_LOOP_GRAPH, SAN_LOOP_COMPACT = 1, 2
+SAN_LOOP_GRAPH, SAN_LOOP_COMPACT, SAN_LOOP_LOGITS = 1, 2, 4
 
 KINDS = ["misc", "proj", "attn_self", "attn_apply", "out", "ln", "attn_ctx", "attn_ctx_apply", "ffn", "logits",
          "topk", "reorder", "aan"]
@@ -320,7 +320,8 @@ class San:
         self._check(self._l.san_profile_read(self._h, ms, n, 1 if reset else 0))
         return {k: (ms[i], int(n[i])) for i, k in enumerate(KINDS)}
 
-    def decode_n(self, n, tokens, cum_io, out_tokens, out_parents, logits_work, use_graph=False, compact=False):
+    def decode_n(self, n, tokens, cum_io, out_tokens, out_parents, logits_work, use_graph=False, compact=False,
+                 keep_logits=False):
         torch = self._torch
         self._want(tokens, torch.int32, self.rows)
         self._want(cum_io, torch.float32, self.rows)
@@ -329,7 +330,8 @@ class San:
         self._want(logits_work, torch.float32, self.rows * self.cfg.vocab)
         self._check(self._l.san_decode_n(self._h, n, self._p(tokens), self._p(cum_io), self._p(out_tokens),
                                          self._p(out_parents), self._p(logits_work),
-                                         (SAN_LOOP_GRAPH if use_graph else 0) | (SAN_LOOP_COMPACT if compact else 0)))
+                                         (SAN_LOOP_GRAPH if use_graph else 0) | (SAN_LOOP_COMPACT if compact else 0) |
+                                         (SAN_LOOP_LOGITS if keep_logits else 0)))
         if compact:
             self._sync_batch()
 

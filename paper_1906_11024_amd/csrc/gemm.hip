@@ -49,7 +49,30 @@ template <> __device__ __forceinline__ void mma_frag<bf16_t>(f32x16& acc, const 
 // CB = bytes of k per row in one LDS stage (128 or 256); rows are padded by 16
 // bytes, which keeps the 16-byte fragment reads of 16 neighbouring lanes on
 // distinct banks for both sizes.
-template <typename T, int WM, int WN, int TM, int TN, int KW, int D, int CB>
+// Maximum over each aligned group of 16 lanes, in every lane: four v_max_f32 with DPP operands.
+// Written out because the compiler spends five instructions per step on fmaxf(v, dpp(v)) (a
+// zeroed destination, the move, two canonicalising maxima, the maximum).  The waits cover
+// the DPP read-after-write hazards, which the compiler cannot see inside the block.
+__device__ __forceinline__ float group16_max(float v) {
+  float r;
+  asm("s_nop 4\n\t"
+      "v_max_f32_dpp %0, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\t"
+      "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\t"
+      "v_max_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\t"
+      "v_max_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf"
+      : "=v"(r)
+      : "v"(v));
+  return r;
+}
+
+// CAND: the tile is not stored.  Its rows go through LDS to groups of 16 lanes that
+// reduce each row of BN columns to (max, sum of exp(x - max)) and a few entries that
+// include its p.cand_k largest (see GemmParams::cand_*): the beam step needs nothing
+// else of the output layer.
+template <typename T, int WM, int WN, int TM, int TN, int KW, int D, int CB, bool CAND>
 __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
   constexpr int kRowBytes = CB + 16;
   constexpr int SEGS = CB / 16;                      // 16-byte segments of a row chunk
@@ -260,6 +283,128 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
             acc[i][j][v] += red[((((g - 1) * (WM * WN) + w_in) * (TM * TN) + i * TN + j) * 16 + v) * 64 + lane];
   }
 
+  if constexpr (CAND) {
+    static_assert(KW == 1, "the tile is complete in every wave");
+    constexpr int LDW = BN + 4;                    // fp32 words per LDS row (16-byte multiple, rows 4 banks apart)
+    constexpr int PR = BM * LDW * 4 <= STAGE ? BM : (BM / 2 * LDW * 4 <= STAGE ? BM / 2 : BM / 4);   // rows per pass
+    constexpr int VPL = BN / 16;                   // values of a row per lane
+    constexpr int NGRP = NG / 16;                  // 16-lane groups, one row each at a time
+    static_assert(PR % 32 == 0 && PR * LDW * 4 <= STAGE && PR % NGRP == 0 && VPL % 4 == 0, "candidate pass shape");
+    constexpr int kNoCol = 0x7fffffff;
+    float* tile = reinterpret_cast<float*>(smem);
+    const int l16 = lane & 15, grp = tid >> 4;
+    const int kc = p.cand_k, ntiles = p.cand_tiles, slots = 2 * p.cand_k;   // slots <= 16 lanes
+    for (int pass = 0; pass < BM / PR; ++pass) {
+      __syncthreads();   // the k loop's stages (or the previous pass's rows) are dead
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int rb = (wm * TM + i) * 32 - pass * PR;
+        if (rb < 0 || rb >= PR) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int col = (wn * TN + j) * 32 + l32;
+          const bool live = n0 + col < p.N;
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            tile[(rb + (v >> 2) * 8 + kh * 4 + (v & 3)) * LDW + col] = live ? acc[i][j][v] : -INFINITY;
+        }
+      }
+      __syncthreads();
+      for (int r = grp; r < PR; r += NGRP) {
+        // lane l holds columns c*64 + 4*l .. +3 (c = 0 .. VPL/4-1): val[q] is column (q/4)*64 + 4*l + q%4,
+        // ascending in q
+        float val[VPL];
+        const float* rp = tile + r * LDW + 4 * l16;
+#pragma unroll
+        for (int c = 0; c < VPL / 4; ++c) {
+          const float4 q4 = *reinterpret_cast<const float4*>(rp + c * 64);
+          val[4 * c] = q4.x; val[4 * c + 1] = q4.y; val[4 * c + 2] = q4.z; val[4 * c + 3] = q4.w;
+        }
+        float lm = val[0];
+#pragma unroll
+        for (int q = 1; q < VPL; ++q) lm = fmaxf(lm, val[q]);
+        const float row_m = group16_max(lm);       // finite: a tile has at least one live column
+        // Threshold: the kc-th largest distinct lane maximum.  At least kc entries of the row are >= it,
+        // so the row's kc largest all are, and usually hardly any other entry is.
+        float thr = row_m;
+        for (int round = 1; round < kc; ++round) thr = group16_max(lm < thr ? lm : -INFINITY);
+        float es = 0.f;
+        int cnt = 0;
+        const float nm2 = -row_m * 1.44269504088896341f;
+#pragma unroll
+        for (int q = 0; q < VPL; ++q) {
+          es += __builtin_amdgcn_exp2f(fmaf(val[q], 1.44269504088896341f, nm2));   // 0 for the columns past N (-inf)
+          cnt += val[q] >= thr ? 1 : 0;
+        }
+        const float row_s = group_sum<16>(es);
+        // entries >= thr go to the tile's slots in lane order: prefix count over the 16 lanes
+        int incl = cnt;
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x111, 0xF, 0xF, true);   // row_shr:1, zero shifted in
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x112, 0xF, 0xF, true);   // row_shr:2
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x114, 0xF, 0xF, true);   // row_shr:4
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x118, 0xF, 0xF, true);   // row_shr:8
+        int total = cnt;
+        total += dpp_mov_i<kDppQuadSwap1>(total);
+        total += dpp_mov_i<kDppQuadSwap2>(total);
+        total += dpp_mov_i<kDppRowHalfMirror>(total);
+        total += dpp_mov_i<kDppRowMirror>(total);
+        const int m = m0 + pass * PR + r;
+        const bool row_live = m < p.M;
+        const size_t slot = ((size_t)min(m, p.M - 1) * ntiles + tile_x) * slots;
+        if (total <= slots) {
+          int pos = incl - cnt;
+#pragma unroll
+          for (int q = 0; q < VPL; ++q) {
+            if (val[q] >= thr) {
+              if (row_live) {
+                p.cand_v[slot + pos] = val[q];
+                p.cand_i[slot + pos] = n0 + (q >> 2) * 64 + 4 * l16 + (q & 3);
+              }
+              ++pos;
+            }
+          }
+          if (row_live && l16 >= total && l16 < slots) {
+            p.cand_v[slot + l16] = -INFINITY;
+            p.cand_i[slot + l16] = kNoCol;
+          }
+        } else {
+          // too many entries at the threshold (masses of equal values, or fewer than kc live columns):
+          // kc rounds, each taking the best entry left (higher value, then lower column)
+          float out_v = -INFINITY;
+          int out_c = kNoCol;
+          for (int round = 0; round < kc; ++round) {
+            float bv = val[0];
+            int bq = 0;
+#pragma unroll
+            for (int q = 1; q < VPL; ++q)
+              if (val[q] > bv) { bv = val[q]; bq = q; }
+            int bc = (bq >> 2) * 64 + 4 * l16 + (bq & 3);
+#define SAN_BEST16(CTRL)                                                        \
+            {                                                                    \
+              const float ov_ = dpp_mov<CTRL>(bv);                               \
+              const int oc_ = dpp_mov_i<CTRL>(bc);                               \
+              if (ov_ > bv || (ov_ == bv && oc_ < bc)) { bv = ov_; bc = oc_; }   \
+            }
+            SAN_BEST16(kDppQuadSwap1) SAN_BEST16(kDppQuadSwap2) SAN_BEST16(kDppRowHalfMirror) SAN_BEST16(kDppRowMirror)
+#undef SAN_BEST16
+            if (l16 == round) { out_v = bv; out_c = bc; }
+#pragma unroll
+            for (int q = 0; q < VPL; ++q)
+              if ((q >> 2) * 64 + 4 * l16 + (q & 3) == bc) val[q] = -INFINITY;
+          }
+          if (row_live && l16 < slots) {
+            p.cand_v[slot + l16] = out_v;
+            p.cand_i[slot + l16] = out_v == -INFINITY ? kNoCol : n0 + out_c;
+          }
+        }
+        if (row_live && l16 == 0)
+          *reinterpret_cast<float2*>(p.cand_ms + ((size_t)m * ntiles + tile_x) * 2) = make_float2(row_m, row_s);
+      }
+    }
+    if (p.bump && tile_x == 0 && tile_y == 0 && tid == 0) *p.bump = *p.bump + 1;
+    return;
+  }
+
   // acc[i][j][v]: output row m = tile_m + (v/4)*8 + kh*4 + (v%4), column n = tile_n + l32.
   // For a fixed v the 32 lanes of a half-wave hold 32 consecutive columns of one
   // row, so every store instruction writes two contiguous 128-byte (fp32) row
@@ -316,7 +461,7 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
   if (p.bump && tile_x == 0 && tile_y == 0 && tid == 0) *p.bump = *p.bump + 1;
 }
 
-template <typename T, int WM, int WN, int TM, int TN, int KW, int D, int CB = 128>
+template <typename T, int WM, int WN, int TM, int TN, int KW, int D, int CB = 128, bool CAND = false>
 static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
   constexpr int BM = 32 * WM * TM, BN = 32 * WN * TN;
   constexpr int kRowBytes = CB + 16;
@@ -331,7 +476,7 @@ static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
     if (e != hipSuccess) return e;
     const unsigned long long bit = 1ull << (dev & 63);
     if (!(raised.load(std::memory_order_acquire) & bit)) {
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, WM, WN, TM, TN, KW, D, CB>),
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, WM, WN, TM, TN, KW, D, CB, CAND>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
       if (e != hipSuccess) return e;
       raised.fetch_or(bit, std::memory_order_release);
@@ -347,7 +492,7 @@ static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
     q.xcd_rows = (int)grid.y;
     grid = dim3((grid.x + 7) / 8 * 8 * grid.y, 1, 1);
   }
-  hipLaunchKernelGGL((gemm_kernel<T, WM, WN, TM, TN, KW, D, CB>), grid, dim3(WM * WN * KW * 64), smem, stream, q);
+  hipLaunchKernelGGL((gemm_kernel<T, WM, WN, TM, TN, KW, D, CB, CAND>), grid, dim3(WM * WN * KW * 64), smem, stream, q);
   return hipGetLastError();
 }
 
@@ -389,6 +534,33 @@ int gemm_pick_ksplit(int M, int N, int K, int dtype) {
   return ks;
 }
 
+// width of the column tiles a GEMM with out_kind 3 cuts the N columns into
+static int cand_pick_tile(int M, int N, int K, int dtype) { return gemm_pick_tile(M, N, K, dtype, false); }
+int gemm_cand_tile_n(int M, int N, int K, int dtype) {
+  const int tile = cand_pick_tile(M, N, K, dtype);
+  if (tile == 2) return 256;
+  if (tile == 1 || tile == 3) return 128;
+  return 64;
+}
+
+// out_kind 3: the tiles whose k range is whole in every wave, with the candidate epilogue
+static hipError_t launch_gemm_cand(int dtype, const GemmParams& p, hipStream_t stream) {
+  const int bn = gemm_cand_tile_n(p.M, p.N, p.K, dtype);
+  if (p.cand_k < 1 || p.cand_k > kGemmCandMaxK || !p.cand_ms || !p.cand_v || !p.cand_i || p.ksplit != 1 ||
+      p.cand_tiles != (p.N + bn - 1) / bn)
+    return hipErrorInvalidValue;
+  const int tile = cand_pick_tile(p.M, p.N, p.K, dtype);
+  if (dtype == 1) {
+    if (tile == 2) return launch_tile<bf16_t, 4, 4, 2, 2, 1, 2, 128, true>(p, stream);
+    if (tile == 3) return launch_tile<bf16_t, 2, 4, 1, 1, 1, 2, 256, true>(p, stream);
+    if (tile == 1) return launch_tile<bf16_t, 4, 2, 1, 2, 1, 2, 128, true>(p, stream);
+    if (p.K % 128 == 0) return launch_tile<bf16_t, 2, 2, 1, 1, 1, 2, 256, true>(p, stream);
+    return launch_tile<bf16_t, 2, 2, 1, 1, 1, 4, 128, true>(p, stream);
+  }
+  if (tile == 1) return launch_tile<float, 4, 4, 1, 1, 1, 2, 128, true>(p, stream);
+  return launch_tile<float, 2, 2, 1, 1, 1, 4, 128, true>(p, stream);
+}
+
 hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
   if (p.M <= 0 || p.N <= 0) return hipSuccess;
   // bf16 MFMAs retire a 128-byte chunk four times faster than fp32 ones, so bf16
@@ -397,6 +569,7 @@ hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream) {
   const int epc = dtype == 1 ? 64 : 32;
   if (p.K <= 0 || p.K % epc != 0 || p.ksplit < 1) return hipErrorInvalidValue;
   if (p.ksplit > 1 && p.out_kind != 2) return hipErrorInvalidValue;   // only partial outputs may be split across blocks
+  if (p.out_kind == 3) return launch_gemm_cand(dtype, p, stream);
   int tile = gemm_pick_tile(p.M, p.N, p.K, dtype, p.out_kind == 2);
   if (p.ksplit > 1 && tile != 3) tile = 0;   // only the small tiles split k across blocks
   // A wave's MFMA chain over the whole k range is what bounds a small GEMM, and

@@ -14,6 +14,13 @@ namespace san {
 //   out_kind 0: store as T;  1: store fp32;  2: fp32 split-K partials
 //   [ksplit][M][N] at out[0] (no bias, no ReLU; the consumer reduces them).
 //   ksplit > 1 is only allowed with out_kind 2.
+//   out_kind 3: nothing of the product is stored.  The N columns are cut into
+//   cand_tiles tiles of gemm_cand_tile_n() columns; for every row m and tile x the
+//   kernel writes the tile's maximum and sum of exp(value - maximum) to
+//   cand_ms[m][x][2], and to the 2 * cand_k slots cand_v / cand_i [m][x][2 * cand_k]
+//   a set of (value, column) entries, in no particular order, that contains the tile's
+//   cand_k largest (higher value first, then lower column); unused slots hold
+//   (-inf, INT_MAX).  The bias is added; no ReLU, no segments.
 //   bump: if not null, *bump is incremented once by the kernel (step counter).
 struct GemmParams {
   const void* A; int lda;
@@ -26,11 +33,15 @@ struct GemmParams {
   int M, N, K;                // K % (128 / sizeof(T)) == 0
   int relu, out_kind, ksplit;
   int xcd_rows, cps;           // set by the launcher (tile-to-XCD mapping, k chunks per split), callers leave them alone
+  int cand_k, cand_tiles;      // out_kind 3
+  float* cand_ms; float* cand_v; int* cand_i;
 };
+constexpr int kGemmCandMaxK = 8;
 hipError_t launch_gemm(int dtype, const GemmParams& p, hipStream_t stream);
 // split factor that fills the chip for an M x N x K product (1 when the tiles
 // alone already do)
 int gemm_pick_ksplit(int M, int N, int K, int dtype);
+int gemm_cand_tile_n(int M, int N, int K, int dtype);
 
 // ------------------------------------------------------------------ attention
 // One kernel for every attention in the model.  A wave owns one head of one
@@ -150,6 +161,15 @@ hipError_t launch_topk(const float* logits, const float* cum, const int* last_to
                        int vocab, int k, float* cand_lp, int* cand_idx, int* out_tok, int* out_parent,
                        float* out_score, hipStream_t stream, const TopkHistory* hist = nullptr, int* done = nullptr,
                        int* done_count = nullptr, const BeamTail* tail = nullptr, int* last_tok_out = nullptr);
+// The same search fed by the output layer's per-tile candidates (GemmParams out_kind 3 with
+// cand_k == k) instead of the logits: ms [rows][ntiles][2], cv / ci [rows][ntiles][2 k].
+// topk_cands_fit: whether ntiles * 2 k candidate slots per row are within what the kernel holds.
+bool topk_cands_fit(int ntiles, int k);
+hipError_t launch_topk_cands(const float* ms, const float* cv, const int* ci, int ntiles, const float* cum,
+                             const int* last_tok, int eos_id, int batch, int beam, int vocab, int k, float* cand_lp,
+                             int* cand_idx, int* out_tok, int* out_parent, float* out_score, hipStream_t stream,
+                             const TopkHistory* hist = nullptr, int* done = nullptr, int* done_count = nullptr,
+                             const BeamTail* tail = nullptr, int* last_tok_out = nullptr);
 // per sentence, in place: tab[r][j] = tab[parent[r]][j] for j < *t_dev
 hipError_t launch_reorder_table(int* tab, int ld, const int* parent, const int* t_dev, int batch, int beam,
                                 int max_t, hipStream_t stream);

@@ -122,7 +122,7 @@ struct san_ctx {
   hipGraphExec_t graph2 = nullptr;
   const void* graph_key[3] = {nullptr, nullptr, nullptr};
   int graph_rows = 0, graph_entry_rows = 0;
-  bool graph_fused = false;    // the captured steps rely on the fused beam tail (see loop_step)
+  int graph_fused = 0;         // loop mode of the captured steps (see loop_step)
   int* row_map = nullptr;      // san_decode_n after a compaction: current row -> row of the caller's arrays
   float* cum_final = nullptr;  // scores in the caller's numbering
   int* drop_dev = nullptr;     // [max_batch] step at which each of the caller's sentences left the batch
@@ -140,6 +140,11 @@ struct san_ctx {
   std::vector<int> active;     // host copy of group_map
   float* cand_lp = nullptr;
   int* cand_idx = nullptr;
+  // san_decode_n: the output layer hands the beam step per-tile candidates instead of logits
+  float* part_ms = nullptr;    // [rows][tiles][2]
+  float* part_cv = nullptr;    // [rows][tiles][2 beam]
+  int* part_ci = nullptr;
+  int cand_tiles = 0;          // > 0 while a step of the loop runs in that mode: tiles per row
   // state
   int batch = 0, max_src = 0, t = -1;
   size_t weight_bytes = 0, state_bytes = 0;
@@ -826,6 +831,17 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits, bool 
     if ((rc = ffn_block(c, &L, nullptr, B, L.dbg_hidden, nxt.sum ? &nxt : nullptr))) return rc;
   }
   c->kind = SAN_K_LOGITS;
+  if (c->cand_tiles > 0) {
+    GemmParams p{};
+    p.A = c->x; p.lda = d; p.W = c->w_out;
+    p.M = B; p.N = c->V; p.K = d; p.out_kind = 3; p.ksplit = 1;
+    p.seg_w = 1 << 30;
+    p.bump = c->t_dev;
+    p.cand_k = c->cfg.beam; p.cand_tiles = c->cand_tiles;
+    p.cand_ms = c->part_ms; p.cand_v = c->part_cv; p.cand_i = c->part_ci;
+    LAUNCH(c, launch_gemm(c->dt, p, c->stream));
+    return SAN_OK;
+  }
   return gemm(c, c->x, d, c->w_out, nullptr, B, c->V, d, 0, 1, logits, c->V, 0, nullptr, 0, 0, nullptr, 0, 0, 0, false,
               0, true);
 }
@@ -1146,16 +1162,32 @@ int san_compact(san_ctx* c, const int32_t* keep, int32_t n_keep) {
   return SAN_OK;
 }
 
+// Column tiles per row when the loop's output layer emits candidates for `rows` rows; 0: that mode
+// is off (beam too wide for the epilogue, too many candidates per row, buffers not there).
+static int loop_cand_tiles(const san_ctx* c, int rows) {
+  if (!c->part_ms || c->cfg.beam > kGemmCandMaxK || rows <= 0) return 0;
+  const int bn = gemm_cand_tile_n(rows, c->V, c->d, c->dt);
+  const int tiles = (c->V + bn - 1) / bn;
+  return topk_cands_fit(tiles, c->cfg.beam) ? tiles : 0;
+}
+
 // One beam-search step on the ping-pong buffers: parity p reads set p, writes set p^1.
 // entry_rows > 0: the batch was compacted during this call; the history goes to the rows
 // the caller knows (row_map), entry_rows apart per step.
-// fused: the per-sentence merge, the reordering of the per-row state and (dot-product
+// mode & 1 (fused): the per-sentence merge, the reordering of the per-row state and (dot-product
 // self-attention) the embedding of the next step's input run as one kernel, and this step's
-// input was embedded by the previous step's (or by the call's prologue).
+// input was embedded by the previous step's (or by the call's prologue).  mode & 2: the output
+// layer feeds the beam step per-tile candidates and `logits` is not written.
 static int loop_step(san_ctx* c, int p, int32_t* out_tokens, int32_t* out_parents, float* logits, int entry_rows,
-                     bool fused) {
-  const bool aan = c->cfg.self_kind == SAN_SELF_AAN;
+                     int mode) {
+  const bool aan = c->cfg.self_kind == SAN_SELF_AAN, fused = (mode & 1) != 0;
+  // Nobody outside the loop sees a step's logits, and the beam step needs only each row's
+  // log-sum-exp and `beam` largest entries: the output layer then emits those per column tile and
+  // the [rows][vocab] array is neither written nor read.
+  const int tiles = (mode & 2) ? loop_cand_tiles(c, c->batch * c->cfg.beam) : 0;
+  c->cand_tiles = tiles;
   int rc = decode_step_impl(c, c->pp_tok[p], logits, fused && !aan);
+  c->cand_tiles = 0;
   if (rc) return rc;
   TopkHistory h{out_tokens, out_parents, c->t_dev, c->t0_dev, entry_rows > 0 ? c->row_map : nullptr, entry_rows};
   if (fused) {
@@ -1167,14 +1199,26 @@ static int loop_step(san_ctx* c, int p, int32_t* out_tokens, int32_t* out_parent
       tl.anc = c->anc; tl.ld_anc = c->cfg.max_tgt_len;
       tl.emb = c->tgt_emb; tl.pe = c->pe; tl.x = c->x; tl.scale = (float)std::sqrt((double)c->d);
     }
-    HIP_TRY(c, launch_topk(logits, c->pp_cum[p], c->last_tok, c->cfg.eos_id, c->batch, c->cfg.beam, c->V, c->cfg.beam,
-                           c->cand_lp, c->cand_idx, c->pp_tok[p ^ 1], c->pp_par, c->pp_cum[p ^ 1], c->stream, &h,
-                           c->done_dev, c->done_dev + c->cfg.max_batch, &tl, c->last_tok));
+    if (tiles > 0)
+      HIP_TRY(c, launch_topk_cands(c->part_ms, c->part_cv, c->part_ci, tiles, c->pp_cum[p], c->last_tok, c->cfg.eos_id,
+                                   c->batch, c->cfg.beam, c->V, c->cfg.beam, c->cand_lp, c->cand_idx, c->pp_tok[p ^ 1],
+                                   c->pp_par, c->pp_cum[p ^ 1], c->stream, &h, c->done_dev,
+                                   c->done_dev + c->cfg.max_batch, &tl, c->last_tok));
+    else
+      HIP_TRY(c, launch_topk(logits, c->pp_cum[p], c->last_tok, c->cfg.eos_id, c->batch, c->cfg.beam, c->V, c->cfg.beam,
+                             c->cand_lp, c->cand_idx, c->pp_tok[p ^ 1], c->pp_par, c->pp_cum[p ^ 1], c->stream, &h,
+                             c->done_dev, c->done_dev + c->cfg.max_batch, &tl, c->last_tok));
     return SAN_OK;
   }
-  HIP_TRY(c, launch_topk(logits, c->pp_cum[p], c->last_tok, c->cfg.eos_id, c->batch, c->cfg.beam, c->V, c->cfg.beam,
-                         c->cand_lp, c->cand_idx, c->pp_tok[p ^ 1], c->pp_par, c->pp_cum[p ^ 1], c->stream, &h,
-                         c->done_dev, c->done_dev + c->cfg.max_batch));
+  if (tiles > 0)
+    HIP_TRY(c, launch_topk_cands(c->part_ms, c->part_cv, c->part_ci, tiles, c->pp_cum[p], c->last_tok, c->cfg.eos_id,
+                                 c->batch, c->cfg.beam, c->V, c->cfg.beam, c->cand_lp, c->cand_idx, c->pp_tok[p ^ 1],
+                                 c->pp_par, c->pp_cum[p ^ 1], c->stream, &h, c->done_dev,
+                                 c->done_dev + c->cfg.max_batch));
+  else
+    HIP_TRY(c, launch_topk(logits, c->pp_cum[p], c->last_tok, c->cfg.eos_id, c->batch, c->cfg.beam, c->V, c->cfg.beam,
+                           c->cand_lp, c->cand_idx, c->pp_tok[p ^ 1], c->pp_par, c->pp_cum[p ^ 1], c->stream, &h,
+                           c->done_dev, c->done_dev + c->cfg.max_batch));
   return san_beam_reorder(c, c->pp_par);
 }
 
@@ -1183,7 +1227,7 @@ int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io
   if (!c) return SAN_EINVAL;
   if (!tokens_dev || !cum_io_dev || !out_tokens_dev || !out_parents_dev || !logits_work_dev || n < 1)
     return fail(c, SAN_EINVAL, "san_decode_n: bad argument");
-  if (flags & ~(SAN_LOOP_GRAPH | SAN_LOOP_COMPACT)) return fail(c, SAN_EINVAL, "san_decode_n: unknown flag");
+  if (flags & ~(SAN_LOOP_GRAPH | SAN_LOOP_COMPACT | SAN_LOOP_LOGITS)) return fail(c, SAN_EINVAL, "san_decode_n: unknown flag");
   if (reinterpret_cast<uintptr_t>(logits_work_dev) % 16)
     return fail(c, SAN_EINVAL, "san_decode_n: the logits scratch must be 16-byte aligned");
   if (c->t < 0) return fail(c, SAN_ESTATE, "san_decode_n before san_encode");
@@ -1208,6 +1252,13 @@ int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io
     if ((rc = dalloc(c, (void**)&c->row_map, (size_t)c->rows_max * 4, false))) return rc;
     if ((rc = dalloc(c, (void**)&c->cum_final, (size_t)c->rows_max * 4, false))) return rc;
     if ((rc = dalloc(c, (void**)&c->drop_dev, (size_t)c->cfg.max_batch * 4, false))) return rc;
+    if (c->cfg.use_cache && beam <= kGemmCandMaxK && topk_cands_fit((c->V + 63) / 64, beam)) {
+      // sized for the narrowest column tile (64) the output layer may pick
+      const size_t slots = (size_t)c->rows_max * ((c->V + 63) / 64);
+      if ((rc = dalloc(c, (void**)&c->part_cv, slots * 2 * beam * 4, false))) return rc;
+      if ((rc = dalloc(c, (void**)&c->part_ci, slots * 2 * beam * 4, false))) return rc;
+      if ((rc = dalloc(c, (void**)&c->part_ms, slots * 2 * 4, false))) return rc;   // last: it switches the mode on
+    }
   }
   HIP_TRY(c, hipMemcpyAsync(c->pp_tok[0], tokens_dev, (size_t)rows0 * 4, hipMemcpyDeviceToDevice, c->stream));
   HIP_TRY(c, hipMemcpyAsync(c->pp_cum[0], cum_io_dev, (size_t)rows0 * 4, hipMemcpyDeviceToDevice, c->stream));
@@ -1217,6 +1268,7 @@ int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io
   // The beam step's tail is fused (see loop_step) unless finished sentences may leave the batch
   // during this call (their state is then regathered between steps) or nothing is cached.
   const bool fused = c->cfg.use_cache && !compact && c->cfg.beam <= 32;
+  const int mode = (fused ? 1 : 0) | ((c->cfg.use_cache && !(flags & SAN_LOOP_LOGITS)) ? 2 : 0);
   if (fused && c->cfg.self_kind != SAN_SELF_AAN) {
     // the first step's input; every later one is embedded by the step before it
     c->kind = SAN_K_MISC;
@@ -1281,18 +1333,18 @@ int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io
       // buffers or the batch change
       const bool stale = !c->graph2 || c->graph_key[0] != out_tokens_dev || c->graph_key[1] != out_parents_dev ||
                          c->graph_key[2] != logits_work_dev || c->graph_rows != rows ||
-                         c->graph_entry_rows != entry_rows || c->graph_fused != fused;
+                         c->graph_entry_rows != entry_rows || c->graph_fused != mode;
       if (stale && n - done >= 4) {
         if (c->graph2) { (void)hipGraphExecDestroy(c->graph2); c->graph2 = nullptr; }
         // two ordinary steps first, so that one-time set-up inside the launchers
         // (per-kernel attributes) has happened before anything is captured
         for (int i = 0; i < 2; ++i, ++done)
-          if ((rc = loop_step(c, done & 1, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows, fused))) return rc;
+          if ((rc = loop_step(c, done & 1, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows, mode))) return rc;
         hipGraph_t g = nullptr;
         const int t_before = c->t;
         HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
-        rc = loop_step(c, 0, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows, fused);
-        if (!rc) rc = loop_step(c, 1, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows, fused);
+        rc = loop_step(c, 0, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows, mode);
+        if (!rc) rc = loop_step(c, 1, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows, mode);
         const hipError_t e = hipStreamEndCapture(c->stream, &g);
         c->t = t_before;   // capturing queued nothing
         if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
@@ -1303,9 +1355,9 @@ int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io
         c->graph_key[0] = out_tokens_dev; c->graph_key[1] = out_parents_dev; c->graph_key[2] = logits_work_dev;
         c->graph_rows = rows;
         c->graph_entry_rows = entry_rows;
-        c->graph_fused = fused;
+        c->graph_fused = mode;
       }
-      const bool fresh = c->graph2 && c->graph_rows == rows && c->graph_entry_rows == entry_rows && c->graph_fused == fused &&
+      const bool fresh = c->graph2 && c->graph_rows == rows && c->graph_entry_rows == entry_rows && c->graph_fused == mode &&
                          c->graph_key[0] == out_tokens_dev && c->graph_key[1] == out_parents_dev &&
                          c->graph_key[2] == logits_work_dev;
       while (fresh && done + 2 <= n) {
@@ -1321,7 +1373,7 @@ int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io
     while (done < n) {
       if ((rc = check(action))) return rc;
       if (action != kGoOn) break;
-      if ((rc = loop_step(c, done & 1, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows, fused))) return rc;
+      if ((rc = loop_step(c, done & 1, out_tokens_dev, out_parents_dev, logits_work_dev, entry_rows, mode))) return rc;
       ++done;
     }
   }

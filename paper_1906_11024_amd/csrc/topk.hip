@@ -265,6 +265,82 @@ __global__ __launch_bounds__(kTopkThreads) void topk_row_kernel(const float* log
   }
 }
 
+// The same row result from the output layer's per-tile candidates (GEMM out_kind 3) instead of
+// the logits: ms[row][tile] = (max, sum of exp(x - max)) of the tile's columns, cv / ci
+// [row][tile][2 k] = unordered entries that include its k largest (empty slots: id kNone).
+// The row's k largest are among them; k rounds, each taking the best candidate that comes
+// after the previous pick in the order (higher value, then lower word id).  CPT =
+// candidate slots per thread, held in registers.
+constexpr int kCombThreads = 256;
+template <int CPT>
+__global__ __launch_bounds__(kCombThreads) void cand_combine_kernel(const float* ms, const float* cv, const int* ci,
+                                                                    int ntiles, const int* last_tok, int eos_id, int k,
+                                                                    float* cand_lp, int* cand_idx) {
+  constexpr int NW = kCombThreads / kWave;
+  __shared__ float red_m[NW], red_s[NW];
+  __shared__ float bw_v[2][NW];
+  __shared__ int bw_i[2][NW];
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+  const int nc = ntiles * 2 * k;
+  const float* rv = cv + (size_t)row * nc;
+  const int* ri = ci + (size_t)row * nc;
+  float v[CPT];
+  int id[CPT];
+#pragma unroll
+  for (int i = 0; i < CPT; ++i) {
+    const int q = tid + i * kCombThreads;
+    v[i] = q < nc ? rv[q] : -INFINITY;
+    id[i] = q < nc ? ri[q] : kNone;
+  }
+  float m = -INFINITY, s = 0.f;
+  for (int x = tid; x < ntiles; x += kCombThreads) {
+    const float2 t = reinterpret_cast<const float2*>(ms)[(size_t)row * ntiles + x];
+    lse_merge(m, s, t.x, t.y);
+  }
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {   // both partners compute the same pair
+    const float om = __shfl_xor(m, off, kWave), os = __shfl_xor(s, off, kWave);
+    lse_merge(m, s, om, os);
+  }
+  if (lane == 0) { red_m[wid] = m; red_s[wid] = s; }
+
+  float pv = INFINITY;
+  int pi = -1;
+  float my_v = -INFINITY;
+  int my_i = kNone;
+  for (int round = 0; round < k; ++round) {
+    Cand best = {-INFINITY, kNone};
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+      const bool after = (v[i] < pv) || (v[i] == pv && id[i] > pi);
+      if (id[i] != kNone && after && better(v[i], id[i], best.v, best.i)) { best.v = v[i]; best.i = id[i]; }
+    }
+    best = wave_best(best);
+    if (lane == 0) { bw_v[round & 1][wid] = best.v; bw_i[round & 1][wid] = best.i; }
+    __syncthreads();   // one barrier per round: the next round writes the other pair of slots
+    best = Cand{bw_v[round & 1][0], bw_i[round & 1][0]};
+#pragma unroll
+    for (int w = 1; w < NW; ++w)
+      if (better(bw_v[round & 1][w], bw_i[round & 1][w], best.v, best.i)) best = Cand{bw_v[round & 1][w], bw_i[round & 1][w]};
+    pv = best.v;
+    pi = best.i;
+    if (tid == round) { my_v = best.v; my_i = best.i; }
+  }
+  if (tid >= k) return;
+  m = red_m[0];       // visible: k >= 1 barriers since they were written
+  s = red_s[0];
+  for (int w = 1; w < NW; ++w) lse_merge(m, s, red_m[w], red_s[w]);
+  const float lse = m + logf(s);
+  if (eos_id >= 0 && last_tok[row] == eos_id) {   // a finished hypothesis can only be extended by EOS at cost 0
+    const int fid = tid == 0 ? eos_id : (tid - 1 < eos_id ? tid - 1 : tid);
+    cand_lp[(size_t)row * k + tid] = tid == 0 ? 0.f : -INFINITY;
+    cand_idx[(size_t)row * k + tid] = fid;
+    return;
+  }
+  cand_lp[(size_t)row * k + tid] = my_i == kNone ? -INFINITY : my_v - lse;
+  cand_idx[(size_t)row * k + tid] = my_i;
+}
+
 // Merge of one sentence's beam*k candidates by one wave; lanes 0..k-1 end up with the k best.
 // Writes the picks, the optional history and the finished flag; returns this lane's pick.
 __device__ __forceinline__ Cand merge_sentence(int b, int lane, const float* cand_lp, const int* cand_idx, const float* cum,
@@ -423,21 +499,11 @@ static void launch_tail_t(int batch, int beam, hipStream_t stream, const float* 
 #undef SAN_TAIL
 }
 
-hipError_t launch_topk(const float* logits, const float* cum, const int* last_tok, int eos_id, int batch, int beam,
-                       int vocab, int k, float* cand_lp, int* cand_idx, int* out_tok, int* out_parent,
-                       float* out_score, hipStream_t stream, const TopkHistory* hist, int* done, int* done_count,
-                       const BeamTail* tail, int* last_tok_out) {
-  const int rows = batch * beam;
-  if (tail && (k != beam || beam > kMaxK || (tail->emb && (!tail->anc || !last_tok_out || tail->d % 4)))) return hipErrorInvalidValue;
-  if (rows <= 0) return hipSuccess;
-  if (vocab <= kTopkVpt * kTopkThreads)
-    hipLaunchKernelGGL(topk_row_kernel<true>, dim3(rows), dim3(kTopkThreads), 0, stream, logits, last_tok, eos_id,
-                       vocab, k, cand_lp, cand_idx);
-  else
-    hipLaunchKernelGGL(topk_row_kernel<false>, dim3(rows), dim3(kTopkThreads), 0, stream, logits, last_tok, eos_id,
-                       vocab, k, cand_lp, cand_idx);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+// the per-sentence stage: plain merge, or the merge inside the beam tail
+static hipError_t launch_merge(const float* cum, int eos_id, int batch, int beam, int vocab, int k, float* cand_lp,
+                               int* cand_idx, int* out_tok, int* out_parent, float* out_score, hipStream_t stream,
+                               const TopkHistory* hist, int* done, int* done_count, const BeamTail* tail,
+                               int* last_tok_out) {
   TopkHistory h{};
   if (hist) h = *hist;
   if (tail) {
@@ -452,6 +518,54 @@ hipError_t launch_topk(const float* logits, const float* cum, const int* last_to
   hipLaunchKernelGGL(topk_merge_kernel, dim3(batch), dim3(64), 0, stream, cand_lp, cand_idx, cum, beam, vocab, k,
                      out_tok, out_parent, out_score, h, eos_id, done_count ? done : nullptr, done_count);
   return hipGetLastError();
+}
+
+static bool tail_ok(const BeamTail* tail, int beam, int k, const int* last_tok_out) {
+  return !tail || !(k != beam || beam > kMaxK || (tail->emb && (!tail->anc || !last_tok_out || tail->d % 4)));
+}
+
+hipError_t launch_topk(const float* logits, const float* cum, const int* last_tok, int eos_id, int batch, int beam,
+                       int vocab, int k, float* cand_lp, int* cand_idx, int* out_tok, int* out_parent,
+                       float* out_score, hipStream_t stream, const TopkHistory* hist, int* done, int* done_count,
+                       const BeamTail* tail, int* last_tok_out) {
+  const int rows = batch * beam;
+  if (!tail_ok(tail, beam, k, last_tok_out)) return hipErrorInvalidValue;
+  if (rows <= 0) return hipSuccess;
+  if (vocab <= kTopkVpt * kTopkThreads)
+    hipLaunchKernelGGL(topk_row_kernel<true>, dim3(rows), dim3(kTopkThreads), 0, stream, logits, last_tok, eos_id,
+                       vocab, k, cand_lp, cand_idx);
+  else
+    hipLaunchKernelGGL(topk_row_kernel<false>, dim3(rows), dim3(kTopkThreads), 0, stream, logits, last_tok, eos_id,
+                       vocab, k, cand_lp, cand_idx);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_merge(cum, eos_id, batch, beam, vocab, k, cand_lp, cand_idx, out_tok, out_parent, out_score, stream, hist,
+                      done, done_count, tail, last_tok_out);
+}
+
+bool topk_cands_fit(int ntiles, int k) { return k >= 1 && ntiles >= 1 && (long)ntiles * 2 * k <= 20L * kCombThreads; }
+
+hipError_t launch_topk_cands(const float* ms, const float* cv, const int* ci, int ntiles, const float* cum,
+                             const int* last_tok, int eos_id, int batch, int beam, int vocab, int k, float* cand_lp,
+                             int* cand_idx, int* out_tok, int* out_parent, float* out_score, hipStream_t stream,
+                             const TopkHistory* hist, int* done, int* done_count, const BeamTail* tail,
+                             int* last_tok_out) {
+  const int rows = batch * beam;
+  if (!tail_ok(tail, beam, k, last_tok_out) || !topk_cands_fit(ntiles, k) || k > kMaxK) return hipErrorInvalidValue;
+  if (rows <= 0) return hipSuccess;
+  const int nc = ntiles * 2 * k;
+#define SAN_COMB(CPT)                                                                                              \
+  hipLaunchKernelGGL(cand_combine_kernel<CPT>, dim3(rows), dim3(kCombThreads), 0, stream, ms, cv, ci, ntiles, last_tok, \
+                     eos_id, k, cand_lp, cand_idx)
+  if (nc <= 2 * kCombThreads) SAN_COMB(2);
+  else if (nc <= 4 * kCombThreads) SAN_COMB(4);
+  else if (nc <= 8 * kCombThreads) SAN_COMB(8);
+  else SAN_COMB(20);
+#undef SAN_COMB
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_merge(cum, eos_id, batch, beam, vocab, k, cand_lp, cand_idx, out_tok, out_parent, out_score, stream, hist,
+                      done, done_count, tail, last_tok_out);
 }
 
 }  // namespace san

@@ -42,9 +42,13 @@ class Lockstep:
     at most twice the largest logit error of its row (once directly, once through the
     log-sum-exp), i.e. 2 * logit_tol * max|o|, plus the fp32 rounding of the running score."""
 
-    def __init__(self, gpu, orc, src, lens, beam, subset=None, bos_id=wl.BOS_ID):
+    def __init__(self, gpu, orc, src, lens, beam, subset=None, bos_id=wl.BOS_ID, loop=None):
+        """loop: None = the three separate calls; "cands" / "logits" = every step is one
+        san_decode_n(1) call (without / with SAN_LOOP_LOGITS), which searches and reorders by
+        itself; the logits are then compared only in "logits" mode."""
         import torch
         self.torch = torch
+        self.loop = loop
         self.gpu, self.orc, self.beam = gpu, orc, beam
         batch = src.shape[0]
         self.subset = np.arange(batch) if subset is None else np.asarray(subset)
@@ -75,16 +79,25 @@ class Lockstep:
         assert (tie_tol is None) != (logit_tol is None)
         torch, gpu, orc, beam = self.torch, self.gpu, self.orc, self.beam
         rows, V = self.rows, self.V
-        gpu.decode_step(self.tokens, self.logits)
+        cum_np = self.cum.cpu().numpy().astype(np.float64)
+        if self.loop is None:
+            gpu.decode_step(self.tokens, self.logits)
+        else:
+            cum_io = self.cum.clone()
+            gpu.decode_n(1, self.tokens, cum_io, self.o_tok.reshape(1, -1), self.o_par.reshape(1, -1), self.logits,
+                         keep_logits=self.loop == "logits")
+            self.o_sc.copy_(cum_io.reshape(self.o_sc.shape))
         tok_in = self.tokens.cpu().numpy()
         lo = orc.decode_step(tok_in[rows])
-        lg = self.logits[torch.from_numpy(rows).to("cuda")].cpu().numpy()
-        assert np.isfinite(lg).all()
+        lg = None
+        if self.loop != "cands":
+            lg = self.logits[torch.from_numpy(rows).to("cuda")].cpu().numpy()
+            assert np.isfinite(lg).all()
+            self.log["logit_err"].append(float(rel_err_rows(lg, lo).max()))
         self.last_gpu_logits, self.last_orc_logits = lg, lo
-        self.log["logit_err"].append(float(rel_err_rows(lg, lo).max()))
-        gpu.topk(self.logits, self.cum, beam, self.o_tok, self.o_par, self.o_sc)
+        if self.loop is None:
+            gpu.topk(self.logits, self.cum, beam, self.o_tok, self.o_par, self.o_sc)
         tok_g, par_g, sc_g = (t.cpu().numpy() for t in (self.o_tok, self.o_par, self.o_sc))
-        cum_np = self.cum.cpu().numpy().astype(np.float64)
         tok_o, par_o, sc_o, margin = orc.topk(lo, cum_np[rows], beam, last_tokens=tok_in[rows])
         lp_o = so.log_softmax(lo)
         if orc.eos_id >= 0:
@@ -121,7 +134,8 @@ class Lockstep:
         self.log["margin"].append(float(np.min(margin)))
         # both sides follow the GPU's choice
         parent_g = self.o_par.reshape(-1)
-        gpu.beam_reorder(parent_g)
+        if self.loop is None:
+            gpu.beam_reorder(parent_g)
         par_local = (par_g[self.subset] - self.subset[:, None] * beam
                      + np.arange(len(self.subset))[:, None] * beam).reshape(-1)
         orc.beam_reorder(par_local)

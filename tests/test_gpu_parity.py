@@ -614,6 +614,126 @@ def test_decode_n_aan_then_single_steps(use_graph):
         gpu.close()
 
 
+# Inside san_decode_n the output layer does not store logits: each of its column tiles hands the
+# search the tile's maximum, sum of exponentials and largest entries (GEMM epilogue + a per-row
+# combine).  The cases below pick shapes that select every tile of that epilogue; each step is one
+# san_decode_n(1) call checked against the oracle's step with the tolerance rule of Lockstep.
+WIDE = dict(n_enc=1, n_dec=2, d=64, H=4, F=128, V=25604, dtype="f32", batch=32, beam=4, src_len=(3, 9), steps=6,
+            self_pi=[2], encdec_pi=[2], self_kind="dot", name="wide")
+_CAND_CASES = {
+    # 128 x 128 fp32 tiles; the last column tile has 4 live columns
+    "f32_128x128": dict(),
+    # beam 8: that tile has fewer live columns than candidates asked for
+    "f32_128x128_beam8": dict(batch=16, beam=8),
+    # 256 x 256 bf16 tiles in two row passes; 480 rows: a ragged second row tile
+    "bf16_256x256": dict(dtype="bf16", batch=120),
+    # 128 x 128 bf16 tiles, 132 rows
+    "bf16_128x128": dict(dtype="bf16", batch=33),
+    # 64 x 128 bf16 tiles with 256-byte chunks (k a multiple of 128)
+    "bf16_64x128": dict(dtype="bf16", batch=5, d=128),
+    # 64 x 64 bf16 tiles: 256-byte chunks, and 128-byte chunks (k = 64)
+    "bf16_64x64_wide": dict(dtype="bf16", batch=5, d=256, V=2004),
+    "bf16_64x64": dict(dtype="bf16", batch=5, V=2004),
+    # 64 x 64 fp32 tiles, 20 live columns in the last one, an average-attention decoder
+    "f32_64x64_aan": dict(batch=5, V=2004, self_kind="aan", self_pi=[1, 1]),
+}
+
+
+@pytest.mark.parametrize("case", sorted(_CAND_CASES))
+def test_decode_n_candidate_output_layer_matches_oracle(case):
+    cfg = dict(WIDE)
+    cfg.update(_CAND_CASES[case])
+    bf16 = cfg["dtype"] == "bf16"
+    beam, steps = cfg["beam"], cfg["steps"]
+    w = wl.make_weights(cfg, seed=11, sharp=4.0)
+    w["w_out"] = w["w_out"] * np.float32(8.0)
+    if bf16:
+        w["w_out"] = wl.round_to_bf16(w["w_out"])
+    src, lens = wl.make_source(cfg, 11)
+    gpu = hz.make_gpu(cfg, w)
+    orc = hz.make_oracle(cfg, w)
+    ls = hz.Lockstep(gpu, orc, src, lens, beam, loop="cands")
+    for t in range(steps):
+        ls.step(logit_tol=BF16_TOL if bf16 else F32_TOL)
+    print(f"{case}: same picks as the oracle in {np.mean(ls.log['same_frac']):.4f} of (sentence, step) pairs, "
+          f"min margin {min(ls.log['margin']):.2e}, closest flipped gap {min(ls.log['flip_gap']):.2e}")
+    if not bf16:
+        assert np.mean(ls.log["same_frac"]) >= 0.98
+    # the same search with the logits stored and read back (SAN_LOOP_LOGITS), all steps in one call:
+    # both routes see the same logits, so they pick the same words from the same parents
+    B = cfg["batch"] * beam
+    gpu.rewind()
+    tokens = torch.full((B,), wl.BOS_ID, dtype=torch.int32, device="cuda")
+    cum = torch.from_numpy(_cum0(B, beam)).cuda()
+    out_tok = torch.zeros((steps, B), dtype=torch.int32, device="cuda")
+    out_par = torch.zeros((steps, B), dtype=torch.int32, device="cuda")
+    gpu.decode_n(steps, tokens, cum, out_tok, out_par, ls.logits, keep_logits=True)
+    torch.cuda.synchronize()
+    for t in range(steps):
+        assert np.array_equal(out_tok[t].cpu().numpy(), ls.log["tokens"][t].reshape(-1)), (case, t)
+        assert np.array_equal(out_par[t].cpu().numpy(), ls.log["parents"][t].reshape(-1)), (case, t)
+    np.testing.assert_allclose(cum.cpu().numpy(), ls.log["scores"][-1].reshape(-1), rtol=0, atol=1e-4)
+    gpu.close()
+
+
+@pytest.mark.parametrize("shape", ["64x64", "64x64_4_live", "128x128"])
+def test_decode_n_all_equal_logits_take_the_lowest_ids(shape):
+    """A zero output embedding makes every logit 0: every candidate of a sentence ties and the
+    order (higher score, then lower beam * vocab + word) alone decides, in every column tile's
+    exhaustive path (more entries at the threshold than slots) and in the combine."""
+    over = {"64x64": dict(batch=5, V=2004), "64x64_4_live": dict(batch=5, V=1988), "128x128": dict()}[shape]
+    cfg = dict(WIDE)
+    cfg.update(over)
+    beam, B, steps = cfg["beam"], cfg["batch"] * cfg["beam"], 4
+    w = wl.make_weights(cfg, seed=3)
+    w["w_out"] = np.zeros_like(w["w_out"])
+    src, lens = wl.make_source(cfg, 3)
+    ref = hz.make_oracle(cfg, w).search(src, lens, steps, beam)
+    gpu = hz.make_gpu(cfg, w)
+    gpu.encode(torch.from_numpy(src).cuda(), torch.from_numpy(lens).cuda())
+    tokens = torch.full((B,), wl.BOS_ID, dtype=torch.int32, device="cuda")
+    cum = torch.from_numpy(_cum0(B, beam)).cuda()
+    out_tok = torch.zeros((steps, B), dtype=torch.int32, device="cuda")
+    out_par = torch.zeros((steps, B), dtype=torch.int32, device="cuda")
+    logits = torch.empty((B, cfg["V"]), dtype=torch.float32, device="cuda")
+    gpu.decode_n(steps, tokens, cum, out_tok, out_par, logits)
+    torch.cuda.synchronize()
+    for t in range(steps):
+        assert np.array_equal(out_tok[t].cpu().numpy(), ref["tokens"][t]), (shape, t)
+        assert np.array_equal(out_par[t].cpu().numpy(), ref["parents"][t]), (shape, t)
+    assert np.array_equal(ref["tokens"][0].reshape(-1, beam), np.tile(np.arange(beam), (cfg["batch"], 1)))
+    np.testing.assert_allclose(cum.cpu().numpy(), ref["scores"][steps - 1], rtol=0, atol=1e-4)
+    gpu.close()
+
+
+def test_decode_n_with_the_logits_flag_stores_the_last_steps_logits():
+    cfg = mid_cfg(steps=12)
+    beam, B, V, N = cfg["beam"], cfg["batch"] * cfg["beam"], cfg["V"], 9
+    seed, w, src, lens, ref = hz.pick_seed_with_margin(cfg, cfg["self_pi"], cfg["encdec_pi"], "A", N, beam, 1e-3,
+                                                       sharp=4.0, out_scale=8.0, min_gap=1e-3, tries=40)
+    gpu = hz.make_gpu(cfg, w)
+    gpu.encode(torch.from_numpy(src).cuda(), torch.from_numpy(lens).cuda())
+    out_tok = torch.zeros((N, B), dtype=torch.int32, device="cuda")
+    out_par = torch.zeros((N, B), dtype=torch.int32, device="cuda")
+    logits = torch.full((B, V), float("nan"), dtype=torch.float32, device="cuda")
+    tokens = torch.full((B,), wl.BOS_ID, dtype=torch.int32, device="cuda")
+    cum = torch.from_numpy(_cum0(B, beam)).cuda()
+    gpu.decode_n(N, tokens, cum, out_tok, out_par, logits)            # default: the scratch is left alone
+    torch.cuda.synchronize()
+    assert torch.isnan(logits).all()
+    got_tok = out_tok.cpu().numpy()
+    gpu.rewind()
+    cum = torch.from_numpy(_cum0(B, beam)).cuda()
+    gpu.decode_n(N, tokens, cum, out_tok, out_par, logits, keep_logits=True)
+    torch.cuda.synchronize()
+    for t in range(N):
+        assert np.array_equal(got_tok[t], ref["tokens"][t]), (seed, t)
+        assert np.array_equal(out_tok[t].cpu().numpy(), ref["tokens"][t]), (seed, t)
+        assert np.array_equal(out_par[t].cpu().numpy(), ref["parents"][t]), (seed, t)
+    assert hz.rel_err_rows(logits.cpu().numpy(), ref["logits"][N - 1]).max() <= F32_TOL
+    gpu.close()
+
+
 def _eos_case(batch, beam, T, seeds, accept):
     """Tiny vocabulary (EOS gets picked often), oracle search with the end-symbol rule."""
     V = 8
