@@ -56,6 +56,9 @@ def parse():
                     help="decode steps the CPU oracle is timed on (the middle of a decode, like a short GPU window)")
     ap.add_argument("--beam-sweep", default="", help="comma-separated beam sizes: also time SAN vs unshared "
                     "cached decoding at these beams (the paper's Fig. 5 axis), e.g. 4,8,12,16,20")
+    ap.add_argument("--loop-only", default="", choices=["", "eager", "graph", "logits"],
+                    help="time only whole decodes driven by san_decode_n (eager, replayed HIP graph, or graph with "
+                         "SAN_LOOP_LOGITS) and print a short JSON line: the command kernel traces of the loop use")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a kernel of known "
                          "traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -131,6 +134,7 @@ class Runner:
 def loop_leg(torch, make_gpu, cfg, src, lens, use_graph, keep_logits, reps=5):
     """ms per whole decode driven by san_decode_n: one host call per decode on a stream of its own
     (the NULL stream cannot be captured); median of `reps` after one untimed decode."""
+    import numpy as np
     T, B = cfg["steps"], cfg["batch"] * cfg["beam"]
     st = torch.cuda.Stream()
     with torch.cuda.stream(st):
@@ -372,6 +376,14 @@ def main():
     def make(self_pi, ctx_pi, share=sb.SAN_SHARE_A, use_cache=1):
         sc = sb.make_config(cfg, encdec_share=share, use_cache=use_cache)
         return sb.San(sc, blob, self_pi, ctx_pi)
+
+    if args.loop_only:
+        w = loop_leg(torch, lambda: make(cfg["self_pi"], cfg["encdec_pi"]), cfg, src, lens,
+                     args.loop_only != "eager", args.loop_only == "logits", reps=max(1, args.reps))
+        print(json.dumps({"metric": "decoded tokens/sec (batch x beam rows per step), san_decode_n", "value": B * T / w,
+                          "unit": "tokens/s", "ms_per_step": w / T * 1e3, "steps": T, "mode": args.loop_only,
+                          "config": {"workload": args.config}, "lib_source_hash": lib_state["built_from"]}))
+        return
 
     # ------------------------------------------------ headline: SAN policy, cached
     p0, K, window_text = window_of(T, args.steps)

@@ -350,22 +350,27 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
         total += dpp_mov_i<kDppRowMirror>(total);
         const int m = m0 + pass * PR + r;
         const bool row_live = m < p.M;
-        const size_t slot = ((size_t)min(m, p.M - 1) * ntiles + tile_x) * slots;
+        // 32-bit slot offsets from the uniform base pointers (the launcher checks the size): one
+        // add per store instead of 64-bit pointer arithmetic in every lane
+        const unsigned slot = ((unsigned)min(m, p.M - 1) * (unsigned)ntiles + (unsigned)tile_x) * (unsigned)slots;
+        char* const cvb = reinterpret_cast<char*>(p.cand_v);
+        char* const cib = reinterpret_cast<char*>(p.cand_i);
         if (total <= slots) {
-          int pos = incl - cnt;
+          if (row_live) {
+            unsigned off = (slot + (unsigned)(incl - cnt)) * 4u;
+            const int colb = n0 + 4 * l16;
 #pragma unroll
-          for (int q = 0; q < VPL; ++q) {
-            if (val[q] >= thr) {
-              if (row_live) {
-                p.cand_v[slot + pos] = val[q];
-                p.cand_i[slot + pos] = n0 + (q >> 2) * 64 + 4 * l16 + (q & 3);
+            for (int q = 0; q < VPL; ++q) {
+              if (val[q] >= thr) {
+                *reinterpret_cast<float*>(cvb + off) = val[q];
+                *reinterpret_cast<int*>(cib + off) = colb + (q >> 2) * 64 + (q & 3);
+                off += 4u;
               }
-              ++pos;
             }
-          }
-          if (row_live && l16 >= total && l16 < slots) {
-            p.cand_v[slot + l16] = -INFINITY;
-            p.cand_i[slot + l16] = kNoCol;
+            if (l16 >= total && l16 < slots) {
+              *reinterpret_cast<float*>(cvb + (slot + l16) * 4u) = -INFINITY;
+              *reinterpret_cast<int*>(cib + (slot + l16) * 4u) = kNoCol;
+            }
           }
         } else {
           // too many entries at the threshold (masses of equal values, or fewer than kc live columns):
@@ -393,8 +398,8 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
               if ((q >> 2) * 64 + 4 * l16 + (q & 3) == bc) val[q] = -INFINITY;
           }
           if (row_live && l16 < slots) {
-            p.cand_v[slot + l16] = out_v;
-            p.cand_i[slot + l16] = out_v == -INFINITY ? kNoCol : n0 + out_c;
+            *reinterpret_cast<float*>(cvb + (slot + l16) * 4u) = out_v;
+            *reinterpret_cast<int*>(cib + (slot + l16) * 4u) = out_v == -INFINITY ? kNoCol : n0 + out_c;
           }
         }
         if (row_live && l16 == 0)
@@ -547,7 +552,7 @@ int gemm_cand_tile_n(int M, int N, int K, int dtype) {
 static hipError_t launch_gemm_cand(int dtype, const GemmParams& p, hipStream_t stream) {
   const int bn = gemm_cand_tile_n(p.M, p.N, p.K, dtype);
   if (p.cand_k < 1 || p.cand_k > kGemmCandMaxK || !p.cand_ms || !p.cand_v || !p.cand_i || p.ksplit != 1 ||
-      p.cand_tiles != (p.N + bn - 1) / bn)
+      p.cand_tiles != (p.N + bn - 1) / bn || (size_t)p.M * p.cand_tiles * 2 * p.cand_k * 4 >= ((size_t)1 << 31))
     return hipErrorInvalidValue;
   const int tile = cand_pick_tile(p.M, p.N, p.K, dtype);
   if (dtype == 1) {
