@@ -77,7 +77,9 @@ typedef struct {
                           either self_kind                                            */
   int32_t pad_id, bos_id, eos_id; /* word ids in [0, vocab); eos_id < 0 switches EOS handling
                                      off in san_topk                                          */
-  int32_t debug;       /* 1: keep per-layer S / A / hidden copies for san_debug_get   */
+  int32_t debug;       /* sum of: 1 keep per-layer S / A / hidden copies for san_debug_get;
+                          2 run only the general-purpose attention kernel (no matrix-core
+                          kernel for the encoder memory): a cross-check, slower            */
   float ln_eps;        /* LayerNorm epsilon                                           */
 } san_config;
 

@@ -10,7 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsan.so")
-SOURCES = ["san.hip", "gemm.hip", "attention.hip", "attention_split.hip", "rowwise.hip", "topk.hip", "policy.hip"]
+SOURCES = ["san.hip", "gemm.hip", "attention.hip", "attention_split.hip", "attention_mfma.hip", "rowwise.hip", "topk.hip", "policy.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

@@ -423,6 +423,7 @@ template <typename T, int LPP> static hipError_t launch_lpp(const AttnParams& p0
 
 hipError_t launch_attention(int dtype, const AttnParams& p, hipStream_t stream) {
   if (p.rows <= 0 || p.lmax <= 0) return hipSuccess;
+  if (attention_ctx_mfma_fits(dtype, p)) return launch_attention_ctx_mfma(p, stream);
   // Long streams in a launch that has fewer of them than the chip has SIMDs are split over
   // several waves each (attention_split.hip); measured on the 12-layer, 256-step workload
   // (1024 streams of up to 256 cached positions, 256 sentence memories of 128 positions):

@@ -62,6 +62,7 @@ struct AttnParams {
   const void* q; int ldq;           // T [rows][ldq]
   const void* K; long long ldk;     // T, slot stride in elements (unused when apply)
   const void* V; long long ldv;
+  const void* kv_packed; int kv_blocks;   // grouped, optional: the memory once more in fragment order (launch_pack_memory)
   float* S_buf; int ldS;            // fp32 [rows][H][ldS]
   void* out; int ldo;               // T [rows][ldo]
   const int* anc; int ld_anc;       // self mode
@@ -78,6 +79,16 @@ struct AttnParams {
   float scale;
 };
 hipError_t launch_attention(int dtype, const AttnParams& p, hipStream_t stream);
+// Block-head attention over a sentence's memory on the bf16 matrix cores (one wave per sentence
+// and head, every query of the sentence at once).  Needs bf16, dh == 64, grouped non-causal mode,
+// !apply, rpg <= 32 and kv_packed; launch_attention takes this route whenever it fits.
+bool attention_ctx_mfma_fits(int dtype, const AttnParams& p);
+hipError_t launch_attention_ctx_mfma(const AttnParams& p, hipStream_t stream);
+// The memory keys / values of `groups` sentences (row (g * n_pos + pos), 64-wide heads, bf16) in the order
+// that kernel reads its fragments: kv_blocks chunks of 8 KB per (sentence, head), one per 32 positions
+// (zeros past n_pos); out holds groups * H * kv_blocks chunks.
+hipError_t launch_pack_memory(const void* k, long long ldk, const void* v, long long ldv, int groups, int n_pos, int H,
+                              void* out, int kv_blocks, hipStream_t stream);
 // the same attention with each stream split over `waves` (1, 2, 4 or 8) waves of a workgroup; one_query:
 // grouped mode, one query per workgroup instead of four.  launch_attention picks between the two.
 hipError_t launch_attention_split(int dtype, const AttnParams& p, int waves, bool one_query, hipStream_t stream);

@@ -79,6 +79,7 @@ struct DecLayer {
   void *wkv_c = nullptr, *bkv_c = nullptr;    // head: [2d][d] (k;v); follower in mode S: [d][d] (v)
   void *wo_c = nullptr, *bo_c = nullptr, *ln2g = nullptr, *ln2b = nullptr;
   void* mem = nullptr;                        // head: [batch*max_src][2d]; follower (mode S): [..][d]
+  void* mem_packed = nullptr;                 // head, bf16 with 64-wide heads: K and V again, in MFMA fragment order
   float* S_ctx = nullptr;                     // head only
   void* A_ctx = nullptr;                      // head only: T [rows*][d]
   // Eq. 5 blocks, cached decoding: the followers' output projections of the shared A are
@@ -99,6 +100,7 @@ struct san_ctx {
   hipStream_t stream = nullptr;
   int dt = 0, esz = 4;
   int d = 0, H = 0, dh = 0, F = 0, V = 0, rows_max = 0, rows_src_max = 0;
+  int src_pad = 0;             // max_src_len rounded up to 32 (DecLayer::mem_packed holds src_pad / 32 blocks per head)
   std::vector<EncLayer> enc;
   std::vector<DecLayer> dec;
   void *src_emb = nullptr, *tgt_emb = nullptr, *w_out = nullptr;
@@ -271,7 +273,8 @@ const char* check_config(const san_config& c) {
   if (c.self_kind != SAN_SELF_DOT && c.self_kind != SAN_SELF_AAN) return "bad self_kind";
   if (c.encdec_share != SAN_SHARE_A && c.encdec_share != SAN_SHARE_S) return "bad encdec_share";
   if (c.use_cache != 0 && c.use_cache != 1) return "use_cache must be 0 or 1";
-  if (!c.use_cache && c.debug) return "debug copies need use_cache = 1";
+  if (c.debug < 0 || c.debug > 3) return "debug must be a sum of 1 (per-layer copies) and 2 (general-purpose kernels only)";
+  if (!c.use_cache && (c.debug & 1)) return "debug copies need use_cache = 1";
   if (!(c.ln_eps > 0.f)) return "ln_eps must be > 0";
   if (c.pad_id < 0 || c.pad_id >= c.vocab || c.bos_id < 0 || c.bos_id >= c.vocab)
     return "pad_id and bos_id must be word ids in [0, vocab)";
@@ -386,6 +389,7 @@ static int build_ctx(san_ctx* c, const Blob& bl, const void* blob, const std::ve
   c->d = cfg->d_model; c->H = cfg->n_heads; c->dh = c->d / c->H; c->F = cfg->d_ff; c->V = cfg->vocab;
   c->rows_max = cfg->max_batch * cfg->beam;
   c->rows_src_max = cfg->max_batch * cfg->max_src_len;
+  c->src_pad = (cfg->max_src_len + 31) / 32 * 32;
   const size_t d = c->d, F = c->F, V = c->V;
   const bool aan = cfg->self_kind == SAN_SELF_AAN, shareS = cfg->encdec_share == SAN_SHARE_S;
   const bool nocache = !cfg->use_cache;
@@ -492,6 +496,8 @@ static int build_ctx(san_ctx* c, const Blob& bl, const void* blob, const std::ve
         TRY(upload(c, L.bkv_c, 0, blob, o.ctx.bk, d));
         TRY(upload(c, L.bkv_c, d, blob, o.ctx.bv, d));
         TRY(dalloc(c, &L.mem, (size_t)c->rows_src_max * 2 * d * esz, false));
+        if (c->dt == 1 && c->dh == 64 && !(cfg->debug & 2))   // for the matrix-core enc-dec attention (attention_mfma.hip)
+          TRY(dalloc(c, &L.mem_packed, (size_t)cfg->max_batch * c->H * (c->src_pad / 32) * 8192, false));
         TRY(dalloc(c, (void**)&L.S_ctx, drows * c->H * cfg->max_src_len * 4, false));
         TRY(dalloc(c, &L.A_ctx, drows * d * esz, false));
       } else if (shareS) {
@@ -521,13 +527,13 @@ static int build_ctx(san_ctx* c, const Blob& bl, const void* blob, const std::ve
       TRY(wtensor(c, &L.b2, blob, o.ffn.b2, d));
       TRY(wtensor(c, &L.ln3g, blob, o.ln3.g, d));
       TRY(wtensor(c, &L.ln3b, blob, o.ln3.b, d));
-      if (cfg->debug) {
+      if (cfg->debug & 1) {
         TRY(dalloc(c, (void**)&L.dbg_A_self, (size_t)c->rows_max * d * 4, false));
         TRY(dalloc(c, (void**)&L.dbg_A_ctx, (size_t)c->rows_max * d * 4, false));
         TRY(dalloc(c, (void**)&L.dbg_hidden, (size_t)c->rows_max * d * 4, false));
       }
     }
-    if (cfg->debug) TRY(dalloc(c, (void**)&c->dbg_enc, (size_t)c->rows_src_max * d * 4, false));
+    if (cfg->debug & 1) TRY(dalloc(c, (void**)&c->dbg_enc, (size_t)c->rows_src_max * d * 4, false));
     // workspaces, sized for the largest row count any call uses
     size_t mrows = drows > (size_t)c->rows_src_max ? drows : (size_t)c->rows_src_max;
     const size_t wide = F > 2 * d ? F : 2 * d;
@@ -683,6 +689,9 @@ int san_encode(san_ctx* c, const int32_t* src_ids_dev, const int32_t* src_len_de
     if (!L.mem) continue;
     const int N = L.wq_c ? 2 * d : d;
     if ((rc = gemm(c, c->x, d, L.wkv_c, L.bkv_c, Ms, N, d, 0, 0, L.mem, N))) return rc;
+    if (L.mem_packed)
+      LAUNCH(c, launch_pack_memory(L.mem, N, (char*)L.mem + (size_t)d * c->esz, N, batch, max_src, c->H, L.mem_packed,
+                                   c->src_pad / 32, c->stream));
   }
   HIP_TRY(c, hipMemsetAsync(c->t_dev, 0, 4, c->stream));
   HIP_TRY(c, hipMemsetAsync(c->done_dev, 0, ((size_t)c->cfg.max_batch + 1) * 4, c->stream));
@@ -713,7 +722,7 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits, bool 
   const int d = c->d, B = c->batch * c->cfg.beam, T = c->cfg.max_tgt_len;
   const float scale = 1.0f / std::sqrt((float)c->dh);
   const bool aan = c->cfg.self_kind == SAN_SELF_AAN, shareS = c->cfg.encdec_share == SAN_SHARE_S;
-  const bool dbg = c->cfg.debug != 0;
+  const bool dbg = (c->cfg.debug & 1) != 0;
   const int cache_rows = c->batch_enc * c->cfg.beam;   // the caches keep the encoded batch's row stride
   const long long slab = (long long)cache_rows * d;    // cache elements per position
   const int* group_map = c->batch != c->batch_enc ? c->group_map : nullptr;
@@ -785,6 +794,7 @@ static int decode_cached(san_ctx* c, const int32_t* tokens, float* logits, bool 
         a.q = c->qkv; a.ldq = d;
         a.K = L.mem; a.ldk = 2 * d;
         a.V = (char*)L.mem + (size_t)d * c->esz; a.ldv = 2 * d;
+        a.kv_packed = L.mem_packed; a.kv_blocks = c->src_pad / 32;
         a.out = L.A_ctx;
         const bool has_followers = n + 1 < Ld && c->dec[n + 1].ctx_head == n;
         a.emit = (shareS && has_followers) || dbg;
@@ -1022,7 +1032,7 @@ int san_beam_reorder(san_ctx* c, const int32_t* parent_idx_dev) {
 
 int san_debug_get(san_ctx* c, int32_t what, int32_t layer, void* dst_dev, size_t cap) {
   if (!c) return SAN_EINVAL;
-  if (!c->cfg.debug) return fail(c, SAN_ESTATE, "san_debug_get needs cfg.debug = 1");
+  if (!(c->cfg.debug & 1)) return fail(c, SAN_ESTATE, "san_debug_get needs cfg.debug = 1");
   if (!dst_dev || layer < 0 || layer >= (int)c->dec.size()) return fail(c, SAN_EINVAL, "san_debug_get: bad argument");
   DecLayer& L = c->dec[layer];
   if (what == SAN_DBG_ENC_OUT || what == SAN_DBG_MEM) {   // written by san_encode
@@ -1397,7 +1407,7 @@ int san_decode_n(san_ctx* c, int32_t n, const int32_t* tokens_dev, float* cum_io
 
 int san_policy_accumulate(san_ctx* c) {
   if (!c) return SAN_EINVAL;
-  if (!c->cfg.debug || !c->cfg.use_cache) return fail(c, SAN_ESTATE, "san_policy_accumulate needs cfg.debug = 1 and use_cache = 1");
+  if (!(c->cfg.debug & 1) || !c->cfg.use_cache) return fail(c, SAN_ESTATE, "san_policy_accumulate needs cfg.debug = 1 and use_cache = 1");
   if (c->t < 1) return fail(c, SAN_ESTATE, "san_policy_accumulate before the first decode step");
   const int L = (int)c->dec.size(), B = c->batch * c->cfg.beam;
   if (L > kMaxPolicyLayers) return fail(c, SAN_EINVAL, "too many decoder layers for policy statistics");

@@ -257,6 +257,53 @@ def test_bf16_lockstep(base, kind):
     gpu.close()
 
 
+@pytest.mark.parametrize("beam,src_len,share,zero_len", [(4, (1, 37), "A", True), (1, (5, 64), "A", False),
+                                                         (8, (1, 100), "S", True), (20, (30, 33), "A", False),
+                                                         (32, (1, 140), "A", False)])
+def test_bf16_memory_attention_on_matrix_cores(beam, src_len, share, zero_len):
+    """bf16 models with 64-wide heads run the block head's attention over the encoder memory on
+    the matrix cores (memories of 1, 2, 3, 4 and more than 4 blocks of 32 positions take different
+    variants; 1 to 32 hypotheses per sentence).  Checked three ways: the logits against the oracle
+    (Lockstep), the weights and the context vectors of every layer against the oracle's within what
+    bf16 inputs allow, and -- where both get bit-identical inputs, the first block head -- against the
+    general-purpose kernel of a second context (cfg.debug bit 2): the same weights to fp32 rounding,
+    the same context vectors to one bf16 rounding step."""
+    cfg = mid_cfg(dtype="bf16", batch=4, beam=beam, src_len=src_len, steps=5, encdec_pi=[2, 2])
+    w = wl.make_weights(cfg, seed=19, sharp=3.0)
+    src, lens = ragged(cfg, 19)
+    if zero_len:
+        lens[1] = 0
+        src[1, :] = wl.PAD_ID
+    gpu = hz.make_gpu(cfg, w, share=share, debug=1)
+    ref = hz.make_gpu(cfg, w, share=share, debug=3)
+    orc = hz.make_oracle(cfg, w, share=share)
+    ls = hz.Lockstep(gpu, orc, src, lens, beam)
+    ref.encode(ls.src_d, ls.len_d)
+    ref_logits = torch.empty_like(ls.logits)
+    for t in range(cfg["steps"]):
+        tokens = ls.tokens.clone()
+        ls.step(logit_tol=BF16_TOL)
+        ref.decode_step(tokens, ref_logits)
+        for n in range(cfg["n_dec"]):
+            S = gpu.debug_get(sb.SAN_DBG_S_CTX, n).cpu().numpy()
+            A = gpu.debug_get(sb.SAN_DBG_A_CTX, n).cpu().numpy()
+            So, Ao = orc.dump["S_ctx"][n], orc.dump["A_ctx"][n]
+            live = np.repeat(lens > 0, beam)
+            assert np.abs(S[live].sum(-1) - 1).max() < 1e-5 and np.all(S[~live] == 0)
+            assert np.abs(S - So[..., :S.shape[-1]]).max() < 3e-2, (t, n)
+            assert np.abs(A - Ao).max() <= 3e-2 * max(1.0, np.abs(Ao).max()), (t, n)
+            if n == 0:
+                Sr = ref.debug_get(sb.SAN_DBG_S_CTX, n).cpu().numpy()
+                Ar = ref.debug_get(sb.SAN_DBG_A_CTX, n).cpu().numpy()
+                assert np.abs(S - Sr).max() < 2e-6, (t, np.abs(S - Sr).max())
+                assert np.all(np.abs(A - Ar) <= 2.0 ** -7 * np.abs(Ar) + 1e-6), (t, np.abs(A - Ar).max())
+        assert hz.rel_err_rows(ref_logits.cpu().numpy(), ls.logits.cpu().numpy()).max() < 2e-2
+        ref.beam_reorder(ls.o_par.reshape(-1))
+    assert max(ls.log["logit_err"]) <= BF16_TOL
+    gpu.close()
+    ref.close()
+
+
 @pytest.mark.parametrize("beam", [4, 6, 12, 20])   # each beam range has its own state-reorder kernel
 def test_aan_fp32_lockstep(beam):
     cfg = mid_cfg(self_kind="aan", self_pi=[1, 1, 1, 1], steps=30 if beam == 4 else 12, beam=beam)
@@ -838,12 +885,15 @@ def test_random_shapes_and_policies(case):
 
 
 # ------------------------------------------------------ dropping sentences from a running batch
-@pytest.mark.parametrize("kind,share", [("dot", "A"), ("dot", "S"), ("aan", "A")])
-def test_compact_keeps_the_remaining_sentences_exact(kind, share):
+@pytest.mark.parametrize("kind,share,dtype", [("dot", "A", "f32"), ("dot", "S", "f32"), ("aan", "A", "f32"),
+                                             ("dot", "A", "bf16"), ("dot", "S", "bf16")])
+def test_compact_keeps_the_remaining_sentences_exact(kind, share, dtype):
     """san_compact drops sentences mid-decode; the ones that stay go on exactly as the
     oracle decodes them (sentences never interact), through two compactions; san_rewind
-    brings the whole batch back."""
-    cfg = mid_cfg(steps=20, self_kind=kind)
+    brings the whole batch back.  (bf16: the matrix-core kernel reads the packed memory of
+    the sentences that stayed.)"""
+    cfg = mid_cfg(steps=20, self_kind=kind, dtype=dtype)
+    tol = F32_TOL if dtype == "f32" else BF16_TOL
     if kind == "aan":
         cfg["self_pi"] = [1] * cfg["n_dec"]
     w = wl.make_weights(cfg, seed=31, sharp=4.0)
@@ -859,11 +909,12 @@ def test_compact_keeps_the_remaining_sentences_exact(kind, share):
         if t == 11:
             hz.lockstep_compact(ls, [1, 2])
             assert gpu.active().tolist() == [1, 3] and gpu.rows == 2 * cfg["beam"]
-        lg, _ = ls.step(logit_tol=F32_TOL)
+        lg, _ = ls.step(logit_tol=tol)
         if t == 0:
             first_logits = lg.copy()
-    assert max(ls.log["logit_err"]) <= F32_TOL
-    assert sum(ls.log["exact"]) >= 0.8 * 20
+    assert max(ls.log["logit_err"]) <= tol
+    if dtype == "f32":
+        assert sum(ls.log["exact"]) >= 0.8 * 20
     gpu.rewind()
     assert gpu.active().tolist() == [0, 1, 2, 3, 4] and gpu.batch == 5
     B = 5 * cfg["beam"]
