@@ -51,7 +51,7 @@ __device__ __forceinline__ float lane_value(float v, int src_lane) {   // src_la
 // first score is computed (one memory round trip per wave).  NB == 0: any length; one block in
 // registers, refilled as soon as it has been used.
 template <int NB>
-__global__ __launch_bounds__(256, 2) void attention_ctx_mfma_kernel(AttnParams p) {
+__global__ __launch_bounds__(256, 2) void attention_kernel_ctx_mfma(AttnParams p) {
   const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
   const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (wave >= p.groups * p.H) return;                 // whole waves; no barrier in this kernel
@@ -247,16 +247,16 @@ hipError_t launch_attention_ctx_mfma(const AttnParams& p, hipStream_t stream) {
   if (waves <= 0) return hipSuccess;
   const dim3 grid((unsigned)((waves + 3) / 4)), blk(256);
   const int nb = (p.lmax + kMfmaBlock - 1) / kMfmaBlock;
-  if (nb <= 1) hipLaunchKernelGGL(attention_ctx_mfma_kernel<1>, grid, blk, 0, stream, p);
-  else if (nb == 2) hipLaunchKernelGGL(attention_ctx_mfma_kernel<2>, grid, blk, 0, stream, p);
-  else if (nb == 3) hipLaunchKernelGGL(attention_ctx_mfma_kernel<3>, grid, blk, 0, stream, p);
-  else if (nb == 4) hipLaunchKernelGGL(attention_ctx_mfma_kernel<4>, grid, blk, 0, stream, p);
-  else hipLaunchKernelGGL(attention_ctx_mfma_kernel<0>, grid, blk, 0, stream, p);
+  if (nb <= 1) hipLaunchKernelGGL(attention_kernel_ctx_mfma<1>, grid, blk, 0, stream, p);
+  else if (nb == 2) hipLaunchKernelGGL(attention_kernel_ctx_mfma<2>, grid, blk, 0, stream, p);
+  else if (nb == 3) hipLaunchKernelGGL(attention_kernel_ctx_mfma<3>, grid, blk, 0, stream, p);
+  else if (nb == 4) hipLaunchKernelGGL(attention_kernel_ctx_mfma<4>, grid, blk, 0, stream, p);
+  else hipLaunchKernelGGL(attention_kernel_ctx_mfma<0>, grid, blk, 0, stream, p);
   return hipGetLastError();
 }
 
 // One block of 32 positions of one (sentence, head): k / v rows (g * n_pos + pos) * ld + h * 64 -> the packed
-// chunk described in attention_ctx_mfma_kernel; positions >= n_pos become zeros.
+// chunk described in attention_kernel_ctx_mfma; positions >= n_pos become zeros.
 __global__ __launch_bounds__(256) void pack_memory_kernel(const bf16_t* k, long long ldk, const bf16_t* v, long long ldv,
                                                           int n_pos, int H, unsigned char* out, int kv_blocks) {
   __shared__ unsigned short tile[kMfmaDh][kMfmaBlock + 2];   // values, [channel][position]

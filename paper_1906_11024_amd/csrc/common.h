@@ -16,12 +16,17 @@ struct bf16_t {
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x.v) << 16); }
 
-// round-to-nearest-even fp32 -> bf16 (NaN kept quiet)
+// round-to-nearest-even fp32 -> bf16 (NaN kept quiet): the hardware conversion of gfx950
+// (v_cvt_pk_bf16_f32, two values per instruction where the compiler can pair them)
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+  return __builtin_bit_cast(uint16_t, (__bf16)f);
+}
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2_bits(float lo, float hi) {   // lo in the low half
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  bf16x2_t v;
+  v[0] = (__bf16)lo;
+  v[1] = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, v);
 }
 
 template <typename T> __device__ __forceinline__ T from_f32(float f);
@@ -63,7 +68,7 @@ __device__ __forceinline__ void store_frag(bf16_t* p, const float (&in)[8]) {
   uint32_t w[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    w[i] = (uint32_t)f32_to_bf16_bits(in[2 * i]) | ((uint32_t)f32_to_bf16_bits(in[2 * i + 1]) << 16);
+    w[i] = f32x2_to_bf16x2_bits(in[2 * i], in[2 * i + 1]);
   v.x = w[0]; v.y = w[1]; v.z = w[2]; v.w = w[3];
   *reinterpret_cast<uint4*>(p) = v;
 }
@@ -78,8 +83,8 @@ __device__ __forceinline__ float4 load4(const bf16_t* p) {
 __device__ __forceinline__ void store4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
 __device__ __forceinline__ void store4(bf16_t* p, float4 v) {
   uint2 o;
-  o.x = (uint32_t)f32_to_bf16_bits(v.x) | ((uint32_t)f32_to_bf16_bits(v.y) << 16);
-  o.y = (uint32_t)f32_to_bf16_bits(v.z) | ((uint32_t)f32_to_bf16_bits(v.w) << 16);
+  o.x = f32x2_to_bf16x2_bits(v.x, v.y);
+  o.y = f32x2_to_bf16x2_bits(v.z, v.w);
   *reinterpret_cast<uint2*>(p) = o;
 }
 
