@@ -230,13 +230,14 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnPara
 
   if (!p.apply) {
     // ---- pass 1: scores (Eq. 1, numerator)
+    const float scale2 = p.scale * 1.44269504088896341f;
     float qf[NQ][EPL];
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
       if (qrow[i] >= 0) {
         load_frag(Qp + (size_t)qrow[i] * p.ldq + col, qf[i]);
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) qf[i][e] *= p.scale;
+        for (int e = 0; e < EPL; ++e) qf[i][e] *= scale2;   // scores in log2 units: the softmax is one v_exp_f32 per score
       } else {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) qf[i][e] = 0.f;
@@ -287,7 +288,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnPara
       m = group_max<16>(m);
       float s = 0.f;
       for (int j = l16; j < n; j += 16) {
-        const float e = (row[j] == -INFINITY) ? 0.f : expf(row[j] - m);
+        const float e = (row[j] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(row[j] - m);
         row[j] = e;
         s += e;
       }
@@ -314,7 +315,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnPara
         m = wave_max(m);
         float s = 0.f;
         for (int j = lane; j < n; j += kWave) {
-          const float e = (row[j] == -INFINITY) ? 0.f : expf(row[j] - m);
+          const float e = (row[j] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(row[j] - m);
           row[j] = e;
           s += e;
         }

@@ -110,11 +110,21 @@ template <int N> __device__ __forceinline__ float group_sum(float v) {
   if (N >= 16) v += dpp_mov<kDppRowMirror>(v);
   return v;
 }
+// Maxima are written as v_max_f32 instructions: for fmaxf(v, dpp(v)) the compiler emits five (a
+// zeroed destination, the move, two canonicalising maxima, the maximum), for fmaxf of two swapped
+// registers three.  The s_nop cover the DPP read-after-write hazards (2 wait states after a VALU
+// write of the source, 5 after a VALU write of EXEC), which the compiler cannot see inside asm.
+__device__ __forceinline__ float max_raw(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
 template <int N> __device__ __forceinline__ float group_max(float v) {
-  if (N >= 2) v = fmaxf(v, dpp_mov<kDppQuadSwap1>(v));
-  if (N >= 4) v = fmaxf(v, dpp_mov<kDppQuadSwap2>(v));
-  if (N >= 8) v = fmaxf(v, dpp_mov<kDppRowHalfMirror>(v));
-  if (N >= 16) v = fmaxf(v, dpp_mov<kDppRowMirror>(v));
+  static_assert(N == 1 || N == 2 || N == 4 || N == 8 || N == 16, "group size");
+  if (N >= 2) asm("s_nop 4\n\tv_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf" : "+v"(v));
+  if (N >= 4) asm("s_nop 1\n\tv_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf" : "+v"(v));
+  if (N >= 8) asm("s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf" : "+v"(v));
+  if (N >= 16) asm("s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf" : "+v"(v));
   return v;
 }
 
@@ -135,12 +145,12 @@ __device__ __forceinline__ float sum_xor32(float v) {
 __device__ __forceinline__ float max_xor16(float v) {
   const unsigned x = __float_as_uint(v);
   const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  return max_raw(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 __device__ __forceinline__ float max_xor32(float v) {
   const unsigned x = __float_as_uint(v);
   const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  return max_raw(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
 // The value lane ^ 16 (lane ^ 32) holds.

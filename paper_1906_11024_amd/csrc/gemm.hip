@@ -49,25 +49,6 @@ template <> __device__ __forceinline__ void mma_frag<bf16_t>(f32x16& acc, const 
 // CB = bytes of k per row in one LDS stage (128 or 256); rows are padded by 16
 // bytes, which keeps the 16-byte fragment reads of 16 neighbouring lanes on
 // distinct banks for both sizes.
-// Maximum over each aligned group of 16 lanes, in every lane: four v_max_f32 with DPP operands.
-// Written out because the compiler spends five instructions per step on fmaxf(v, dpp(v)) (a
-// zeroed destination, the move, two canonicalising maxima, the maximum).  The waits cover
-// the DPP read-after-write hazards, which the compiler cannot see inside the block.
-__device__ __forceinline__ float group16_max(float v) {
-  float r;
-  asm("s_nop 4\n\t"
-      "v_max_f32_dpp %0, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
-      "s_nop 1\n\t"
-      "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
-      "s_nop 1\n\t"
-      "v_max_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
-      "s_nop 1\n\t"
-      "v_max_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf"
-      : "=v"(r)
-      : "v"(v));
-  return r;
-}
-
 // CAND: the tile is not stored.  Its rows go through LDS to groups of 16 lanes that
 // reduce each row of BN columns to (max, sum of exp(x - max)) and a few entries that
 // include its p.cand_k largest (see GemmParams::cand_*): the beam step needs nothing
@@ -323,11 +304,11 @@ __global__ __launch_bounds__(WM* WN* KW * 64) void gemm_kernel(GemmParams p) {
         float lm = val[0];
 #pragma unroll
         for (int q = 1; q < VPL; ++q) lm = fmaxf(lm, val[q]);
-        const float row_m = group16_max(lm);       // finite: a tile has at least one live column
+        const float row_m = group_max<16>(lm);       // finite: a tile has at least one live column
         // Threshold: the kc-th largest distinct lane maximum.  At least kc entries of the row are >= it,
         // so the row's kc largest all are, and usually hardly any other entry is.
         float thr = row_m;
-        for (int round = 1; round < kc; ++round) thr = group16_max(lm < thr ? lm : -INFINITY);
+        for (int round = 1; round < kc; ++round) thr = group_max<16>(lm < thr ? lm : -INFINITY);
         float es = 0.f;
         int cnt = 0;
         const float nm2 = -row_m * 1.44269504088896341f;
