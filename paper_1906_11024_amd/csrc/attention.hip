@@ -7,6 +7,8 @@
 // LDS (one row per query), the softmax max/sum are wave shuffles, and the
 // normalised weights are written out once per sharing block so that the other
 // layers of the block (apply mode) only stream their own V.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -230,32 +232,56 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attention_kernel(AttnPara
 
   if (!p.apply) {
     // ---- pass 1: scores (Eq. 1, numerator)
-    const float scale2 = p.scale * 1.44269504088896341f;
-    float qf[NQ][EPL];
+    const float scale2 = p.scale * 1.44269504088896341f;   // scores in log2 units: the softmax is one v_exp_f32 per score
+    constexpr bool kPacked = std::is_same<T, bf16_t>::value;
+    // fp32: the query times the scale, as floats.  bf16: the raw pairs -- both operands are bf16, their
+    // products exact in fp32, so the packed dot product (two products and an add per instruction)
+    // replaces unpacking and multiply-adds; the scale is applied to the sum.
+    float qf[kPacked ? 1 : NQ][EPL];
+    uint4 qraw[kPacked ? NQ : 1];
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
-      if (qrow[i] >= 0) {
-        load_frag(Qp + (size_t)qrow[i] * p.ldq + col, qf[i]);
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) qf[i][e] *= scale2;   // scores in log2 units: the softmax is one v_exp_f32 per score
+      if constexpr (kPacked) {
+        qraw[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (qrow[i] >= 0) qraw[i] = *reinterpret_cast<const uint4*>(Qp + (size_t)qrow[i] * p.ldq + col);
       } else {
+        if (qrow[i] >= 0) {
+          load_frag(Qp + (size_t)qrow[i] * p.ldq + col, qf[i]);
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) qf[i][e] = 0.f;
+          for (int e = 0; e < EPL; ++e) qf[i][e] *= scale2;
+        } else {
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) qf[i][e] = 0.f;
+        }
       }
     }
     auto scores = [&](int j0, const uint4 (&buf)[U]) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int j = j0 + u * PPL + g;
-        float kf[EPL];
-        widen(buf[u], kf);
+        if constexpr (kPacked) {
+          typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 #pragma unroll
-        for (int i = 0; i < NQ; ++i) {
-          float dot = 0.f;
+          for (int i = 0; i < NQ; ++i) {
+            float dot = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, qraw[i].x),
+                                                        __builtin_bit_cast(bf16x2_t, buf[u].x), 0.f, false);
+            dot = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, qraw[i].y), __builtin_bit_cast(bf16x2_t, buf[u].y), dot, false);
+            dot = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, qraw[i].z), __builtin_bit_cast(bf16x2_t, buf[u].z), dot, false);
+            dot = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, qraw[i].w), __builtin_bit_cast(bf16x2_t, buf[u].w), dot, false);
+            dot = lanes_sum<LPP>(dot) * scale2;
+            if (c == 0 && j < n) sc[i * p.lmax + j] = (j < nk[i]) ? dot : -INFINITY;
+          }
+        } else {
+          float kf[EPL];
+          widen(buf[u], kf);
 #pragma unroll
-          for (int e = 0; e < EPL; ++e) dot = fmaf(qf[i][e], kf[e], dot);
-          dot = lanes_sum<LPP>(dot);
-          if (c == 0 && j < n) sc[i * p.lmax + j] = (j < nk[i]) ? dot : -INFINITY;
+          for (int i = 0; i < NQ; ++i) {
+            float dot = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) dot = fmaf(qf[i][e], kf[e], dot);
+            dot = lanes_sum<LPP>(dot);
+            if (c == 0 && j < n) sc[i * p.lmax + j] = (j < nk[i]) ? dot : -INFINITY;
+          }
         }
       }
     };
