@@ -84,19 +84,26 @@ __global__ __launch_bounds__(256, 2) void attention_kernel_ctx_mfma(AttnParams p
   // 8 ks .. 8 ks + 7 after K Q^T.  Positions past the memory's end are zeros in the packed copy.
   constexpr int NS = NB > 0 ? NB : 1;
   u32x4 kf[NS][4], vf[NS][2][2];
+  // (lanes whose positions lie past the memory's end load nothing: those fragments are zeros)
   auto load_keys = [&](int b, auto slot) {
     const unsigned char* kp = mem + (size_t)b * kMfmaChunk + (half * 32 + l32) * 16;
+    const bool live = b * kMfmaBlock + l32 < n;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) kf[slot][s] = *reinterpret_cast<const u32x4*>(kp + s * 1024);
+    for (int s = 0; s < 4; ++s) {
+      kf[slot][s] = u32x4{0u, 0u, 0u, 0u};
+      if (live) kf[slot][s] = *reinterpret_cast<const u32x4*>(kp + s * 1024);
+    }
   };
   auto load_values = [&](int b, auto slot) {
     const unsigned char* vp = mem + (size_t)b * kMfmaChunk + 4096 + (half * 32 + l32) * 8;
+    const int p0 = b * kMfmaBlock + 4 * half;
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
-        const u32x2 a = *reinterpret_cast<const u32x2*>(vp + ((cb * 2 + ks) * 2 + 0) * 512);
-        const u32x2 c = *reinterpret_cast<const u32x2*>(vp + ((cb * 2 + ks) * 2 + 1) * 512);
+        u32x2 a = u32x2{0u, 0u}, c = u32x2{0u, 0u};
+        if (p0 + ks * 16 < n) a = *reinterpret_cast<const u32x2*>(vp + ((cb * 2 + ks) * 2 + 0) * 512);
+        if (p0 + ks * 16 + 8 < n) c = *reinterpret_cast<const u32x2*>(vp + ((cb * 2 + ks) * 2 + 1) * 512);
         vf[slot][cb][ks] = u32x4{a.x, a.y, c.x, c.y};
       }
   };
