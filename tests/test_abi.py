@@ -73,7 +73,7 @@ def _init(lib, sc, self_pi, ctx_pi, nbytes=None, enc_pi=()):
                                          ("d_ff", 100), ("vocab", 1001), ("beam", 0), ("beam", 33),
                                          ("dtype", 7), ("self_kind", 2), ("encdec_share", 5), ("max_tgt_len", 0),
                                          ("ln_eps", 0.0), ("n_dec_layers", 0), ("pad_id", -1), ("bos_id", 1000),
-                                         ("eos_id", 1000)])
+                                         ("eos_id", 1000), ("debug", 4), ("debug", -1)])
 def test_bad_config_is_einval(lib, field, value):
     sc = sb.make_config(wl.get_config("tiny"))
     setattr(sc, field, value)
