@@ -288,19 +288,22 @@ __global__ __launch_bounds__(kCombThreads) void cand_combine_kernel(const float*
   int id[CPT];
 #pragma unroll
   for (int i = 0; i < CPT; ++i) {
-    const int q = tid + i * kCombThreads;
-    v[i] = q < nc ? rv[q] : -INFINITY;
-    id[i] = q < nc ? ri[q] : kNone;
+    // unconditional requests (clamped index), so that all of them are in flight together
+    const int q = tid + i * kCombThreads, qc = min(q, nc - 1);
+    const float lv = rv[qc];
+    const int li = ri[qc];
+    v[i] = q < nc ? lv : -INFINITY;
+    id[i] = q < nc ? li : kNone;
   }
   float m = -INFINITY, s = 0.f;
   for (int x = tid; x < ntiles; x += kCombThreads) {
     const float2 t = reinterpret_cast<const float2*>(ms)[(size_t)row * ntiles + x];
     lse_merge(m, s, t.x, t.y);
   }
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {   // both partners compute the same pair
-    const float om = __shfl_xor(m, off, kWave), os = __shfl_xor(s, off, kWave);
-    lse_merge(m, s, om, os);
+  {
+    const float mw = wave_max(m);
+    s = wave_sum(m == -INFINITY ? 0.f : s * __expf(m - mw));
+    m = mw;
   }
   if (lane == 0) { red_m[wid] = m; red_s[wid] = s; }
 
