@@ -683,6 +683,9 @@ _CAND_CASES = {
     "bf16_64x64": dict(dtype="bf16", batch=5, V=2004),
     # 64 x 64 fp32 tiles, 20 live columns in the last one, an average-attention decoder
     "f32_64x64_aan": dict(batch=5, V=2004, self_kind="aan", self_pi=[1, 1]),
+    # bf16, 64-wide heads, enc-dec weights shared (Tab. 4 "shared V: no"): the matrix-core attention emits the
+    # block's weights for the follower inside the loop; beam 8
+    "bf16_share_s_beam8": dict(dtype="bf16", batch=6, beam=8, d=256, V=2004, src_len=(1, 70), share="S"),
 }
 
 
@@ -690,6 +693,7 @@ _CAND_CASES = {
 def test_decode_n_candidate_output_layer_matches_oracle(case):
     cfg = dict(WIDE)
     cfg.update(_CAND_CASES[case])
+    share = cfg.pop("share", "A")
     bf16 = cfg["dtype"] == "bf16"
     beam, steps = cfg["beam"], cfg["steps"]
     w = wl.make_weights(cfg, seed=11, sharp=4.0)
@@ -697,8 +701,8 @@ def test_decode_n_candidate_output_layer_matches_oracle(case):
     if bf16:
         w["w_out"] = wl.round_to_bf16(w["w_out"])
     src, lens = wl.make_source(cfg, 11)
-    gpu = hz.make_gpu(cfg, w)
-    orc = hz.make_oracle(cfg, w)
+    gpu = hz.make_gpu(cfg, w, share=share)
+    orc = hz.make_oracle(cfg, w, share=share)
     ls = hz.Lockstep(gpu, orc, src, lens, beam, loop="cands")
     for t in range(steps):
         ls.step(logit_tol=BF16_TOL if bf16 else F32_TOL)
