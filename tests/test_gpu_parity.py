@@ -686,6 +686,8 @@ _CAND_CASES = {
     # bf16, 64-wide heads, enc-dec weights shared (Tab. 4 "shared V: no"): the matrix-core attention emits the
     # block's weights for the follower inside the loop; beam 8
     "bf16_share_s_beam8": dict(dtype="bf16", batch=6, beam=8, d=256, V=2004, src_len=(1, 70), share="S"),
+    # beam 12 is wider than the epilogue's candidate lists: the loop falls back to stored logits by itself
+    "f32_beam12_stored_logits": dict(batch=3, beam=12, V=2004),
 }
 
 
